@@ -1,0 +1,211 @@
+/*
+ * tfm.h - C boundary of the MI355X (gfx950) mixed-precision Transformer training step.
+ *
+ * The library implements one path of the paper (fairseq, arXiv 1904.01038): the single-GPU training step of a
+ * Transformer encoder-decoder or decoder-only language model (Applications: machine translation; language
+ * modeling) with
+ *   - loss = criterion(model, batch)                     (Design, Criterions)
+ *   - half-precision forward/backward, full-precision parameter update, dynamic loss scaling: the loss is scaled
+ *     right after the forward pass, the gradients are unscaled before the update
+ *                                                         (Implementation, Mixed precision)
+ *   - gradients accumulated over several sub-batches before one update ("delayed updates")
+ *                                                         (Implementation, Multi-GPU training)
+ *   - an optimiser that updates the parameters from the gradients (Design, Optimizers); here Adam.
+ *
+ * General rules
+ *   - Every function returns 0 on success and a negative TFM_E* code on failure.  Nothing throws, aborts or
+ *     prints.  tfm_last_error() gives a human-readable message for the last failure on a context.
+ *   - "host" pointers are ordinary CPU memory owned by the caller and may be reused as soon as the call returns.
+ *     "device" pointers are HIP device memory owned by the caller.  The library allocates no device memory:
+ *     parameters, optimiser state, gradients and activations all live in the caller's workspace.
+ *   - One context = one HIP stream = one caller thread at a time.  Work is enqueued on the context's stream;
+ *     calls that return results to the host (an `out` struct, tfm_get_*) synchronise that stream.
+ *   - Inputs are validated on the host before anything is enqueued: a call that fails with TFM_EINVAL leaves
+ *     parameters, gradients and scaler state untouched.
+ *   - Same context state + same inputs => bit-identical results (no floating-point atomics anywhere).
+ */
+#ifndef TFM_H
+#define TFM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TFM_OK        0
+#define TFM_EINVAL   -1   /* bad config / shape / token id outside [0, vocab) / length out of range / over capacity */
+#define TFM_ENOMEM   -2   /* workspace too small */
+#define TFM_EHIP     -3   /* a HIP runtime call failed (message holds the HIP error string) */
+#define TFM_ESTATE   -4   /* call not allowed in this state, e.g. tfm_apply_update with no accumulated sub-batch */
+#define TFM_ESCALE   -5   /* the loss scale fell below min_loss_scale */
+
+#define TFM_FP32 0
+#define TFM_FP16 1
+#define TFM_BF16 2
+
+typedef struct tfm_ctx tfm_ctx;   /* opaque; created by tfm_create, released by tfm_destroy */
+
+typedef struct {
+  int32_t enc_layers;       /* 0 = decoder-only language model (src must then be NULL)                      */
+  int32_t dec_layers;       /* >= 1                                                                          */
+  int32_t d_model;          /* model width d; multiple of 8                                                  */
+  int32_t n_heads;          /* d_model % n_heads == 0; head width d_h = d_model / n_heads <= 128             */
+  int32_t d_ffn;            /* feed-forward inner width F; multiple of 8                                     */
+  int32_t vocab;            /* V; one shared embedding table, output projection tied to it, no output bias   */
+  int32_t pad_id, eos_id;   /* padding id (ignored everywhere) and end-of-sentence id                        */
+  int32_t max_sentences;    /* capacity: sentences per sub-batch                                             */
+  int32_t max_len;          /* capacity: longest source or target sentence                                   */
+  int32_t max_tokens;       /* capacity: non-pad tokens per sub-batch on either side                         */
+  int32_t precision;        /* TFM_FP32 | TFM_FP16 (dynamic loss scaling) | TFM_BF16 (scale fixed at its initial value) */
+  int32_t pre_norm;         /* 0: LayerNorm after each residual sum; 1: before each sub-layer + a final one  */
+  float   dropout;          /* on embeddings and on each sub-layer output before the residual sum; [0, 1)    */
+  float   label_smoothing;  /* eps in q = (1-eps) onehot + eps/V                                             */
+  float   adam_beta1, adam_beta2, adam_eps;
+  float   clip_norm;        /* 0 = off; else the unscaled gradient is scaled down to this L2 norm            */
+  float   init_loss_scale;  /* a power of two; use 1 for fp32/bf16                                           */
+  int32_t scale_window;     /* clean updates after which the scale doubles                                   */
+  float   min_loss_scale;   /* tfm_apply_update reports TFM_ESCALE below this                                */
+  uint64_t seed;            /* dropout seed; parameters are set by the caller                                */
+} tfm_config;
+
+typedef struct {
+  double  loss_sum;         /* sum over non-pad target tokens of the label-smoothed loss, nats, NOT scaled   */
+  double  nll_sum;          /* same for the plain negative log-likelihood                                    */
+  int64_t ntokens;          /* non-pad target tokens of this sub-batch                                       */
+  int32_t overflow;         /* 1 if this sub-batch produced a non-finite gradient value                      */
+  float   loss_scale;       /* scale that was applied                                                        */
+} tfm_step_out;
+
+typedef struct {
+  int32_t skipped;          /* 1: overflow in the window, nothing was updated                                */
+  float   loss_scale_after;
+  int32_t clean_steps;      /* clean updates since the last overflow or growth                               */
+  int64_t num_updates;      /* optimiser steps taken so far                                                  */
+  float   grad_norm;        /* L2 norm of the unscaled, token-normalised gradient (NaN when skipped)         */
+  int64_t ntokens_total;    /* target tokens in the window                                                   */
+} tfm_update_out;
+
+/* Bytes of device workspace tfm_create needs for this configuration. */
+int tfm_workspace_bytes(const tfm_config* cfg, size_t* bytes);
+
+/* Create a context.  dev_workspace: device memory, 256-byte aligned, at least tfm_workspace_bytes() long, owned
+ * by the caller and kept alive until tfm_destroy; its contents are initialised here (parameters and optimiser
+ * state zero).  hip_stream: a hipStream_t (NULL = the default stream). */
+int tfm_create(const tfm_config* cfg, void* dev_workspace, size_t bytes, void* hip_stream, tfm_ctx** out);
+void tfm_destroy(tfm_ctx* ctx);                      /* does not free the workspace */
+const char* tfm_last_error(const tfm_ctx* ctx);      /* ctx may be NULL: message of the last failed tfm_create */
+
+/* Parameters: canonical order and names; matrices are row-major W[out, in] (y = x W^T + b). */
+int tfm_num_params(const tfm_ctx* ctx, int32_t* n);
+int tfm_param_info(const tfm_ctx* ctx, int32_t i, char name[64], int64_t shape[2]);   /* shape[1] = 0 for vectors */
+int tfm_set_param(tfm_ctx* ctx, int32_t i, const float* host, int64_t n);  /* sets the fp32 master and the half copy */
+int tfm_get_param(tfm_ctx* ctx, int32_t i, float* host, int64_t n);        /* fp32 master                             */
+/* Accumulated gradient of the current window as fp32, still multiplied by the loss scale, not token-normalised. */
+int tfm_get_grad(tfm_ctx* ctx, int32_t i, float* host, int64_t n);
+/* Adam moments (which = 0: first, 1: second). */
+int tfm_get_adam(tfm_ctx* ctx, int32_t i, int32_t which, float* host, int64_t n);
+int tfm_set_adam(tfm_ctx* ctx, int32_t i, int32_t which, const float* host, int64_t n);
+int tfm_get_scaler(tfm_ctx* ctx, float* loss_scale, int32_t* clean_steps, int64_t* num_updates);
+int tfm_set_scaler(tfm_ctx* ctx, float loss_scale, int32_t clean_steps, int64_t num_updates);
+
+/* One sub-batch: forward, loss (scaled right after the forward pass), backward; gradients are added to the
+ * window's accumulator (Implementation, Mixed precision; Multi-GPU training).
+ *   src, tgt        host, int32, row-major [B, Ls] and [B, Lt], right-padded with pad_id.  src = NULL (and
+ *                   src_lens = NULL, Ls = 0) for the decoder-only model.
+ *   src_lens,tgt_lens host, int32 [B], 1 <= len <= L*.  Positions beyond len are ignored.
+ *   The decoder is fed eos followed by the target without its last token (teacher forcing); the loss runs over
+ *   all tgt_lens[b] target tokens.
+ *   out             host, may be NULL: then nothing is copied back and the call does not synchronise. */
+int tfm_train_step(tfm_ctx* ctx, const int32_t* src, const int32_t* tgt, const int32_t* src_lens,
+                   const int32_t* tgt_lens, int32_t B, int32_t Ls, int32_t Lt, tfm_step_out* out);
+
+/* End of the window: inf/nan scan; on overflow skip, halve the scale; else unscale, normalise by the window's
+ * target tokens, optional clipping, Adam step in fp32 on the master weights, refresh the half copy; the scale
+ * doubles after scale_window clean updates.  Clears the accumulator.  out may be NULL (no synchronisation; a
+ * too-small scale is then reported by the next call that synchronises). */
+int tfm_apply_update(tfm_ctx* ctx, float lr, tfm_update_out* out);
+
+/* Test hook: the NEXT tfm_train_step multiplies its loss scale by mult (forces an overflow with 1e6 or inf). */
+int tfm_debug_set_loss_multiplier(tfm_ctx* ctx, float mult);
+
+/* Profiling: when on, every kernel launch is bracketed by HIP events on the context's stream and its duration is
+ * added to its class.  tfm_profile_read synchronises and returns, per class, launches, total milliseconds and the
+ * algorithmic flops and bytes the launches were credited with.  Classes: see TFM_PROF_*. */
+#define TFM_PROF_GEMM      0
+#define TFM_PROF_ATTENTION 1
+#define TFM_PROF_NORM      2   /* residual + dropout + LayerNorm forward and backward, bias column sums */
+#define TFM_PROF_LOSS      3
+#define TFM_PROF_EMBED     4
+#define TFM_PROF_OPTIM     5   /* inf/nan scan, accumulation, Adam */
+#define TFM_PROF_CLASSES   6
+typedef struct { int64_t launches; double ms; double flops; double bytes; } tfm_prof_entry;
+int tfm_profile_enable(tfm_ctx* ctx, int32_t on);
+int tfm_profile_read(tfm_ctx* ctx, tfm_prof_entry out[TFM_PROF_CLASSES], int32_t reset);
+
+/* ---- single operations on caller-owned device buffers (used by the kernel-level parity tests) ---------------
+ * dtype: TFM_FP32 / TFM_FP16 / TFM_BF16 for every tensor argument unless stated.  stream: hipStream_t or NULL.  */
+
+/* C[M,N] = epilogue(op(A) op(B)).  form 0 "NT": A[M,K], B[N,K];  1 "NN": A[M,K], B[K,N];  2 "TN": A[K,M], B[K,N].
+ * lda/ldb/ldc are row strides in elements.  epilogue: + bias[N] (may be NULL), ReLU if relu != 0, multiply by
+ * (mask[m,n] > 0) if mask != NULL (row stride ldc), + residual[m,n] if residual != NULL (row stride ldc; may alias C). */
+int tfm_op_gemm(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K, const void* A, int32_t lda,
+                const void* B, int32_t ldb, void* C, int32_t ldc, const void* bias, int32_t relu,
+                const void* mask, const void* residual, void* stream);
+
+/* Multi-head attention over packed sentences.  q rows of sentence b are q_off[b]..q_off[b+1], keys/values
+ * k_off[b]..k_off[b+1] (device int32 [B+1]).  Head h uses columns h*dh..(h+1)*dh.  o = softmax(q k^T/sqrt(dh)
+ * [+ causal mask]) v; lse (device fp32 [H, q_off[B]]) receives the row log-sum-exp of the scaled scores. */
+int tfm_op_attention_fwd(int32_t dtype, const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v,
+                         int32_t ldv, void* o, int32_t ldo, float* lse, const int32_t* q_off, const int32_t* k_off,
+                         int32_t B, int32_t H, int32_t dh, int32_t max_lq, int32_t max_lk, int32_t total_q,
+                         int32_t causal, void* stream);
+int tfm_op_attention_bwd(int32_t dtype, const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v,
+                         int32_t ldv, const void* o, int32_t ldo, const void* d_o, int32_t lddo, const float* lse,
+                         void* dq, int32_t lddq, void* dk, int32_t lddk, void* dv, int32_t lddv,
+                         const int32_t* q_off, const int32_t* k_off, int32_t B, int32_t H, int32_t dh,
+                         int32_t max_lq, int32_t max_lk, int32_t total_q, int32_t total_k, int32_t causal,
+                         void* stream);
+
+/* s = x + dropout(y) (y may be NULL: s = x), n = gamma * (s - mean)/sqrt(var + 1e-5) + beta.  [rows, d], contiguous.
+ * s_out may be NULL.  mean, rstd: device fp32 [rows].  gamma/beta in `dtype`.  dropout: keep bits from (key, p). */
+int tfm_op_residual_layernorm_fwd(int32_t dtype, const void* x, const void* y, const void* gamma, const void* beta,
+                                  void* s_out, void* n_out, float* mean, float* rstd, int32_t rows, int32_t d,
+                                  uint64_t drop_key, float p, void* stream);
+/* ds = add + LayerNorm-backward(dn) (add may be NULL); ds_drop = dropout-backward(ds) if p > 0 (else untouched);
+ * dgamma/dbeta [d]; dbias [d] = column sums of dropout-backward(ds) (may be NULL).  scratch: device fp32, at least
+ * tfm_op_layernorm_bwd_scratch(rows, d) bytes. */
+size_t tfm_op_layernorm_bwd_scratch(int32_t rows, int32_t d);
+int tfm_op_layernorm_bwd(int32_t dtype, const void* dn, const void* add, const void* s, const float* mean,
+                         const float* rstd, const void* gamma, void* ds, void* ds_drop, void* dgamma, void* dbeta,
+                         void* dbias, int32_t rows, int32_t d, uint64_t drop_key, float p, void* scratch,
+                         void* stream);
+
+/* Fused log-softmax + label-smoothed cross-entropy, forward and backward, in place: z[rows, V] (row stride V) is
+ * overwritten with scale * (softmax(z) - q), q = (1-eps) onehot(label) + eps/V.  loss_rows / nll_rows: device
+ * fp32 [rows], unscaled, nats. */
+int tfm_op_loss(int32_t dtype, void* z, const int32_t* labels, float* loss_rows, float* nll_rows, int32_t rows,
+                int32_t V, float eps, float scale, void* stream);
+
+/* Adam on a flat fp32 range with gradient g (dtype gdtype) pre-multiplied by 1/inv_scale:
+ * gg = g * grad_mult; m = b1 m + (1-b1) gg; v = b2 v + (1-b2) gg^2; w -= lr * (m/bc1) / (sqrt(v/bc2) + eps);
+ * half copy (dtype hdtype, may be NULL) = w. */
+int tfm_op_adam(float* w, float* m, float* v, const void* g, int32_t gdtype, void* half_copy, int32_t hdtype,
+                int64_t n, float lr, float beta1, float beta2, float eps, float grad_mult, float bc1, float bc2,
+                void* stream);
+
+/* result[0] = 1.0f if any element of x[n] is non-finite else 0; result[1] = sum of squares (fp32 device [2]). */
+int tfm_op_scan(int32_t dtype, const void* x, int64_t n, float* result, void* scratch, void* stream);
+size_t tfm_op_scan_scratch(int64_t n);
+
+/* Dropout keep bits of (key, p) for elements [0, n): out[i] = 1 or 0 (device uint8). */
+int tfm_op_dropout_mask(uint64_t key, float p, uint8_t* out, int64_t n, void* stream);
+/* Host helper: the 64-bit key of a dropout site (stream 0 encoder / 1 decoder; layer -1 = embedding;
+ * sub 0 self-attention, 1 cross-attention, 2 feed-forward) at a training step. */
+uint64_t tfm_dropout_key(uint64_t seed, uint64_t step, int32_t stream, int32_t layer, int32_t sub);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

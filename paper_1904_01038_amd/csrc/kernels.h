@@ -1,0 +1,109 @@
+// Host-side launchers of the gfx950 kernels.  Every launcher only enqueues work on the given stream; none of them
+// allocates or synchronises.  `dt` is a tfm::DType; all tensor arguments of one call share it unless noted.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace tfm {
+
+// Device-resident state of one context: the loss scaler, the optimiser step counter and per-call results.  It is
+// read and written by kernels so that a training step needs no host round trip.
+struct DevState {
+  float loss_scale;          // S
+  int clean_steps;           // clean updates since the last overflow or growth
+  long long num_updates;     // optimiser steps taken
+  int window_overflow;       // OR of the sub-batch overflow flags of the current window
+  int scale_too_small;       // sticky: S fell below the configured minimum
+  // last tfm_train_step
+  double loss_sum, nll_sum;
+  int step_overflow;
+  float step_scale;
+  // last scan
+  float scan_flag;           // 1.0 if a non-finite value was seen
+  double scan_sumsq;         // sum of squares of the scanned buffer
+  // last tfm_apply_update
+  int skipped;
+  float grad_norm;
+  float grad_mult;           // 1/(S*N) * clip coefficient
+  float bc1, bc2;            // 1 - beta^t
+};
+
+struct GemmArgs {
+  int dt;
+  int form;                  // 0 NT, 1 NN, 2 TN
+  int M, N, K;
+  const void* A; int lda;
+  const void* B; int ldb;
+  void* C; int ldc;
+  const void* bias;          // [N] or null
+  int relu;
+  const void* mask;          // [M, N] stride ldc or null: multiply by (mask > 0)
+  const void* residual;      // [M, N] stride ldc or null: added last (may alias C)
+};
+void launch_gemm(hipStream_t s, const GemmArgs& a);
+bool gemm_mfma_supported(const GemmArgs& a);
+void launch_gemm_naive(hipStream_t s, const GemmArgs& a);
+
+struct AttnArgs {
+  int dt;
+  const void *q, *k, *v; int ldq, ldk, ldv;
+  void* o; int ldo;                      // forward: written; backward: read
+  float* lse;                            // [H, total_q]
+  const int *q_off, *k_off;              // device [B+1]
+  int B, H, dh, max_lq, max_lk, total_q, total_k, causal;
+  // backward only
+  const void* d_o; int lddo;
+  void *dq, *dk, *dv; int lddq, lddk, lddv;
+};
+void launch_attention_fwd(hipStream_t s, const AttnArgs& a);
+void launch_attention_bwd(hipStream_t s, const AttnArgs& a);
+void launch_attention_fwd_naive(hipStream_t s, const AttnArgs& a);
+void launch_attention_bwd_naive(hipStream_t s, const AttnArgs& a);
+
+void launch_residual_layernorm_fwd(hipStream_t s, int dt, const void* x, const void* y, const void* gamma,
+                                   const void* beta, void* s_out, void* n_out, float* mean, float* rstd, int rows,
+                                   int d, uint64_t key, float p);
+size_t layernorm_bwd_scratch_bytes(int rows, int d);
+void launch_layernorm_bwd(hipStream_t s, int dt, const void* dn, const void* add, const void* sres, const float* mean,
+                          const float* rstd, const void* gamma, void* ds, void* ds_drop, void* dgamma, void* dbeta,
+                          void* dbias, int rows, int d, uint64_t key, float p, void* scratch);
+size_t colsum_scratch_bytes(int rows, int n);
+void launch_colsum(hipStream_t s, int dt, const void* x, int ld, int rows, int n, void* out, void* scratch);
+
+// z[rows, V] in place; scale = (scale_ptr ? *scale_ptr : 1) * mult; if step_scale_out != null the applied scale is
+// stored there.
+void launch_loss(hipStream_t s, int dt, void* z, const int* labels, float* loss_rows, float* nll_rows, int rows, int V,
+                 float eps, const float* scale_ptr, float mult, float* step_scale_out);
+// sums[0] = sum loss_rows, sums[1] = sum nll_rows (double, single block, fixed order)
+void launch_sum_rows(hipStream_t s, const float* loss_rows, const float* nll_rows, int rows, double* sums);
+
+void launch_embed_fwd(hipStream_t s, int dt, const void* E, const int* ids, const int* pos, const float* pe, void* out,
+                      int rows, int d, uint64_t key, float p);
+// Adds sqrt(d) * dropout-backward(dx) of every occurrence of a token to its row of the embedding gradient.
+// uniq[u] = token id, start[u]..start[u+1] index `entries`; an entry is (stream << 30) | row.
+void launch_embed_bwd(hipStream_t s, int dt, void* gE, const int* uniq, const int* start, const int* entries, int n_uniq,
+                      const void* dx0, const void* dx1, int d, uint64_t key0, uint64_t key1, float p);
+
+size_t scan_scratch_bytes(int64_t n);
+// flag/sumsq of x[n] -> result[0], result[1] (fp32) and, if st != null, st->scan_flag / scan_sumsq and
+// st->step_overflow / window_overflow (|=).  If acc != null: acc = x (acc_mode 1) or acc += x (acc_mode 2), fp32.
+void launch_scan(hipStream_t s, int dt, const void* x, int64_t n, float* result, DevState* st, float* acc, int acc_mode,
+                 void* scratch);
+void launch_convert(hipStream_t s, int src_dt, const void* src, int dst_dt, void* dst, int64_t n);
+
+struct AdamArgs {
+  float *w, *m, *v; const void* g; int gdt; void* half_copy; int hdt; int64_t n;
+  float lr, beta1, beta2, eps;
+  const DevState* st;        // if non-null: skip flag, grad_mult, bc1, bc2 come from the device state
+  float grad_mult, bc1, bc2;
+};
+void launch_adam(hipStream_t s, const AdamArgs& a);
+// One-thread kernel: the loss-scale state machine and the Adam step scalars.
+void launch_scaler_update(hipStream_t s, DevState* st, long long ntokens, float clip_norm, float beta1, float beta2,
+                          int scale_window, float min_scale, int dynamic);
+void launch_dropout_mask(hipStream_t s, uint64_t key, float p, uint8_t* out, int64_t n);
+
+uint64_t dropout_site_key(uint64_t seed, uint64_t step, int stream, int layer, int sub);
+
+}  // namespace tfm

@@ -1,0 +1,282 @@
+// Residual + dropout + LayerNorm forward and backward, and column sums (bias gradients).  All HBM-bound: one
+// wavefront owns one row, each lane moves 8 contiguous elements per access (16 bytes in half precision), the row
+// stays in registers between the statistics and the normalisation, statistics are fp32.
+#include "common.h"
+#include "kernels.h"
+
+namespace tfm {
+
+constexpr int LN_VEC = 8;
+constexpr float LN_EPS = 1e-5f;
+
+// s = x + drop(y); n = gamma * (s - mean) * rstd + beta.  NCH = chunks of 8 elements per lane (d <= NCH * 512).
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void residual_layernorm_fwd_kernel(
+    const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ gamma, const T* __restrict__ beta,
+    T* __restrict__ s_out, T* __restrict__ n_out, float* __restrict__ mean, float* __restrict__ rstd, int rows, int d,
+    uint64_t key, uint32_t thr, float inv_keep) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const size_t base = (size_t)row * d;
+  float v[NCH][LN_VEC];
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (lane + 64 * c) * LN_VEC;
+    if (col < d) {
+      load_f<T, LN_VEC>(x + base + col, v[c]);
+      if (y) {
+        float t[LN_VEC];
+        load_f<T, LN_VEC>(y + base + col, t);
+        if (thr) drop_apply<LN_VEC>(t, key, base + col, thr, inv_keep);
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i) v[c][i] += t[i];
+      }
+      if (s_out) {
+        store_f<T, LN_VEC>(s_out + base + col, v[c]);
+        // the backward pass reads the stored (rounded) sum, so normalise exactly that
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i) v[c][i] = to_f<T>(from_f<T>(v[c][i]));
+      }
+#pragma unroll
+      for (int i = 0; i < LN_VEC; ++i) sum += v[c][i];
+    }
+  }
+  const float mu = wave_sum(sum) / (float)d;
+  float sq = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (lane + 64 * c) * LN_VEC;
+    if (col < d) {
+#pragma unroll
+      for (int i = 0; i < LN_VEC; ++i) { const float t = v[c][i] - mu; sq += t * t; }
+    }
+  }
+  const float rs = rsqrtf(wave_sum(sq) / (float)d + LN_EPS);
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (lane + 64 * c) * LN_VEC;
+    if (col < d) {
+      float g[LN_VEC], b[LN_VEC], o[LN_VEC];
+      load_f<T, LN_VEC>(gamma + col, g);
+      load_f<T, LN_VEC>(beta + col, b);
+#pragma unroll
+      for (int i = 0; i < LN_VEC; ++i) o[i] = g[i] * ((v[c][i] - mu) * rs) + b[i];
+      store_f<T, LN_VEC>(n_out + base + col, o);
+    }
+  }
+}
+
+template <typename T>
+static void ln_fwd_dispatch(hipStream_t s, const void* x, const void* y, const void* gamma, const void* beta, void* s_out,
+                            void* n_out, float* mean, float* rstd, int rows, int d, uint64_t key, float p) {
+  const uint32_t thr = (p > 0.f && y) ? drop_threshold(p) : 0u;
+  const float inv_keep = 1.f / (1.f - p);
+  dim3 grid((rows + 3) / 4), block(256);
+  const int nch = (d + 511) / 512;
+#define LN_FWD(N)                                                                                                        \
+  hipLaunchKernelGGL((residual_layernorm_fwd_kernel<T, N>), grid, block, 0, s, (const T*)x, (const T*)y, (const T*)gamma, \
+                     (const T*)beta, (T*)s_out, (T*)n_out, mean, rstd, rows, d, key, thr, inv_keep)
+  if (nch <= 1) LN_FWD(1); else if (nch == 2) LN_FWD(2); else if (nch == 3) LN_FWD(3); else LN_FWD(4);
+#undef LN_FWD
+}
+
+void launch_residual_layernorm_fwd(hipStream_t s, int dt, const void* x, const void* y, const void* gamma,
+                                   const void* beta, void* s_out, void* n_out, float* mean, float* rstd, int rows,
+                                   int d, uint64_t key, float p) {
+  if (rows <= 0) return;
+  if (dt == F32) ln_fwd_dispatch<float>(s, x, y, gamma, beta, s_out, n_out, mean, rstd, rows, d, key, p);
+  else if (dt == F16) ln_fwd_dispatch<half_t>(s, x, y, gamma, beta, s_out, n_out, mean, rstd, rows, d, key, p);
+  else ln_fwd_dispatch<bf16_t>(s, x, y, gamma, beta, s_out, n_out, mean, rstd, rows, d, key, p);
+}
+
+// ---- backward -----------------------------------------------------------------------------------------------------------
+// Per row: xhat = (s - mean) rstd; dxhat = dn * gamma; ds = rstd (dxhat - mean(dxhat) - xhat mean(dxhat xhat)) + add.
+// Column partial sums (dgamma = sum dn xhat, dbeta = sum dn, dbias = sum dropout-backward(ds)) are kept in registers
+// while a wavefront walks its rows, combined across the block's 4 wavefronts in LDS, and written once per block to
+// partial[block][3][d]; a second kernel adds the partials in a fixed order.
+constexpr int LNB_MAX_BLOCKS = 512;
+
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void layernorm_bwd_kernel(
+    const T* __restrict__ dn, const T* __restrict__ add, const T* __restrict__ sres, const float* __restrict__ mean,
+    const float* __restrict__ rstd, const T* __restrict__ gamma, T* __restrict__ ds, T* __restrict__ ds_drop,
+    float* __restrict__ partial, int rows, int d, uint64_t key, uint32_t thr, float inv_keep) {
+  extern __shared__ float lds[];     // [3][4][d]
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  float g[NCH][LN_VEC], ag[NCH][LN_VEC], ab[NCH][LN_VEC], ac[NCH][LN_VEC];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (lane + 64 * c) * LN_VEC;
+    if (col < d) load_f<T, LN_VEC>(gamma + col, g[c]);
+#pragma unroll
+    for (int i = 0; i < LN_VEC; ++i) ag[c][i] = ab[c][i] = ac[c][i] = 0.f;
+  }
+  for (int row = blockIdx.x * 4 + w; row < rows; row += gridDim.x * 4) {
+    const size_t base = (size_t)row * d;
+    const float mu = mean[row], rs = rstd[row];
+    float xh[NCH][LN_VEC], dxh[NCH][LN_VEC];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int col = (lane + 64 * c) * LN_VEC;
+      if (col < d) {
+        float a[LN_VEC], b[LN_VEC];
+        load_f<T, LN_VEC>(dn + base + col, a);
+        load_f<T, LN_VEC>(sres + base + col, b);
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i) {
+          xh[c][i] = (b[i] - mu) * rs;
+          dxh[c][i] = a[i] * g[c][i];
+          s1 += dxh[c][i];
+          s2 += dxh[c][i] * xh[c][i];
+          ag[c][i] += a[i] * xh[c][i];
+          ab[c][i] += a[i];
+        }
+      }
+    }
+    const float c1 = wave_sum(s1) / (float)d, c2 = wave_sum(s2) / (float)d;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int col = (lane + 64 * c) * LN_VEC;
+      if (col < d) {
+        float o[LN_VEC];
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i) o[i] = rs * (dxh[c][i] - c1 - xh[c][i] * c2);
+        if (add) {
+          float t[LN_VEC];
+          load_f<T, LN_VEC>(add + base + col, t);
+#pragma unroll
+          for (int i = 0; i < LN_VEC; ++i) o[i] += t[i];
+        }
+        store_f<T, LN_VEC>(ds + base + col, o);
+        if (thr) {
+          drop_apply<LN_VEC>(o, key, base + col, thr, inv_keep);
+          store_f<T, LN_VEC>(ds_drop + base + col, o);
+        }
+        // the consumers read the rounded value; sum exactly what they will see
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i) ac[c][i] += to_f<T>(from_f<T>(o[i]));
+      }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (lane + 64 * c) * LN_VEC;
+    if (col < d) {
+#pragma unroll
+      for (int i = 0; i < LN_VEC; ++i) {
+        lds[(0 * 4 + w) * d + col + i] = ag[c][i];
+        lds[(1 * 4 + w) * d + col + i] = ab[c][i];
+        lds[(2 * 4 + w) * d + col + i] = ac[c][i];
+      }
+    }
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < 3 * d; j += 256) {
+    const int k = j / d, col = j - k * d;
+    const float t = (lds[(k * 4 + 0) * d + col] + lds[(k * 4 + 1) * d + col]) + (lds[(k * 4 + 2) * d + col] + lds[(k * 4 + 3) * d + col]);
+    partial[((size_t)blockIdx.x * 3 + k) * d + col] = t;
+  }
+}
+
+// out_k[j] = sum_p partial[p][k][j], p in a fixed order; k < nk <= 3.
+template <typename T>
+__global__ void reduce_partials_kernel(const float* __restrict__ partial, int np, int nk, int n, T* o0, T* o1, T* o2) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  for (int k = 0; k < nk; ++k) {
+    T* o = k == 0 ? o0 : (k == 1 ? o1 : o2);
+    if (!o) continue;
+    float acc = 0.f;
+    for (int p = 0; p < np; ++p) acc += partial[((size_t)p * nk + k) * n + j];
+    o[j] = from_f<T>(acc);
+  }
+}
+
+static int lnb_blocks(int rows) {
+  int b = (rows + 3) / 4;
+  return b > LNB_MAX_BLOCKS ? LNB_MAX_BLOCKS : (b < 1 ? 1 : b);
+}
+size_t layernorm_bwd_scratch_bytes(int rows, int d) { return (size_t)lnb_blocks(rows) * 3 * d * sizeof(float); }
+
+template <typename T>
+static void ln_bwd_dispatch(hipStream_t s, const void* dn, const void* add, const void* sres, const float* mean,
+                            const float* rstd, const void* gamma, void* ds, void* ds_drop, void* dgamma, void* dbeta,
+                            void* dbias, int rows, int d, uint64_t key, float p, void* scratch) {
+  const uint32_t thr = (p > 0.f && ds_drop) ? drop_threshold(p) : 0u;
+  const float inv_keep = 1.f / (1.f - p);
+  const int nb = lnb_blocks(rows);
+  const size_t shm = (size_t)12 * d * sizeof(float);
+  const int nch = (d + 511) / 512;
+#define LN_BWD(N)                                                                                                       \
+  hipLaunchKernelGGL((layernorm_bwd_kernel<T, N>), dim3(nb), dim3(256), shm, s, (const T*)dn, (const T*)add,             \
+                     (const T*)sres, mean, rstd, (const T*)gamma, (T*)ds, (T*)ds_drop, (float*)scratch, rows, d, key, thr, \
+                     inv_keep)
+  if (nch <= 1) LN_BWD(1); else if (nch == 2) LN_BWD(2); else if (nch == 3) LN_BWD(3); else LN_BWD(4);
+#undef LN_BWD
+  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((d + 255) / 256), dim3(256), 0, s, (const float*)scratch, nb, 3, d,
+                     (T*)dgamma, (T*)dbeta, (T*)dbias);
+}
+
+void launch_layernorm_bwd(hipStream_t s, int dt, const void* dn, const void* add, const void* sres, const float* mean,
+                          const float* rstd, const void* gamma, void* ds, void* ds_drop, void* dgamma, void* dbeta,
+                          void* dbias, int rows, int d, uint64_t key, float p, void* scratch) {
+  if (dt == F32) ln_bwd_dispatch<float>(s, dn, add, sres, mean, rstd, gamma, ds, ds_drop, dgamma, dbeta, dbias, rows, d, key, p, scratch);
+  else if (dt == F16) ln_bwd_dispatch<half_t>(s, dn, add, sres, mean, rstd, gamma, ds, ds_drop, dgamma, dbeta, dbias, rows, d, key, p, scratch);
+  else ln_bwd_dispatch<bf16_t>(s, dn, add, sres, mean, rstd, gamma, ds, ds_drop, dgamma, dbeta, dbias, rows, d, key, p, scratch);
+}
+
+// ---- column sums --------------------------------------------------------------------------------------------------------
+// out[j] = sum_r x[r, j].  Block = 64 column chunks (8 columns each) x 4 row lanes; grid.y row slabs write partials.
+constexpr int CS_ROWS_PER_BLOCK = 64;
+
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, int ld, int rows, int n, float* __restrict__ partial) {
+  __shared__ float lds[4][64 * LN_VEC];
+  const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+  const int col = (blockIdx.x * 64 + cx) * LN_VEC;
+  float acc[LN_VEC];
+#pragma unroll
+  for (int i = 0; i < LN_VEC; ++i) acc[i] = 0.f;
+  const int r0 = blockIdx.y * CS_ROWS_PER_BLOCK;
+  const int r1 = min(rows, r0 + CS_ROWS_PER_BLOCK);
+  if (col < n) {
+    for (int r = r0 + ry; r < r1; r += 4) {
+      float t[LN_VEC];
+      load_f<T, LN_VEC>(x + (size_t)r * ld + col, t);
+#pragma unroll
+      for (int i = 0; i < LN_VEC; ++i) acc[i] += t[i];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < LN_VEC; ++i) lds[ry][cx * LN_VEC + i] = acc[i];
+  __syncthreads();
+  for (int j = threadIdx.x; j < 64 * LN_VEC; j += 256) {
+    const int c = blockIdx.x * 64 * LN_VEC + j;
+    if (c < n) partial[(size_t)blockIdx.y * n + c] = (lds[0][j] + lds[1][j]) + (lds[2][j] + lds[3][j]);
+  }
+}
+
+size_t colsum_scratch_bytes(int rows, int n) {
+  return (size_t)((rows + CS_ROWS_PER_BLOCK - 1) / CS_ROWS_PER_BLOCK + 1) * n * sizeof(float);
+}
+
+template <typename T>
+static void colsum_dispatch(hipStream_t s, const void* x, int ld, int rows, int n, void* out, void* scratch) {
+  const int ny = (rows + CS_ROWS_PER_BLOCK - 1) / CS_ROWS_PER_BLOCK;
+  dim3 grid((n + 64 * LN_VEC - 1) / (64 * LN_VEC), ny);
+  hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, s, (const T*)x, ld, rows, n, (float*)scratch);
+  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((n + 255) / 256), dim3(256), 0, s, (const float*)scratch, ny, 1, n,
+                     (T*)out, (T*)nullptr, (T*)nullptr);
+}
+
+void launch_colsum(hipStream_t s, int dt, const void* x, int ld, int rows, int n, void* out, void* scratch) {
+  if (dt == F32) colsum_dispatch<float>(s, x, ld, rows, n, out, scratch);
+  else if (dt == F16) colsum_dispatch<half_t>(s, x, ld, rows, n, out, scratch);
+  else colsum_dispatch<bf16_t>(s, x, ld, rows, n, out, scratch);
+}
+
+}  // namespace tfm

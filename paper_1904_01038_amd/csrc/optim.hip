@@ -1,0 +1,204 @@
+// Inf/nan scan (+ optional accumulation into the fp32 window buffer), the loss-scale state machine, and the fp32
+// master-weight Adam update.  All HBM-bound streaming kernels with 16-byte accesses; reductions use per-block
+// partials added in a fixed order (no floating-point atomics), so every result is reproducible.
+#include "common.h"
+#include "kernels.h"
+
+namespace tfm {
+
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_VEC = 8;
+constexpr int SCAN_MAX_BLOCKS = 2048;
+
+static int scan_blocks(int64_t n) {
+  int64_t b = (n + (int64_t)SCAN_THREADS * SCAN_VEC - 1) / ((int64_t)SCAN_THREADS * SCAN_VEC);
+  if (b > SCAN_MAX_BLOCKS) b = SCAN_MAX_BLOCKS;
+  return b < 1 ? 1 : (int)b;
+}
+size_t scan_scratch_bytes(int64_t n) { return (size_t)scan_blocks(n) * 2 * sizeof(float); }
+
+// ACC: 0 none, 1 acc = x, 2 acc += x.  n must be a multiple of SCAN_VEC (buffers are padded by the caller).
+template <typename T, int ACC>
+__global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(const T* __restrict__ x, int64_t n, float* __restrict__ acc,
+                                                            float* __restrict__ partial) {
+  __shared__ float sh[16];
+  float bad = 0.f, sq = 0.f;
+  const int64_t stride = (int64_t)gridDim.x * SCAN_THREADS * SCAN_VEC;
+  for (int64_t i = ((int64_t)blockIdx.x * SCAN_THREADS + threadIdx.x) * SCAN_VEC; i < n; i += stride) {
+    float v[SCAN_VEC];
+    load_f<T, SCAN_VEC>(x + i, v);
+#pragma unroll
+    for (int k = 0; k < SCAN_VEC; ++k) {
+      if (!(fabsf(v[k]) <= 3.402823466e38f)) bad = 1.f;
+      sq += v[k] * v[k];
+    }
+    if (ACC == 1) {
+      store_f<float, SCAN_VEC>(acc + i, v);
+    } else if (ACC == 2) {
+      float a[SCAN_VEC];
+      load_f<float, SCAN_VEC>(acc + i, a);
+#pragma unroll
+      for (int k = 0; k < SCAN_VEC; ++k) a[k] += v[k];
+      store_f<float, SCAN_VEC>(acc + i, a);
+    }
+  }
+  bad = block_max(bad, sh);
+  sq = block_sum(sq, sh);
+  if (threadIdx.x == 0) { partial[2 * blockIdx.x] = bad; partial[2 * blockIdx.x + 1] = sq; }
+}
+
+__global__ __launch_bounds__(256) void scan_finish_kernel(const float* __restrict__ partial, int nb, float* __restrict__ result,
+                                                          DevState* __restrict__ st) {
+  __shared__ double shs[256];
+  __shared__ float shb[256];
+  double sq = 0.0;
+  float bad = 0.f;
+  for (int i = threadIdx.x; i < nb; i += 256) { bad = fmaxf(bad, partial[2 * i]); sq += (double)partial[2 * i + 1]; }
+  shs[threadIdx.x] = sq;
+  shb[threadIdx.x] = bad;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) { shs[threadIdx.x] += shs[threadIdx.x + o]; shb[threadIdx.x] = fmaxf(shb[threadIdx.x], shb[threadIdx.x + o]); }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    // a non-finite partial sum also means a non-finite (or overflowing) input
+    const float flag = (shb[0] > 0.f || !(fabs(shs[0]) <= 1.7e308)) ? 1.f : 0.f;
+    if (result) { result[0] = flag; result[1] = (float)shs[0]; }
+    if (st) {
+      st->scan_flag = flag;
+      st->scan_sumsq = shs[0];
+      st->step_overflow = flag > 0.f ? 1 : 0;
+      if (flag > 0.f) st->window_overflow = 1;
+    }
+  }
+}
+
+template <typename T>
+static void scan_dispatch(hipStream_t s, const void* x, int64_t n, float* result, DevState* st, float* acc, int acc_mode,
+                          void* scratch) {
+  const int nb = scan_blocks(n);
+  dim3 grid(nb), block(SCAN_THREADS);
+  if (acc_mode == 1) hipLaunchKernelGGL((scan_kernel<T, 1>), grid, block, 0, s, (const T*)x, n, acc, (float*)scratch);
+  else if (acc_mode == 2) hipLaunchKernelGGL((scan_kernel<T, 2>), grid, block, 0, s, (const T*)x, n, acc, (float*)scratch);
+  else hipLaunchKernelGGL((scan_kernel<T, 0>), grid, block, 0, s, (const T*)x, n, acc, (float*)scratch);
+  hipLaunchKernelGGL(scan_finish_kernel, dim3(1), dim3(256), 0, s, (const float*)scratch, nb, result, st);
+}
+
+void launch_scan(hipStream_t s, int dt, const void* x, int64_t n, float* result, DevState* st, float* acc, int acc_mode,
+                 void* scratch) {
+  if (dt == F32) scan_dispatch<float>(s, x, n, result, st, acc, acc_mode, scratch);
+  else if (dt == F16) scan_dispatch<half_t>(s, x, n, result, st, acc, acc_mode, scratch);
+  else scan_dispatch<bf16_t>(s, x, n, result, st, acc, acc_mode, scratch);
+}
+
+// ---- conversion ---------------------------------------------------------------------------------------------------------
+template <typename S, typename D>
+__global__ void convert_kernel(const S* __restrict__ src, D* __restrict__ dst, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = from_f<D>(to_f<S>(src[i]));
+}
+template <typename S>
+static void convert_from(hipStream_t s, const void* src, int dst_dt, void* dst, int64_t n) {
+  int64_t b = (n + 255) / 256;
+  if (b > 4096) b = 4096;
+  dim3 grid((unsigned)b), block(256);
+  if (dst_dt == F32) hipLaunchKernelGGL((convert_kernel<S, float>), grid, block, 0, s, (const S*)src, (float*)dst, n);
+  else if (dst_dt == F16) hipLaunchKernelGGL((convert_kernel<S, half_t>), grid, block, 0, s, (const S*)src, (half_t*)dst, n);
+  else hipLaunchKernelGGL((convert_kernel<S, bf16_t>), grid, block, 0, s, (const S*)src, (bf16_t*)dst, n);
+}
+void launch_convert(hipStream_t s, int src_dt, const void* src, int dst_dt, void* dst, int64_t n) {
+  if (n <= 0) return;
+  if (src_dt == F32) convert_from<float>(s, src, dst_dt, dst, n);
+  else if (src_dt == F16) convert_from<half_t>(s, src, dst_dt, dst, n);
+  else convert_from<bf16_t>(s, src, dst_dt, dst, n);
+}
+
+// ---- loss-scale state machine + Adam scalars (one thread) -----------------------------------------------------------------
+// Overflow anywhere in the window: skip, halve the scale, restart the clean counter.  Otherwise take an optimiser
+// step and double the scale after `scale_window` clean updates (Implementation, Mixed precision).
+__global__ void scaler_update_kernel(DevState* st, long long ntokens, float clip_norm, float beta1, float beta2,
+                                     int scale_window, float min_scale, int dynamic) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  if (st->window_overflow) {
+    st->skipped = 1;
+    st->grad_norm = __uint_as_float(0x7fc00000u);
+    st->grad_mult = 0.f;
+    if (dynamic) st->loss_scale *= 0.5f;
+    st->clean_steps = 0;
+  } else {
+    st->skipped = 0;
+    const double inv = 1.0 / ((double)st->loss_scale * (double)(ntokens > 0 ? ntokens : 1));
+    const double gnorm = sqrt(st->scan_sumsq) * inv;
+    double coef = 1.0;
+    if (clip_norm > 0.f && gnorm > (double)clip_norm) coef = (double)clip_norm / gnorm;
+    st->grad_norm = (float)gnorm;
+    st->grad_mult = (float)(inv * coef);
+    st->num_updates += 1;
+    const double t = (double)st->num_updates;
+    st->bc1 = (float)(1.0 - pow((double)beta1, t));
+    st->bc2 = (float)(1.0 - pow((double)beta2, t));
+    st->clean_steps += 1;
+    if (dynamic && st->clean_steps == scale_window) { st->loss_scale *= 2.f; st->clean_steps = 0; }
+  }
+  st->window_overflow = 0;
+  if (st->loss_scale < min_scale) st->scale_too_small = 1;
+}
+void launch_scaler_update(hipStream_t s, DevState* st, long long ntokens, float clip_norm, float beta1, float beta2,
+                          int scale_window, float min_scale, int dynamic) {
+  hipLaunchKernelGGL(scaler_update_kernel, dim3(1), dim3(64), 0, s, st, ntokens, clip_norm, beta1, beta2, scale_window, min_scale, dynamic);
+}
+
+// ---- Adam -------------------------------------------------------------------------------------------------------------------
+// Per parameter: read w, m, v (12 B) and the gradient (2 or 4 B), write w, m, v (12 B) and the half model copy (2 B).
+constexpr int ADAM_VEC = 4;
+template <typename GT, typename HT>
+__global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ w, float* __restrict__ m, float* __restrict__ v,
+                                                   const GT* __restrict__ g, HT* __restrict__ hcopy, int64_t n, float lr, float beta1,
+                                                   float beta2, float eps, const DevState* __restrict__ st, float grad_mult,
+                                                   float bc1, float bc2) {
+  if (st) {
+    if (st->skipped) return;
+    grad_mult = st->grad_mult; bc1 = st->bc1; bc2 = st->bc2;
+  }
+  const float step = lr / bc1, rbc2 = 1.f / bc2;
+  const int64_t stride = (int64_t)gridDim.x * 256 * ADAM_VEC;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * ADAM_VEC; i < n; i += stride) {
+    float wv[ADAM_VEC], mv[ADAM_VEC], vv[ADAM_VEC], gv[ADAM_VEC];
+    load_f<float, ADAM_VEC>(w + i, wv);
+    load_f<float, ADAM_VEC>(m + i, mv);
+    load_f<float, ADAM_VEC>(v + i, vv);
+    load_f<GT, ADAM_VEC>(g + i, gv);
+#pragma unroll
+    for (int k = 0; k < ADAM_VEC; ++k) {
+      const float gg = gv[k] * grad_mult;
+      mv[k] = beta1 * mv[k] + (1.f - beta1) * gg;
+      vv[k] = beta2 * vv[k] + (1.f - beta2) * gg * gg;
+      wv[k] -= step * mv[k] / (sqrtf(vv[k] * rbc2) + eps);
+    }
+    store_f<float, ADAM_VEC>(w + i, wv);
+    store_f<float, ADAM_VEC>(m + i, mv);
+    store_f<float, ADAM_VEC>(v + i, vv);
+    if (hcopy) store_f<HT, ADAM_VEC>(hcopy + i, wv);
+  }
+}
+
+template <typename GT>
+static void adam_dispatch(hipStream_t s, const AdamArgs& a) {
+  int64_t b = (a.n + 256 * ADAM_VEC - 1) / (256 * ADAM_VEC);
+  if (b > 8192) b = 8192;
+  dim3 grid((unsigned)(b < 1 ? 1 : b)), block(256);
+#define ADAM(HT)                                                                                                       \
+  hipLaunchKernelGGL((adam_kernel<GT, HT>), grid, block, 0, s, a.w, a.m, a.v, (const GT*)a.g, (HT*)a.half_copy, a.n, a.lr, \
+                     a.beta1, a.beta2, a.eps, a.st, a.grad_mult, a.bc1, a.bc2)
+  if (a.hdt == F16) ADAM(half_t); else if (a.hdt == BF16) ADAM(bf16_t); else ADAM(float);
+#undef ADAM
+}
+void launch_adam(hipStream_t s, const AdamArgs& a) {
+  if (a.n <= 0) return;
+  if (a.gdt == F32) adam_dispatch<float>(s, a);
+  else if (a.gdt == F16) adam_dispatch<half_t>(s, a);
+  else adam_dispatch<bf16_t>(s, a);
+}
+
+}  // namespace tfm

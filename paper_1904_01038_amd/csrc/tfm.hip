@@ -1,0 +1,978 @@
+// C boundary and step scheduler of the training step: configuration checks, carving of the caller's workspace,
+// host-side ingest (packing the padded batch into an un-padded token stream), and the static forward/backward/
+// update kernel schedule.  No device memory is allocated here; one small pinned host buffer stages the token ids.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/tfm.h"
+#include "kernels.h"
+#include "common.h"
+
+using namespace tfm;
+
+namespace {
+
+thread_local char g_create_error[256] = "";
+
+struct Param {
+  std::string name;
+  int64_t rows, cols;      // cols = 0 for vectors
+  int64_t off;             // element offset in the flat buffers
+  int64_t numel() const { return cols ? rows * cols : rows; }
+};
+
+enum Kind { SELF = 0, CROSS = 1, FFN = 2 };
+
+struct Block {
+  Kind kind;
+  int layer;
+  int w_a, b_a;            // wqkv | wq | w1
+  int w_kv, b_kv;          // cross-attention only
+  int w_o, b_o;            // wo | w2
+  int ln_g, ln_b;
+  void* inter;             // qkv [R,3d] | q [R,d] | h [R,F]
+  void* kv;                // cross: [R,2d] over source rows
+  void* ctx;               // attention output [R,d]
+  float* lse;              // [H,R]
+};
+
+struct Stream {
+  int id;                  // 0 encoder, 1 decoder
+  std::vector<Block> blocks;
+  std::vector<void*> resid, norm;          // K+1 each
+  std::vector<float*> mean, rstd;          // K+1 each
+  int lnf_g = -1, lnf_b = -1;
+  int *ids = nullptr, *pos = nullptr, *off = nullptr;   // device
+  int rows = 0, max_len = 0;               // current batch
+};
+
+struct Arena {
+  char* base;
+  size_t off = 0;
+  void* take(size_t bytes) {
+    off = (off + 255) & ~(size_t)255;
+    void* p = base ? base + off : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+constexpr int STAGE_SLOTS = 4;
+
+struct ProfRec { int cls; hipEvent_t a, b; double flops, bytes; };
+
+}  // namespace
+
+struct tfm_ctx {
+  tfm_config cfg;
+  hipStream_t stream;
+  char err[256];
+  int dt;                  // compute dtype
+  size_t esz;              // its size
+  std::vector<Param> params;
+  int64_t P;               // padded flat length
+  float *W, *M, *V, *G;    // fp32 master, Adam moments, window accumulator
+  void *Wh, *g;            // model copy and sub-batch gradient in compute dtype (Wh == W in fp32 mode)
+  DevState* st;
+  Stream enc, dec;
+  int R;                   // row capacity
+  // scratch
+  void *demb[2];           // gradient w.r.t. the embedding output of the encoder / decoder stream
+  void *y, *dcur, *dsA, *dsB, *dy, *dctx, *dinter, *dq, *dkv, *dmemA, *dmemB, *logits;
+  float *loss_rows, *nll_rows, *pe;
+  void *red_scratch, *scan_scratch;
+  int *labels, *uniq, *ustart, *uentries, *ibase;   // device ints (ibase = start of the int block)
+  size_t int_block_ints;
+  // host staging
+  int* stage[STAGE_SLOTS];
+  hipEvent_t stage_ev[STAGE_SLOTS];
+  bool stage_used[STAGE_SLOTS];
+  int stage_next;
+  std::vector<int> count;  // counting sort over the vocabulary
+  // window state (host mirror of what the host itself decides)
+  int window_mb;
+  long long window_tokens;
+  uint64_t train_steps;
+  float next_mult;
+  // profiling
+  bool prof;
+  std::vector<ProfRec> recs;
+  std::vector<hipEvent_t> ev_pool;
+  tfm_prof_entry prof_acc[TFM_PROF_CLASSES];
+};
+
+namespace {
+
+int fail(tfm_ctx* c, int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(c ? c->err : g_create_error, 256, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(c, expr)                                                                          \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess) return fail(c, TFM_EHIP, "%s: %s", #expr, hipGetErrorString(e_));        \
+  } while (0)
+
+int add_param(std::vector<Param>& ps, int64_t& off, const std::string& name, int64_t rows, int64_t cols) {
+  Param p{name, rows, cols, off};
+  off += (p.numel() + 255) / 256 * 256;
+  ps.push_back(p);
+  return (int)ps.size() - 1;
+}
+
+void build_params(const tfm_config& c, std::vector<Param>& ps, int64_t& P, Stream& enc, Stream& dec) {
+  const int d = c.d_model, F = c.d_ffn;
+  int64_t off = 0;
+  add_param(ps, off, "embed", c.vocab, d);
+  auto ln = [&](const std::string& pre, int& g, int& b) {
+    g = add_param(ps, off, pre + ".g", d, 0);
+    b = add_param(ps, off, pre + ".b", d, 0);
+  };
+  auto self_block = [&](const std::string& pre, int layer) {
+    Block b{};
+    b.kind = SELF; b.layer = layer; b.w_kv = b.b_kv = -1;
+    b.w_a = add_param(ps, off, pre + ".self.wqkv", 3 * d, d);
+    b.b_a = add_param(ps, off, pre + ".self.bqkv", 3 * d, 0);
+    b.w_o = add_param(ps, off, pre + ".self.wo", d, d);
+    b.b_o = add_param(ps, off, pre + ".self.bo", d, 0);
+    ln(pre + ".ln_self", b.ln_g, b.ln_b);
+    return b;
+  };
+  auto cross_block = [&](const std::string& pre, int layer) {
+    Block b{};
+    b.kind = CROSS; b.layer = layer;
+    b.w_a = add_param(ps, off, pre + ".cross.wq", d, d);
+    b.b_a = add_param(ps, off, pre + ".cross.bq", d, 0);
+    b.w_kv = add_param(ps, off, pre + ".cross.wkv", 2 * d, d);
+    b.b_kv = add_param(ps, off, pre + ".cross.bkv", 2 * d, 0);
+    b.w_o = add_param(ps, off, pre + ".cross.wo", d, d);
+    b.b_o = add_param(ps, off, pre + ".cross.bo", d, 0);
+    ln(pre + ".ln_cross", b.ln_g, b.ln_b);
+    return b;
+  };
+  auto ffn_block = [&](const std::string& pre, int layer) {
+    Block b{};
+    b.kind = FFN; b.layer = layer; b.w_kv = b.b_kv = -1;
+    b.w_a = add_param(ps, off, pre + ".ffn.w1", F, d);
+    b.b_a = add_param(ps, off, pre + ".ffn.b1", F, 0);
+    b.w_o = add_param(ps, off, pre + ".ffn.w2", d, F);
+    b.b_o = add_param(ps, off, pre + ".ffn.b2", d, 0);
+    ln(pre + ".ln_ffn", b.ln_g, b.ln_b);
+    return b;
+  };
+  enc.id = 0; dec.id = 1;
+  for (int i = 0; i < c.enc_layers; ++i) {
+    const std::string pre = "enc." + std::to_string(i);
+    enc.blocks.push_back(self_block(pre, i));
+    enc.blocks.push_back(ffn_block(pre, i));
+  }
+  if (c.enc_layers && c.pre_norm) ln("enc.ln_final", enc.lnf_g, enc.lnf_b);
+  for (int i = 0; i < c.dec_layers; ++i) {
+    const std::string pre = "dec." + std::to_string(i);
+    dec.blocks.push_back(self_block(pre, i));
+    if (c.enc_layers) dec.blocks.push_back(cross_block(pre, i));
+    dec.blocks.push_back(ffn_block(pre, i));
+  }
+  if (c.pre_norm) ln("dec.ln_final", dec.lnf_g, dec.lnf_b);
+  P = off;
+}
+
+int validate(const tfm_config& c, char* msg) {
+#define BAD(...) do { snprintf(msg, 256, __VA_ARGS__); return TFM_EINVAL; } while (0)
+  if (c.enc_layers < 0 || c.enc_layers > 64 || c.dec_layers < 1 || c.dec_layers > 64) BAD("layer counts out of range");
+  if (c.d_model < 8 || c.d_model > 1024 || c.d_model % 8) BAD("d_model must be a multiple of 8 in [8, 1024]");
+  if (c.n_heads < 1 || c.d_model % c.n_heads) BAD("d_model must be divisible by n_heads");
+  if (c.d_model / c.n_heads > 128) BAD("head width above 128");
+  if (c.d_ffn < 8 || c.d_ffn % 8) BAD("d_ffn must be a multiple of 8");
+  if (c.vocab < 4 || c.vocab > (1 << 24)) BAD("vocab out of range");
+  if (c.pad_id < 0 || c.pad_id >= c.vocab || c.eos_id < 0 || c.eos_id >= c.vocab) BAD("pad/eos id outside the vocabulary");
+  if (c.max_sentences < 1 || c.max_sentences > 65535) BAD("max_sentences out of range");
+  if (c.max_len < 1 || c.max_len > 4096) BAD("max_len out of range");
+  if (c.max_tokens < 1 || c.max_tokens > (1 << 20)) BAD("max_tokens out of range");
+  if ((int64_t)c.max_tokens * c.vocab > ((int64_t)1 << 33)) BAD("max_tokens * vocab too large");
+  if (c.precision < 0 || c.precision > 2) BAD("precision must be 0, 1 or 2");
+  if (c.pre_norm != 0 && c.pre_norm != 1) BAD("pre_norm must be 0 or 1");
+  if (!(c.dropout >= 0.f && c.dropout < 1.f)) BAD("dropout must be in [0, 1)");
+  if (!(c.label_smoothing >= 0.f && c.label_smoothing < 1.f)) BAD("label_smoothing must be in [0, 1)");
+  if (!(c.adam_beta1 >= 0.f && c.adam_beta1 < 1.f && c.adam_beta2 >= 0.f && c.adam_beta2 < 1.f && c.adam_eps > 0.f)) BAD("bad Adam constants");
+  if (!(c.clip_norm >= 0.f)) BAD("clip_norm must be >= 0");
+  if (!(c.init_loss_scale > 0.f) || !std::isfinite(c.init_loss_scale)) BAD("init_loss_scale must be positive");
+  if (c.scale_window < 1) BAD("scale_window must be >= 1");
+  if (!(c.min_loss_scale >= 0.f)) BAD("min_loss_scale must be >= 0");
+#undef BAD
+  return TFM_OK;
+}
+
+// Carves every buffer out of the workspace.  With ctx->... pointers null-based (base == nullptr) it only sizes.
+size_t carve(tfm_ctx* c, char* base) {
+  const tfm_config& cf = c->cfg;
+  const size_t R = (size_t)cf.max_tokens, d = cf.d_model, F = cf.d_ffn, H = cf.n_heads, esz = c->esz;
+  Arena a{base};
+  c->W = (float*)a.take(c->P * 4);
+  c->M = (float*)a.take(c->P * 4);
+  c->V = (float*)a.take(c->P * 4);
+  c->G = (float*)a.take(c->P * 4);
+  c->g = a.take(c->P * esz);
+  c->Wh = c->dt == F32 ? (void*)c->W : a.take(c->P * esz);
+  c->st = (DevState*)a.take(sizeof(DevState));
+  for (Stream* s : {&c->enc, &c->dec}) {
+    const size_t K = s->blocks.size();
+    if (K == 0) continue;
+    s->resid.assign(K + 1, nullptr); s->norm.assign(K + 1, nullptr);
+    s->mean.assign(K + 1, nullptr); s->rstd.assign(K + 1, nullptr);
+    for (size_t k = 0; k <= K; ++k) {
+      s->resid[k] = a.take(R * d * esz);
+      s->norm[k] = a.take(R * d * esz);
+      s->mean[k] = (float*)a.take(R * 4);
+      s->rstd[k] = (float*)a.take(R * 4);
+    }
+    for (Block& b : s->blocks) {
+      if (b.kind == SELF) { b.inter = a.take(R * 3 * d * esz); b.ctx = a.take(R * d * esz); b.lse = (float*)a.take(H * R * 4); }
+      else if (b.kind == CROSS) { b.inter = a.take(R * d * esz); b.kv = a.take(R * 2 * d * esz); b.ctx = a.take(R * d * esz); b.lse = (float*)a.take(H * R * 4); }
+      else { b.inter = a.take(R * F * esz); }
+    }
+  }
+  const size_t wide = std::max(3 * d, F);
+  c->y = a.take(R * d * esz);
+  c->dcur = a.take(R * d * esz);
+  c->demb[0] = a.take(R * d * esz);
+  c->demb[1] = a.take(R * d * esz);
+  c->dsA = a.take(R * d * esz);
+  c->dsB = a.take(R * d * esz);
+  c->dy = a.take(R * d * esz);
+  c->dctx = a.take(R * d * esz);
+  c->dinter = a.take(R * wide * esz);
+  c->dq = a.take(R * d * esz);
+  c->dkv = a.take(R * 2 * d * esz);
+  c->dmemA = a.take(R * d * esz);
+  c->dmemB = a.take(R * d * esz);
+  c->logits = a.take(R * (size_t)cf.vocab * esz);
+  c->loss_rows = (float*)a.take(R * 4);
+  c->nll_rows = (float*)a.take(R * 4);
+  c->pe = (float*)a.take((size_t)cf.max_len * d * 4);
+  const size_t red = std::max(layernorm_bwd_scratch_bytes((int)R, (int)d), colsum_scratch_bytes((int)R, (int)wide));
+  c->red_scratch = a.take(red);
+  c->scan_scratch = a.take(scan_scratch_bytes(c->P));
+  // one block of ints, filled by a single host-to-device copy per step:
+  // enc ids, pos [R each], off [B+1]; dec ids, pos, off; labels [R]; uniq [2R], ustart [2R+1], uentries [2R]
+  const size_t Bc = (size_t)cf.max_sentences + 1;
+  c->int_block_ints = 2 * (2 * R + Bc) + R + 2 * R + (2 * R + 1) + 2 * R;
+  c->ibase = (int*)a.take(c->int_block_ints * 4);
+  int* p = c->ibase;
+  auto nxt = [&](size_t n) { int* r = base ? p : nullptr; p += n; return r; };
+  c->enc.ids = nxt(R); c->enc.pos = nxt(R); c->enc.off = nxt(Bc);
+  c->dec.ids = nxt(R); c->dec.pos = nxt(R); c->dec.off = nxt(Bc);
+  c->labels = nxt(R);
+  c->uniq = nxt(2 * R); c->ustart = nxt(2 * R + 1); c->uentries = nxt(2 * R);
+  return (a.off + 255) & ~(size_t)255;
+}
+
+// ---- profiling wrapper -------------------------------------------------------------------------------------------------
+template <typename F>
+void run(tfm_ctx* c, int cls, double flops, double bytes, F&& launch) {
+  if (!c->prof) { launch(); return; }
+  auto get_ev = [&]() {
+    if (!c->ev_pool.empty()) { hipEvent_t e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
+    hipEvent_t e; hipEventCreate(&e); return e;
+  };
+  ProfRec r{cls, get_ev(), get_ev(), flops, bytes};
+  hipEventRecord(r.a, c->stream);
+  launch();
+  hipEventRecord(r.b, c->stream);
+  c->recs.push_back(r);
+}
+
+void prof_collect(tfm_ctx* c) {
+  for (ProfRec& r : c->recs) {
+    float ms = 0.f;
+    hipEventElapsedTime(&ms, r.a, r.b);
+    tfm_prof_entry& e = c->prof_acc[r.cls];
+    e.launches += 1; e.ms += ms; e.flops += r.flops; e.bytes += r.bytes;
+    c->ev_pool.push_back(r.a); c->ev_pool.push_back(r.b);
+  }
+  c->recs.clear();
+}
+
+// ---- small helpers over the flat parameter buffers ----------------------------------------------------------------------
+inline void* wh(tfm_ctx* c, int i) { return (char*)c->Wh + c->params[i].off * c->esz; }
+inline void* gr(tfm_ctx* c, int i) { return (char*)c->g + c->params[i].off * c->esz; }
+
+void gemm(tfm_ctx* c, int form, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C, int ldc,
+          const void* bias = nullptr, int relu = 0, const void* mask = nullptr, const void* residual = nullptr) {
+  if (M <= 0 || N <= 0) return;
+  GemmArgs a{c->dt, form, M, N, K, A, lda, B, ldb, C, ldc, bias, relu, mask, residual};
+  run(c, TFM_PROF_GEMM, 2.0 * M * N * K, 0.0, [&] { launch_gemm(c->stream, a); });
+}
+
+double attn_flops(const std::vector<int>& lq, const std::vector<int>& lk, int d, bool causal) {
+  double f = 0;
+  for (size_t b = 0; b < lq.size(); ++b) f += 4.0 * d * lq[b] * (double)lk[b] * (causal ? 0.5 : 1.0);
+  return f;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tfm_workspace_bytes(const tfm_config* cfg, size_t* bytes) {
+  if (!cfg || !bytes) return fail(nullptr, TFM_EINVAL, "null argument");
+  char msg[256];
+  int rc = validate(*cfg, msg);
+  if (rc) return fail(nullptr, rc, "%s", msg);
+  tfm_ctx tmp{};
+  tmp.cfg = *cfg;
+  tmp.dt = cfg->precision;
+  tmp.esz = dtype_size(tmp.dt);
+  build_params(*cfg, tmp.params, tmp.P, tmp.enc, tmp.dec);
+  *bytes = carve(&tmp, nullptr);
+  return TFM_OK;
+}
+
+int tfm_create(const tfm_config* cfg, void* ws, size_t bytes, void* hip_stream, tfm_ctx** out) {
+  if (!cfg || !ws || !out) return fail(nullptr, TFM_EINVAL, "null argument");
+  char msg[256];
+  int rc = validate(*cfg, msg);
+  if (rc) return fail(nullptr, rc, "%s", msg);
+  if (((uintptr_t)ws & 255) != 0) return fail(nullptr, TFM_EINVAL, "workspace must be 256-byte aligned");
+  tfm_ctx* c = new tfm_ctx{};
+  c->cfg = *cfg;
+  c->stream = (hipStream_t)hip_stream;
+  c->dt = cfg->precision;
+  c->esz = dtype_size(c->dt);
+  c->R = cfg->max_tokens;
+  build_params(*cfg, c->params, c->P, c->enc, c->dec);
+  const size_t need = carve(c, nullptr);
+  if (bytes < need) {
+    delete c;
+    return fail(nullptr, TFM_ENOMEM, "workspace has %zu bytes, %zu needed", bytes, need);
+  }
+  carve(c, (char*)ws);
+  c->count.assign(cfg->vocab, 0);
+  c->next_mult = 1.f;
+  auto cleanup = [&](int code) { tfm_destroy(c); return code; };
+  // zero parameters, moments, gradients and the accumulator (they are contiguous at the start of the workspace)
+  hipError_t e = hipMemsetAsync(ws, 0, (char*)c->st - (char*)ws + sizeof(DevState), c->stream);
+  if (e != hipSuccess) { fail(nullptr, TFM_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); return cleanup(TFM_EHIP); }
+  DevState init{};
+  init.loss_scale = cfg->init_loss_scale;
+  e = hipMemcpyAsync(c->st, &init, sizeof(init), hipMemcpyHostToDevice, c->stream);
+  if (e == hipSuccess) {
+    // sinusoidal position table in double, stored fp32: PE(t,2i) = sin(t / 10000^(2i/d)), PE(t,2i+1) = cos(same)
+    std::vector<float> pe((size_t)cfg->max_len * cfg->d_model);
+    for (int t = 0; t < cfg->max_len; ++t)
+      for (int i = 0; i < cfg->d_model / 2; ++i) {
+        const double ang = (double)t / std::pow(10000.0, 2.0 * i / cfg->d_model);
+        pe[(size_t)t * cfg->d_model + 2 * i] = (float)std::sin(ang);
+        pe[(size_t)t * cfg->d_model + 2 * i + 1] = (float)std::cos(ang);
+      }
+    e = hipMemcpyAsync(c->pe, pe.data(), pe.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  }
+  if (e != hipSuccess) { fail(nullptr, TFM_EHIP, "init copy: %s", hipGetErrorString(e)); return cleanup(TFM_EHIP); }
+  for (int i = 0; i < STAGE_SLOTS; ++i) {
+    e = hipHostMalloc((void**)&c->stage[i], c->int_block_ints * 4, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming);
+    if (e != hipSuccess) { fail(nullptr, TFM_EHIP, "staging buffers: %s", hipGetErrorString(e)); return cleanup(TFM_EHIP); }
+  }
+  *out = c;
+  return TFM_OK;
+}
+
+void tfm_destroy(tfm_ctx* c) {
+  if (!c) return;
+  hipStreamSynchronize(c->stream);
+  for (int i = 0; i < STAGE_SLOTS; ++i) {
+    if (c->stage[i]) hipHostFree(c->stage[i]);
+    if (c->stage_ev[i]) hipEventDestroy(c->stage_ev[i]);
+  }
+  for (ProfRec& r : c->recs) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+  for (hipEvent_t e : c->ev_pool) hipEventDestroy(e);
+  delete c;
+}
+
+const char* tfm_last_error(const tfm_ctx* c) { return c ? c->err : g_create_error; }
+
+int tfm_num_params(const tfm_ctx* c, int32_t* n) {
+  if (!c || !n) return TFM_EINVAL;
+  *n = (int32_t)c->params.size();
+  return TFM_OK;
+}
+
+int tfm_param_info(const tfm_ctx* c, int32_t i, char name[64], int64_t shape[2]) {
+  if (!c || i < 0 || i >= (int)c->params.size()) return TFM_EINVAL;
+  if (name) { std::strncpy(name, c->params[i].name.c_str(), 63); name[63] = 0; }
+  if (shape) { shape[0] = c->params[i].rows; shape[1] = c->params[i].cols; }
+  return TFM_OK;
+}
+
+static int check_param(tfm_ctx* c, int32_t i, const void* host, int64_t n) {
+  if (!c) return TFM_EINVAL;
+  if (i < 0 || i >= (int)c->params.size()) return fail(c, TFM_EINVAL, "parameter index %d out of range", i);
+  if (!host || n != c->params[i].numel()) return fail(c, TFM_EINVAL, "parameter %d has %lld elements, got %lld", i, (long long)c->params[i].numel(), (long long)n);
+  return TFM_OK;
+}
+
+int tfm_set_param(tfm_ctx* c, int32_t i, const float* host, int64_t n) {
+  int rc = check_param(c, i, host, n);
+  if (rc) return rc;
+  const Param& p = c->params[i];
+  HIP_TRY(c, hipMemcpyAsync(c->W + p.off, host, n * 4, hipMemcpyHostToDevice, c->stream));
+  if (c->dt != F32) launch_convert(c->stream, F32, c->W + p.off, c->dt, (char*)c->Wh + p.off * c->esz, n);
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return TFM_OK;
+}
+
+static int get_flat(tfm_ctx* c, int32_t i, const float* dev, float* host, int64_t n) {
+  int rc = check_param(c, i, host, n);
+  if (rc) return rc;
+  HIP_TRY(c, hipMemcpyAsync(host, dev + c->params[i].off, n * 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return TFM_OK;
+}
+
+int tfm_get_param(tfm_ctx* c, int32_t i, float* host, int64_t n) { return c ? get_flat(c, i, c->W, host, n) : TFM_EINVAL; }
+
+int tfm_get_grad(tfm_ctx* c, int32_t i, float* host, int64_t n) {
+  int rc = check_param(c, i, host, n);
+  if (rc) return rc;
+  if (c->window_mb == 0) { std::memset(host, 0, n * 4); return TFM_OK; }
+  if (c->window_mb >= 2) return get_flat(c, i, c->G, host, n);
+  // a single sub-batch so far: its gradient is still in the compute dtype; convert through the accumulator
+  const Param& p = c->params[i];
+  launch_convert(c->stream, c->dt, (char*)c->g + p.off * c->esz, F32, c->G + p.off, n);
+  return get_flat(c, i, c->G, host, n);
+}
+
+int tfm_get_adam(tfm_ctx* c, int32_t i, int32_t which, float* host, int64_t n) {
+  if (!c || which < 0 || which > 1) return TFM_EINVAL;
+  return get_flat(c, i, which ? c->V : c->M, host, n);
+}
+
+int tfm_set_adam(tfm_ctx* c, int32_t i, int32_t which, const float* host, int64_t n) {
+  if (!c || which < 0 || which > 1) return TFM_EINVAL;
+  int rc = check_param(c, i, host, n);
+  if (rc) return rc;
+  HIP_TRY(c, hipMemcpyAsync((which ? c->V : c->M) + c->params[i].off, host, n * 4, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return TFM_OK;
+}
+
+int tfm_get_scaler(tfm_ctx* c, float* loss_scale, int32_t* clean_steps, int64_t* num_updates) {
+  if (!c) return TFM_EINVAL;
+  DevState h;
+  HIP_TRY(c, hipMemcpyAsync(&h, c->st, sizeof(h), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (loss_scale) *loss_scale = h.loss_scale;
+  if (clean_steps) *clean_steps = h.clean_steps;
+  if (num_updates) *num_updates = h.num_updates;
+  return TFM_OK;
+}
+
+int tfm_set_scaler(tfm_ctx* c, float loss_scale, int32_t clean_steps, int64_t num_updates) {
+  if (!c) return TFM_EINVAL;
+  if (!(loss_scale > 0.f) || clean_steps < 0 || num_updates < 0) return fail(c, TFM_EINVAL, "bad scaler state");
+  DevState h;
+  HIP_TRY(c, hipMemcpyAsync(&h, c->st, sizeof(h), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  h.loss_scale = loss_scale; h.clean_steps = clean_steps; h.num_updates = num_updates;
+  HIP_TRY(c, hipMemcpyAsync(c->st, &h, sizeof(h), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return TFM_OK;
+}
+
+int tfm_debug_set_loss_multiplier(tfm_ctx* c, float mult) {
+  if (!c) return TFM_EINVAL;
+  c->next_mult = mult;
+  return TFM_OK;
+}
+
+int tfm_profile_enable(tfm_ctx* c, int32_t on) {
+  if (!c) return TFM_EINVAL;
+  c->prof = on != 0;
+  return TFM_OK;
+}
+
+int tfm_profile_read(tfm_ctx* c, tfm_prof_entry out[TFM_PROF_CLASSES], int32_t reset) {
+  if (!c || !out) return TFM_EINVAL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  prof_collect(c);
+  std::memcpy(out, c->prof_acc, sizeof(c->prof_acc));
+  if (reset) std::memset(c->prof_acc, 0, sizeof(c->prof_acc));
+  return TFM_OK;
+}
+
+}  // extern "C"
+
+// ---- the step ------------------------------------------------------------------------------------------------------------
+namespace {
+
+struct StepCtx {
+  tfm_ctx* c;
+  std::vector<int> slen, tlen;
+  int B, Ts, Tt;
+  uint64_t step;
+};
+
+uint64_t site_key(const StepCtx& s, int stream, int layer, int sub) {
+  return dropout_site_key(s.c->cfg.seed, s.step, stream, layer, sub);
+}
+uint64_t block_key(const StepCtx& s, const Stream& st, int k) {
+  const Block& b = st.blocks[k];
+  return site_key(s, st.id, b.layer, (int)b.kind);
+}
+
+void attention(const StepCtx& s, bool bwd, const Stream& qs, const Stream& ks, const std::vector<int>& lq,
+               const std::vector<int>& lk, const void* q, int ldq, const void* k, int ldk, const void* v, int ldv, void* o,
+               float* lse, bool causal, const void* d_o = nullptr, void* dq = nullptr, int lddq = 0, void* dk = nullptr,
+               int lddk = 0, void* dv = nullptr, int lddv = 0) {
+  tfm_ctx* c = s.c;
+  const int d = c->cfg.d_model, H = c->cfg.n_heads;
+  AttnArgs a{};
+  a.dt = c->dt; a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.o = o; a.ldo = d; a.lse = lse;
+  a.q_off = qs.off; a.k_off = ks.off; a.B = s.B; a.H = H; a.dh = d / H; a.max_lq = qs.max_len; a.max_lk = ks.max_len;
+  a.total_q = qs.rows; a.total_k = ks.rows; a.causal = causal ? 1 : 0;
+  a.d_o = d_o; a.lddo = d; a.dq = dq; a.dk = dk; a.dv = dv; a.lddq = lddq; a.lddk = lddk; a.lddv = lddv;
+  const double f = attn_flops(lq, lk, d, causal);
+  const double bytes = (double)c->esz * d * (bwd ? (4.0 * qs.rows + 4.0 * ks.rows) : (2.0 * qs.rows + 2.0 * ks.rows));
+  if (!bwd) run(c, TFM_PROF_ATTENTION, f, bytes, [&] { launch_attention_fwd(c->stream, a); });
+  else run(c, TFM_PROF_ATTENTION, 2.0 * f, bytes, [&] { launch_attention_bwd(c->stream, a); });
+}
+
+// y = f_k(fin): the sub-layer without its residual wrapper
+void sublayer_fwd(const StepCtx& s, Stream& st, int k, const void* fin, void* y) {
+  tfm_ctx* c = s.c;
+  Block& b = st.blocks[k];
+  const int d = c->cfg.d_model, F = c->cfg.d_ffn, T = st.rows;
+  const std::vector<int>& len = st.id ? s.tlen : s.slen;
+  if (b.kind == SELF) {
+    gemm(c, 0, T, 3 * d, d, fin, d, wh(c, b.w_a), d, b.inter, 3 * d, wh(c, b.b_a));
+    const char* qkv = (const char*)b.inter;
+    attention(s, false, st, st, len, len, qkv, 3 * d, qkv + d * c->esz, 3 * d, qkv + 2 * d * c->esz, 3 * d, b.ctx, b.lse, st.id == 1);
+    gemm(c, 0, T, d, d, b.ctx, d, wh(c, b.w_o), d, y, d, wh(c, b.b_o));
+  } else if (b.kind == CROSS) {
+    Stream& en = c->enc;
+    const void* mem = en.norm[en.blocks.size()];
+    gemm(c, 0, T, d, d, fin, d, wh(c, b.w_a), d, b.inter, d, wh(c, b.b_a));
+    gemm(c, 0, en.rows, 2 * d, d, mem, d, wh(c, b.w_kv), d, b.kv, 2 * d, wh(c, b.b_kv));
+    const char* kv = (const char*)b.kv;
+    attention(s, false, st, en, s.tlen, s.slen, b.inter, d, kv, 2 * d, kv + d * c->esz, 2 * d, b.ctx, b.lse, false);
+    gemm(c, 0, T, d, d, b.ctx, d, wh(c, b.w_o), d, y, d, wh(c, b.b_o));
+  } else {
+    gemm(c, 0, T, F, d, fin, d, wh(c, b.w_a), d, b.inter, F, wh(c, b.b_a), 1);
+    gemm(c, 0, T, d, F, b.inter, F, wh(c, b.w_o), F, y, d, wh(c, b.b_o));
+  }
+}
+
+void ln_fwd(tfm_ctx* c, const void* x, const void* y, int g, int b, void* s_out, void* n_out, float* mean, float* rstd,
+            int rows, uint64_t key) {
+  const int d = c->cfg.d_model;
+  const double bytes = (double)c->esz * rows * d * (1.0 + (y ? 1.0 : 0.0) + (s_out ? 1.0 : 0.0) + 1.0);
+  run(c, TFM_PROF_NORM, 0.0, bytes, [&] {
+    launch_residual_layernorm_fwd(c->stream, c->dt, x, y, wh(c, g), wh(c, b), s_out, n_out, mean, rstd, rows, d, key, c->cfg.dropout);
+  });
+}
+
+void stream_fwd(const StepCtx& s, Stream& st) {
+  tfm_ctx* c = s.c;
+  const int K = (int)st.blocks.size(), d = c->cfg.d_model, T = st.rows;
+  const bool pre = c->cfg.pre_norm != 0;
+  void* emb = pre ? st.resid[0] : st.norm[0];
+  run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * T * d * 2.0, [&] {
+    launch_embed_fwd(c->stream, c->dt, c->Wh, st.ids, st.pos, c->pe, emb, T, d, site_key(s, st.id, -1, 0), c->cfg.dropout);
+  });
+  if (pre) ln_fwd(c, st.resid[0], nullptr, st.blocks[0].ln_g, st.blocks[0].ln_b, nullptr, st.norm[0], st.mean[0], st.rstd[0], T, 0);
+  for (int k = 0; k < K; ++k) {
+    sublayer_fwd(s, st, k, st.norm[k], c->y);
+    int g, b;
+    if (pre) { g = k + 1 < K ? st.blocks[k + 1].ln_g : st.lnf_g; b = k + 1 < K ? st.blocks[k + 1].ln_b : st.lnf_b; }
+    else { g = st.blocks[k].ln_g; b = st.blocks[k].ln_b; }
+    ln_fwd(c, pre ? st.resid[k] : st.norm[k], c->y, g, b, st.resid[k + 1], st.norm[k + 1], st.mean[k + 1], st.rstd[k + 1], T,
+           block_key(s, st, k));
+  }
+}
+
+void colsum(tfm_ctx* c, const void* x, int ld, int rows, int n, void* out) {
+  run(c, TFM_PROF_NORM, 0.0, (double)c->esz * rows * n, [&] { launch_colsum(c->stream, c->dt, x, ld, rows, n, out, c->red_scratch); });
+}
+
+// backward of sub-layer k given dy; writes the gradient w.r.t. its input (plus `residual` if given) to dout
+void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const void* fin, const void* residual, void* dout,
+                  void** dmem_cur, void** dmem_other, bool* dmem_valid) {
+  tfm_ctx* c = s.c;
+  Block& b = st.blocks[k];
+  const int d = c->cfg.d_model, F = c->cfg.d_ffn, T = st.rows;
+  const std::vector<int>& len = st.id ? s.tlen : s.slen;
+  if (b.kind == SELF) {
+    gemm(c, 2, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d);
+    gemm(c, 1, T, d, d, dy, d, wh(c, b.w_o), d, c->dctx, d);
+    const char* qkv = (const char*)b.inter;
+    char* dqkv = (char*)c->dinter;
+    attention(s, true, st, st, len, len, qkv, 3 * d, qkv + d * c->esz, 3 * d, qkv + 2 * d * c->esz, 3 * d, b.ctx, b.lse, st.id == 1,
+              c->dctx, dqkv, 3 * d, dqkv + d * c->esz, 3 * d, dqkv + 2 * d * c->esz, 3 * d);
+    gemm(c, 2, 3 * d, d, T, dqkv, 3 * d, fin, d, gr(c, b.w_a), d);
+    colsum(c, dqkv, 3 * d, T, 3 * d, gr(c, b.b_a));
+    gemm(c, 1, T, d, 3 * d, dqkv, 3 * d, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
+  } else if (b.kind == CROSS) {
+    Stream& en = c->enc;
+    const void* mem = en.norm[en.blocks.size()];
+    gemm(c, 2, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d);
+    gemm(c, 1, T, d, d, dy, d, wh(c, b.w_o), d, c->dctx, d);
+    const char* kv = (const char*)b.kv;
+    char* dkv = (char*)c->dkv;
+    attention(s, true, st, en, s.tlen, s.slen, b.inter, d, kv, 2 * d, kv + d * c->esz, 2 * d, b.ctx, b.lse, false, c->dctx,
+              c->dq, d, dkv, 2 * d, dkv + d * c->esz, 2 * d);
+    gemm(c, 2, d, d, T, c->dq, d, fin, d, gr(c, b.w_a), d);
+    colsum(c, c->dq, d, T, d, gr(c, b.b_a));
+    gemm(c, 1, T, d, d, c->dq, d, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
+    gemm(c, 2, 2 * d, d, en.rows, dkv, 2 * d, mem, d, gr(c, b.w_kv), d);
+    colsum(c, dkv, 2 * d, en.rows, 2 * d, gr(c, b.b_kv));
+    gemm(c, 1, en.rows, d, 2 * d, dkv, 2 * d, wh(c, b.w_kv), d, *dmem_other, d, nullptr, 0, nullptr, *dmem_valid ? *dmem_cur : nullptr);
+    std::swap(*dmem_cur, *dmem_other);
+    *dmem_valid = true;
+  } else {
+    gemm(c, 2, d, F, T, dy, d, b.inter, F, gr(c, b.w_o), F);
+    gemm(c, 1, T, F, d, dy, d, wh(c, b.w_o), F, c->dinter, F, nullptr, 0, b.inter, nullptr);
+    gemm(c, 2, F, d, T, c->dinter, F, fin, d, gr(c, b.w_a), d);
+    colsum(c, c->dinter, F, T, F, gr(c, b.b_a));
+    gemm(c, 1, T, d, F, c->dinter, F, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
+  }
+}
+
+void ln_bwd(tfm_ctx* c, const void* dn, const void* add, const void* sres, const float* mean, const float* rstd, int g, int b,
+            void* ds, void* ds_drop, int bias_param, int rows, uint64_t key) {
+  const int d = c->cfg.d_model;
+  const bool drop = c->cfg.dropout > 0.f && ds_drop;
+  const double bytes = (double)c->esz * rows * d * (2.0 + (add ? 1.0 : 0.0) + 1.0 + (drop ? 1.0 : 0.0));
+  run(c, TFM_PROF_NORM, 0.0, bytes, [&] {
+    launch_layernorm_bwd(c->stream, c->dt, dn, add, sres, mean, rstd, wh(c, g), ds, drop ? ds_drop : nullptr, gr(c, g), gr(c, b),
+                         bias_param >= 0 ? gr(c, bias_param) : nullptr, rows, d, key, c->cfg.dropout, c->red_scratch);
+  });
+}
+
+// Backward through a stream.  On entry c->dcur holds the gradient w.r.t. the stream output norm[K]; returns the buffer
+// holding the gradient w.r.t. the embedding output.
+void* stream_bwd(const StepCtx& s, Stream& st, void** dmem_cur, void** dmem_other, bool* dmem_valid, void* dn_in) {
+  tfm_ctx* c = s.c;
+  const int K = (int)st.blocks.size(), T = st.rows;
+  const bool pre = c->cfg.pre_norm != 0;
+  const bool drop = c->cfg.dropout > 0.f;
+  // Every gradient w.r.t. a block output is consumed by the LayerNorm-backward kernel before the sub-layer's last
+  // GEMM writes the next one, so a single buffer (dcur) carries it down the stack.
+  void* dn = dn_in;
+  if (!pre) {
+    for (int k = K - 1; k >= 0; --k) {
+      Block& b = st.blocks[k];
+      ln_bwd(c, dn, nullptr, st.resid[k + 1], st.mean[k + 1], st.rstd[k + 1], b.ln_g, b.ln_b, c->dsA, c->dy, b.b_o, T, block_key(s, st, k));
+      const void* dy = drop ? c->dy : c->dsA;
+      void* out = k == 0 ? c->demb[st.id] : c->dcur;
+      sublayer_bwd(s, st, k, dy, st.norm[k], c->dsA, out, dmem_cur, dmem_other, dmem_valid);
+      dn = out;
+    }
+    return dn;
+  }
+  // pre-norm: the residual stream's gradient ping-pongs between dsA and dsB
+  void* dR = nullptr;
+  void* ds = c->dsA;
+  void* ds_alt = c->dsB;
+  for (int idx = K; idx >= 0; --idx) {
+    const int g = idx < K ? st.blocks[idx].ln_g : st.lnf_g;
+    const int b = idx < K ? st.blocks[idx].ln_b : st.lnf_b;
+    const int bias = idx >= 1 ? st.blocks[idx - 1].b_o : -1;
+    if (idx == 0) ds = c->demb[st.id];
+    ln_bwd(c, dn, dR, st.resid[idx], st.mean[idx], st.rstd[idx], g, b, ds, idx >= 1 ? c->dy : nullptr, bias, T,
+           idx >= 1 ? block_key(s, st, idx - 1) : 0);
+    if (idx == 0) return ds;
+    const void* dy = drop ? c->dy : ds;
+    sublayer_bwd(s, st, idx - 1, dy, st.norm[idx - 1], nullptr, c->dcur, dmem_cur, dmem_other, dmem_valid);
+    dn = c->dcur;
+    dR = ds;
+    std::swap(ds, ds_alt);
+  }
+  return nullptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int32_t* src_lens, const int32_t* tgt_lens,
+                   int32_t B, int32_t Ls, int32_t Lt, tfm_step_out* out) {
+  if (!c) return TFM_EINVAL;
+  const tfm_config& cf = c->cfg;
+  const bool has_enc = cf.enc_layers > 0;
+  // ---- validation: nothing is enqueued before every check has passed
+  if (!tgt || !tgt_lens) return fail(c, TFM_EINVAL, "tgt and tgt_lens are required");
+  if (has_enc && (!src || !src_lens)) return fail(c, TFM_EINVAL, "src and src_lens are required for an encoder-decoder model");
+  if (!has_enc && (src || src_lens)) return fail(c, TFM_EINVAL, "src must be NULL for a decoder-only model");
+  if (B < 1 || B > cf.max_sentences) return fail(c, TFM_EINVAL, "B = %d outside [1, %d]", B, cf.max_sentences);
+  if (Lt < 1 || Lt > cf.max_len || (has_enc && (Ls < 1 || Ls > cf.max_len))) return fail(c, TFM_EINVAL, "padded length outside [1, %d]", cf.max_len);
+  long long Ts = 0, Tt = 0;
+  for (int b = 0; b < B; ++b) {
+    if (tgt_lens[b] < 1 || tgt_lens[b] > Lt) return fail(c, TFM_EINVAL, "tgt_lens[%d] = %d outside [1, %d]", b, tgt_lens[b], Lt);
+    Tt += tgt_lens[b];
+    if (has_enc) {
+      if (src_lens[b] < 1 || src_lens[b] > Ls) return fail(c, TFM_EINVAL, "src_lens[%d] = %d outside [1, %d]", b, src_lens[b], Ls);
+      Ts += src_lens[b];
+    }
+  }
+  if (Tt > cf.max_tokens || Ts > cf.max_tokens) return fail(c, TFM_EINVAL, "%lld source / %lld target tokens exceed max_tokens = %d", Ts, Tt, cf.max_tokens);
+  for (int b = 0; b < B; ++b) {
+    for (int t = 0; t < tgt_lens[b]; ++t) {
+      const int id = tgt[(size_t)b * Lt + t];
+      if (id < 0 || id >= cf.vocab) return fail(c, TFM_EINVAL, "tgt[%d,%d] = %d outside the vocabulary", b, t, id);
+    }
+    if (has_enc) for (int t = 0; t < src_lens[b]; ++t) {
+      const int id = src[(size_t)b * Ls + t];
+      if (id < 0 || id >= cf.vocab) return fail(c, TFM_EINVAL, "src[%d,%d] = %d outside the vocabulary", b, t, id);
+    }
+  }
+
+  // ---- ingest: pack into the staging slot
+  const int slot = c->stage_next;
+  c->stage_next = (slot + 1) % STAGE_SLOTS;
+  if (c->stage_used[slot]) HIP_TRY(c, hipEventSynchronize(c->stage_ev[slot]));
+  int* hb = c->stage[slot];
+  const size_t R = (size_t)cf.max_tokens, Bc = (size_t)cf.max_sentences + 1;
+  int* e_ids = hb; int* e_pos = e_ids + R; int* e_off = e_pos + R;
+  int* d_ids = e_off + Bc; int* d_pos = d_ids + R; int* d_off = d_pos + R;
+  int* labels = d_off + Bc;
+  int* uniq = labels + R; int* ustart = uniq + 2 * R; int* uent = ustart + 2 * R + 1;
+  StepCtx s{c};
+  s.B = B; s.Ts = (int)Ts; s.Tt = (int)Tt; s.step = c->train_steps;
+  s.tlen.assign(tgt_lens, tgt_lens + B);
+  if (has_enc) s.slen.assign(src_lens, src_lens + B);
+  int r = 0, maxs = 0, maxt = 0;
+  if (has_enc) {
+    for (int b = 0; b < B; ++b) {
+      e_off[b] = r;
+      for (int t = 0; t < src_lens[b]; ++t, ++r) { e_ids[r] = src[(size_t)b * Ls + t]; e_pos[r] = t; }
+      maxs = std::max(maxs, src_lens[b]);
+    }
+    e_off[B] = r;
+  }
+  r = 0;
+  for (int b = 0; b < B; ++b) {
+    d_off[b] = r;
+    for (int t = 0; t < tgt_lens[b]; ++t, ++r) {
+      labels[r] = tgt[(size_t)b * Lt + t];
+      d_ids[r] = t == 0 ? cf.eos_id : tgt[(size_t)b * Lt + t - 1];   // teacher forcing: eos, then the target shifted right
+      d_pos[r] = t;
+    }
+    maxt = std::max(maxt, tgt_lens[b]);
+  }
+  d_off[B] = r;
+  // token -> occurrences (counting sort over the vocabulary; order: encoder rows, then decoder rows, ascending)
+  int nu = 0;
+  {
+    std::vector<int>& cnt = c->count;
+    for (int i = 0; i < (int)Ts; ++i) if (cnt[e_ids[i]]++ == 0) uniq[nu++] = e_ids[i];
+    for (int i = 0; i < (int)Tt; ++i) if (cnt[d_ids[i]]++ == 0) uniq[nu++] = d_ids[i];
+    std::sort(uniq, uniq + nu);
+    int acc = 0;
+    for (int u = 0; u < nu; ++u) { ustart[u] = acc; const int n = cnt[uniq[u]]; cnt[uniq[u]] = acc; acc += n; }
+    ustart[nu] = acc;
+    for (int i = 0; i < (int)Ts; ++i) uent[cnt[e_ids[i]]++] = i;
+    for (int i = 0; i < (int)Tt; ++i) uent[cnt[d_ids[i]]++] = (1 << 30) | i;
+    for (int u = 0; u < nu; ++u) cnt[uniq[u]] = 0;
+  }
+  HIP_TRY(c, hipMemcpyAsync(c->ibase, hb, c->int_block_ints * 4, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipEventRecord(c->stage_ev[slot], c->stream));
+  c->stage_used[slot] = true;
+  c->enc.rows = (int)Ts; c->enc.max_len = maxs;
+  c->dec.rows = (int)Tt; c->dec.max_len = maxt;
+
+  const int d = cf.d_model, V = cf.vocab;
+  // a second sub-batch in the window: move the first one's gradient into the fp32 accumulator before g is reused
+  if (c->window_mb == 1)
+    run(c, TFM_PROF_OPTIM, 0.0, (double)c->P * (c->esz + 4.0), [&] { launch_convert(c->stream, c->dt, c->g, F32, c->G, c->P); });
+
+  // ---- forward
+  if (has_enc) stream_fwd(s, c->enc);
+  stream_fwd(s, c->dec);
+  Stream& de = c->dec;
+  const int Kd = (int)de.blocks.size();
+  const void* top = de.norm[Kd];
+  gemm(c, 0, (int)Tt, V, d, top, d, c->Wh, d, c->logits, V);
+  const float mult = c->next_mult;
+  c->next_mult = 1.f;
+  run(c, TFM_PROF_LOSS, 0.0, 2.0 * c->esz * (double)Tt * V, [&] {
+    launch_loss(c->stream, c->dt, c->logits, c->labels, c->loss_rows, c->nll_rows, (int)Tt, V, cf.label_smoothing, &c->st->loss_scale,
+                mult, &c->st->step_scale);
+    launch_sum_rows(c->stream, c->loss_rows, c->nll_rows, (int)Tt, &c->st->loss_sum);
+  });
+
+  // ---- backward
+  gemm(c, 2, V, d, (int)Tt, c->logits, V, top, d, c->g, d);               // embedding gradient, output side
+  gemm(c, 1, (int)Tt, d, V, c->logits, V, c->Wh, d, c->dcur, d);
+  void* dmem_cur = c->dmemA;
+  void* dmem_other = c->dmemB;
+  bool dmem_valid = false;
+  void* ddec = stream_bwd(s, de, &dmem_cur, &dmem_other, &dmem_valid, c->dcur);
+  void* denc = nullptr;
+  if (has_enc) denc = stream_bwd(s, c->enc, &dmem_cur, &dmem_other, &dmem_valid, dmem_cur);
+  run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * d * ((double)Ts + Tt + 2.0 * nu), [&] {
+    launch_embed_bwd(c->stream, c->dt, c->g, c->uniq, c->ustart, c->uentries, nu, denc, ddec, d, site_key(s, 0, -1, 0),
+                     site_key(s, 1, -1, 0), cf.dropout);
+  });
+
+  // ---- inf/nan scan of this sub-batch's gradient (+ accumulation from the second sub-batch on)
+  const int acc_mode = c->window_mb >= 1 ? 2 : 0;
+  run(c, TFM_PROF_OPTIM, 0.0, (double)c->P * (c->esz + (acc_mode ? 8.0 : 0.0)), [&] {
+    launch_scan(c->stream, c->dt, c->g, c->P, nullptr, c->st, acc_mode ? c->G : nullptr, acc_mode, c->scan_scratch);
+  });
+  c->window_mb += 1;
+  c->window_tokens += Tt;
+  c->train_steps += 1;
+  HIP_TRY(c, hipGetLastError());
+  if (out) {
+    DevState h;
+    HIP_TRY(c, hipMemcpyAsync(&h, c->st, sizeof(h), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    out->loss_sum = h.loss_sum; out->nll_sum = h.nll_sum; out->ntokens = Tt; out->overflow = h.step_overflow;
+    out->loss_scale = h.loss_scale;
+  }
+  return TFM_OK;
+}
+
+int tfm_apply_update(tfm_ctx* c, float lr, tfm_update_out* out) {
+  if (!c) return TFM_EINVAL;
+  if (c->window_mb == 0) return fail(c, TFM_ESTATE, "no sub-batch has been accumulated");
+  if (!std::isfinite(lr)) return fail(c, TFM_EINVAL, "learning rate is not finite");
+  const tfm_config& cf = c->cfg;
+  const bool single = c->window_mb == 1;
+  // the scan of a single sub-batch already produced the sum of squares; an accumulated window is scanned again
+  if (!single)
+    run(c, TFM_PROF_OPTIM, 0.0, (double)c->P * 4.0, [&] {
+      // window_overflow is sticky (|=) so this scan cannot clear an earlier sub-batch's flag
+      launch_scan(c->stream, F32, c->G, c->P, nullptr, c->st, nullptr, 0, c->scan_scratch);
+    });
+  launch_scaler_update(c->stream, c->st, c->window_tokens, cf.clip_norm, cf.adam_beta1, cf.adam_beta2, cf.scale_window,
+                       cf.min_loss_scale, cf.precision == TFM_FP16 ? 1 : 0);
+  AdamArgs a{};
+  a.w = c->W; a.m = c->M; a.v = c->V; a.n = c->P;
+  a.g = single ? c->g : (const void*)c->G; a.gdt = single ? c->dt : (int)F32;
+  a.half_copy = c->dt == F32 ? nullptr : c->Wh; a.hdt = c->dt;
+  a.lr = lr; a.beta1 = cf.adam_beta1; a.beta2 = cf.adam_beta2; a.eps = cf.adam_eps; a.st = c->st;
+  run(c, TFM_PROF_OPTIM, 0.0, (double)c->P * (24.0 + (single ? c->esz : 4.0) + (c->dt == F32 ? 0.0 : 2.0)), [&] { launch_adam(c->stream, a); });
+  const long long ntok = c->window_tokens;
+  c->window_mb = 0;
+  c->window_tokens = 0;
+  HIP_TRY(c, hipGetLastError());
+  if (out) {
+    DevState h;
+    HIP_TRY(c, hipMemcpyAsync(&h, c->st, sizeof(h), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    out->skipped = h.skipped; out->loss_scale_after = h.loss_scale; out->clean_steps = h.clean_steps;
+    out->num_updates = h.num_updates; out->grad_norm = h.grad_norm; out->ntokens_total = ntok;
+    if (h.scale_too_small) return fail(c, TFM_ESCALE, "loss scale %g fell below the minimum %g", h.loss_scale, cf.min_loss_scale);
+  }
+  return TFM_OK;
+}
+
+// ---- single operations ---------------------------------------------------------------------------------------------------------
+static int op_done() { return hipGetLastError() == hipSuccess ? TFM_OK : TFM_EHIP; }
+
+int tfm_op_gemm(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K, const void* A, int32_t lda, const void* B,
+                int32_t ldb, void* C, int32_t ldc, const void* bias, int32_t relu, const void* mask, const void* residual,
+                void* stream) {
+  if (dtype < 0 || dtype > 2 || form < 0 || form > 2 || M < 0 || N < 0 || K < 0 || !A || !B || !C) return TFM_EINVAL;
+  if (lda < (form == 2 ? M : K) || ldb < (form == 0 ? K : N) || ldc < N) return TFM_EINVAL;
+  GemmArgs a{dtype, form, M, N, K, A, lda, B, ldb, C, ldc, bias, relu, mask, residual};
+  launch_gemm((hipStream_t)stream, a);
+  return op_done();
+}
+
+int tfm_op_attention_fwd(int32_t dtype, const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v, int32_t ldv,
+                         void* o, int32_t ldo, float* lse, const int32_t* q_off, const int32_t* k_off, int32_t B, int32_t H,
+                         int32_t dh, int32_t max_lq, int32_t max_lk, int32_t total_q, int32_t causal, void* stream) {
+  if (dtype < 0 || dtype > 2 || !q || !k || !v || !o || !lse || !q_off || !k_off || B < 1 || H < 1 || dh < 1 || dh > 128) return TFM_EINVAL;
+  if (max_lq < 1 || max_lk < 1 || max_lq > 4096 || max_lk > 4096) return TFM_EINVAL;
+  AttnArgs a{};
+  a.dt = dtype; a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.o = o; a.ldo = ldo; a.lse = lse;
+  a.q_off = q_off; a.k_off = k_off; a.B = B; a.H = H; a.dh = dh; a.max_lq = max_lq; a.max_lk = max_lk; a.total_q = total_q;
+  a.causal = causal;
+  launch_attention_fwd((hipStream_t)stream, a);
+  return op_done();
+}
+
+int tfm_op_attention_bwd(int32_t dtype, const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v, int32_t ldv,
+                         const void* o, int32_t ldo, const void* d_o, int32_t lddo, const float* lse, void* dq, int32_t lddq,
+                         void* dk, int32_t lddk, void* dv, int32_t lddv, const int32_t* q_off, const int32_t* k_off, int32_t B,
+                         int32_t H, int32_t dh, int32_t max_lq, int32_t max_lk, int32_t total_q, int32_t total_k, int32_t causal,
+                         void* stream) {
+  if (dtype < 0 || dtype > 2 || !q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !q_off || !k_off) return TFM_EINVAL;
+  if (B < 1 || H < 1 || dh < 1 || dh > 128 || max_lq < 1 || max_lk < 1 || max_lq > 4096 || max_lk > 4096) return TFM_EINVAL;
+  AttnArgs a{};
+  a.dt = dtype; a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.o = const_cast<void*>(o); a.ldo = ldo;
+  a.lse = const_cast<float*>(lse); a.q_off = q_off; a.k_off = k_off; a.B = B; a.H = H; a.dh = dh; a.max_lq = max_lq;
+  a.max_lk = max_lk; a.total_q = total_q; a.total_k = total_k; a.causal = causal; a.d_o = d_o; a.lddo = lddo; a.dq = dq;
+  a.dk = dk; a.dv = dv; a.lddq = lddq; a.lddk = lddk; a.lddv = lddv;
+  launch_attention_bwd((hipStream_t)stream, a);
+  return op_done();
+}
+
+int tfm_op_residual_layernorm_fwd(int32_t dtype, const void* x, const void* y, const void* gamma, const void* beta, void* s_out,
+                                  void* n_out, float* mean, float* rstd, int32_t rows, int32_t d, uint64_t drop_key, float p,
+                                  void* stream) {
+  if (dtype < 0 || dtype > 2 || !x || !gamma || !beta || !n_out || !mean || !rstd || rows < 0 || d < 8 || d % 8 || d > 2048) return TFM_EINVAL;
+  launch_residual_layernorm_fwd((hipStream_t)stream, dtype, x, y, gamma, beta, s_out, n_out, mean, rstd, rows, d, drop_key, p);
+  return op_done();
+}
+
+size_t tfm_op_layernorm_bwd_scratch(int32_t rows, int32_t d) { return layernorm_bwd_scratch_bytes(rows, d); }
+
+int tfm_op_layernorm_bwd(int32_t dtype, const void* dn, const void* add, const void* s, const float* mean, const float* rstd,
+                         const void* gamma, void* ds, void* ds_drop, void* dgamma, void* dbeta, void* dbias, int32_t rows,
+                         int32_t d, uint64_t drop_key, float p, void* scratch, void* stream) {
+  if (dtype < 0 || dtype > 2 || !dn || !s || !mean || !rstd || !gamma || !ds || !dgamma || !dbeta || !scratch) return TFM_EINVAL;
+  if (rows < 1 || d < 8 || d % 8 || d > 1024) return TFM_EINVAL;
+  launch_layernorm_bwd((hipStream_t)stream, dtype, dn, add, s, mean, rstd, gamma, ds, ds_drop, dgamma, dbeta, dbias, rows, d,
+                       drop_key, p, scratch);
+  return op_done();
+}
+
+int tfm_op_loss(int32_t dtype, void* z, const int32_t* labels, float* loss_rows, float* nll_rows, int32_t rows, int32_t V,
+                float eps, float scale, void* stream) {
+  if (dtype < 0 || dtype > 2 || !z || !labels || !loss_rows || !nll_rows || rows < 0 || V < 1) return TFM_EINVAL;
+  launch_loss((hipStream_t)stream, dtype, z, labels, loss_rows, nll_rows, rows, V, eps, nullptr, scale, nullptr);
+  return op_done();
+}
+
+int tfm_op_adam(float* w, float* m, float* v, const void* g, int32_t gdtype, void* half_copy, int32_t hdtype, int64_t n,
+                float lr, float beta1, float beta2, float eps, float grad_mult, float bc1, float bc2, void* stream) {
+  if (!w || !m || !v || !g || gdtype < 0 || gdtype > 2 || hdtype < 0 || hdtype > 2 || n < 0 || n % 8) return TFM_EINVAL;
+  AdamArgs a{w, m, v, g, gdtype, half_copy, hdtype, n, lr, beta1, beta2, eps, nullptr, grad_mult, bc1, bc2};
+  launch_adam((hipStream_t)stream, a);
+  return op_done();
+}
+
+size_t tfm_op_scan_scratch(int64_t n) { return scan_scratch_bytes(n); }
+
+int tfm_op_scan(int32_t dtype, const void* x, int64_t n, float* result, void* scratch, void* stream) {
+  if (dtype < 0 || dtype > 2 || !x || !result || !scratch || n < 0 || n % 8) return TFM_EINVAL;
+  launch_scan((hipStream_t)stream, dtype, x, n, result, nullptr, nullptr, 0, scratch);
+  return op_done();
+}
+
+int tfm_op_dropout_mask(uint64_t key, float p, uint8_t* out, int64_t n, void* stream) {
+  if (!out || n < 0 || !(p >= 0.f && p < 1.f)) return TFM_EINVAL;
+  launch_dropout_mask((hipStream_t)stream, key, p, out, n);
+  return op_done();
+}
+
+uint64_t tfm_dropout_key(uint64_t seed, uint64_t step, int32_t stream, int32_t layer, int32_t sub) {
+  return dropout_site_key(seed, step, stream, layer, sub);
+}
+
+}  // extern "C"
