@@ -149,7 +149,8 @@ int tfm_profile_read(tfm_ctx* ctx, tfm_prof_entry out[TFM_PROF_CLASSES], int32_t
 
 /* C[M,N] = epilogue(op(A) op(B)).  form 0 "NT": A[M,K], B[N,K];  1 "NN": A[M,K], B[K,N];  2 "TN": A[K,M], B[K,N].
  * lda/ldb/ldc are row strides in elements.  epilogue: + bias[N] (may be NULL), ReLU if relu != 0, multiply by
- * (mask[m,n] > 0) if mask != NULL (row stride ldc), + residual[m,n] if residual != NULL (row stride ldc; may alias C). */
+ * (mask[m,n] > 0) if mask != NULL (row stride ldc), + residual[m,n] if residual != NULL (row stride ldc; must not
+ * overlap C). */
 int tfm_op_gemm(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K, const void* A, int32_t lda,
                 const void* B, int32_t ldb, void* C, int32_t ldc, const void* bias, int32_t relu,
                 const void* mask, const void* residual, void* stream);

@@ -58,6 +58,9 @@ def lib():
         path = lib_path()
         if not os.path.exists(path):
             raise FileNotFoundError(path + " is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # PyTorch owns the device memory and the stream, so its HIP runtime must be the one this library binds to:
+        # import it first, otherwise the loader would pull in a second copy of the runtime.
+        import torch  # noqa: F401
         L = C.CDLL(path)
         vp, i32, i64, f32, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_uint64
         L.tfm_workspace_bytes.argtypes = [C.POINTER(TfmConfig), C.POINTER(C.c_size_t)]

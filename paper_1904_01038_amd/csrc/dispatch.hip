@@ -5,7 +5,8 @@
 namespace tfm {
 
 void launch_gemm(hipStream_t s, const GemmArgs& a) {
-  launch_gemm_naive(s, a);
+  if (gemm_mfma_supported(a)) launch_gemm_mfma(s, a);
+  else launch_gemm_naive(s, a);
 }
 
 void launch_attention_fwd(hipStream_t s, const AttnArgs& a) { launch_attention_fwd_naive(s, a); }

@@ -39,11 +39,12 @@ struct GemmArgs {
   const void* bias;          // [N] or null
   int relu;
   const void* mask;          // [M, N] stride ldc or null: multiply by (mask > 0)
-  const void* residual;      // [M, N] stride ldc or null: added last (may alias C)
+  const void* residual;      // [M, N] stride ldc or null: added last (must not alias C)
 };
 void launch_gemm(hipStream_t s, const GemmArgs& a);
 bool gemm_mfma_supported(const GemmArgs& a);
 void launch_gemm_naive(hipStream_t s, const GemmArgs& a);
+void launch_gemm_mfma(hipStream_t s, const GemmArgs& a);      // requires gemm_mfma_supported(a)
 
 struct AttnArgs {
   int dt;
