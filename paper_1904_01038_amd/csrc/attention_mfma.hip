@@ -1,0 +1,431 @@
+// Fused multi-head attention on the matrix cores for head width 64, fp16/bf16 operands, fp32 softmax.
+//
+// Every product is formed transposed so that one lane owns one softmax row: for scores S^T[key][query] the MFMA
+// accumulator layout puts a query in lane%32 and 16 keys in the lane's registers, so row max / row sum are
+// in-register reductions plus one exchange between lane halves, and the exponentiated tile is already in the
+// operand layout of the second product (O^T = V^T P^T) - no LDS round trip for P.
+//
+// K and V tiles are staged in LDS once per 64-key chunk and shared by the block's wavefronts.  Operands whose
+// contraction index is the slow one in memory (V for O^T = V^T P^T, K for dQ^T = K^T dS^T, Q and dO for
+// dK^T/dV^T) are staged as they lie and fetched with the CDNA4 LDS transpose read (ds_read_b64_tr_b16).
+//
+// Forward: grid (query chunks of 64, heads, sentences), 2 wavefronts x 32 queries, online softmax over key chunks,
+//          stores the row log-sum-exp.
+// Backward: (1) dQ kernel, same decomposition, recomputes P from the saved log-sum-exp;
+//           (2) dK/dV kernel, grid over key chunks of 64, loops over query chunks.  No atomics.
+#include "common.h"
+#include "kernels.h"
+
+namespace tfm {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int DH = 64;
+constexpr int PT = 80;                 // LDS pitch (halfs) of a [rows][64] tile: 160-byte rows
+constexpr int CH = 64;                 // rows per staged chunk
+constexpr int ATT_THREADS = 128;
+
+template <typename T> struct AMfma;
+template <> struct AMfma<half_t> {
+  static __device__ __forceinline__ f32x16 run(u32x4 a, u32x4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ uint32_t pack2(float a, float b) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 v = {(_Float16)a, (_Float16)b};
+    return __builtin_bit_cast(uint32_t, v);
+  }
+};
+template <> struct AMfma<bf16_t> {
+  static __device__ __forceinline__ f32x16 run(u32x4 a, u32x4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ uint32_t pack2(float a, float b) {
+    return (uint32_t)f_to_bf16_bits(a) | ((uint32_t)f_to_bf16_bits(b) << 16);
+  }
+};
+
+struct AttnP {
+  const uint16_t *q, *k, *v, *o, *d_o;
+  uint16_t *out, *dq, *dk, *dv;
+  int ldq, ldk, ldv, ldo, lddo, lddq, lddk, lddv;
+  float* lse;
+  const int *q_off, *k_off;
+  int total_q, causal;
+  float scale;
+};
+
+// rows r0..r0+31 of a staged tile as an MFMA operand: lane -> row r0 + lane%32, columns kk*16 + (lane/32)*8 .. +8
+__device__ __forceinline__ u32x4 frag_direct(const uint16_t* S, int r0, int kk, int lane) {
+  return *reinterpret_cast<const u32x4*>(S + (r0 + (lane & 31)) * PT + kk * 16 + (lane >> 5) * 8);
+}
+// columns c0..c0+31 of a staged tile as an MFMA operand whose contraction runs over 16 tile rows from kbase:
+// lane -> column c0 + lane%32; k-slot (half = lane/32, e) -> tile row kbase + 4*half + e (e < 4), kbase + 8 + 4*half + e-4.
+// This is the row order in which a 32x32 accumulator holds its rows, so an accumulator converts in place into the
+// other operand of the same product.
+__device__ __forceinline__ u32x4 frag_tr(const uint16_t* S, int c0, int kbase, int lane) {
+  const int s = lane & 15, ibase = lane & 16, half = lane >> 5;
+  const uint16_t* p = S + (kbase + 4 * half + (s >> 2)) * PT + c0 + ibase + 4 * (s & 3);
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * PT));
+  const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+  return u32x4{l2[0], l2[1], h2[0], h2[1]};
+}
+// 64 rows x 64 columns from global (row stride ld) into LDS, zero beyond nvalid rows.  128 threads, 4 vectors each.
+__device__ __forceinline__ void stage_tile(uint16_t* S, const uint16_t* __restrict__ G, int ld, int row0, int nvalid) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v = threadIdx.x + ATT_THREADS * i;
+    const int r = v >> 3, c = (v & 7) * 8;
+    u32x4 x = {0u, 0u, 0u, 0u};
+    if (row0 + r < nvalid) x = *reinterpret_cast<const u32x4*>(G + (size_t)(row0 + r) * ld + c);
+    *reinterpret_cast<u32x4*>(S + r * PT + c) = x;
+  }
+}
+// operand fragments of 32 rows straight from global memory (rows beyond nvalid are zero)
+__device__ __forceinline__ void load_frags(u32x4 (&f)[4], const uint16_t* __restrict__ G, int ld, int row, int nvalid, int lane) {
+  const int r = row + (lane & 31);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    f[kk] = u32x4{0u, 0u, 0u, 0u};
+    if (r < nvalid) f[kk] = *reinterpret_cast<const u32x4*>(G + (size_t)r * ld + kk * 16 + (lane >> 5) * 8);
+  }
+}
+template <typename T>
+__device__ __forceinline__ float dot8(u32x4 a, u32x4 b) {
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t x = a[i], y = b[i];
+    float x0, x1, y0, y1;
+    if (sizeof(T) == 2 && __is_same(T, half_t)) {
+      typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+      const h2 xv = __builtin_bit_cast(h2, x), yv = __builtin_bit_cast(h2, y);
+      x0 = (float)xv[0]; x1 = (float)xv[1]; y0 = (float)yv[0]; y1 = (float)yv[1];
+    } else {
+      x0 = bf16_bits_to_f((uint16_t)(x & 0xffff)); x1 = bf16_bits_to_f((uint16_t)(x >> 16));
+      y0 = bf16_bits_to_f((uint16_t)(y & 0xffff)); y1 = bf16_bits_to_f((uint16_t)(y >> 16));
+    }
+    s += x0 * y0 + x1 * y1;
+  }
+  return s;
+}
+template <typename T>
+__device__ __forceinline__ void store4(uint16_t* p, float a, float b, float c, float d) {
+  u32x2 v = {AMfma<T>::pack2(a, b), AMfma<T>::pack2(c, d)};
+  *reinterpret_cast<u32x2*>(p) = v;
+}
+
+// ---- forward ------------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(ATT_THREADS) void attn_fwd_mfma_kernel(AttnP p) {
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[CH * PT];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[CH * PT];
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;
+  const int qstart = blockIdx.x * 64;
+  if (qstart >= lq) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
+  const int qi0 = qstart + wave * 32;
+  const bool active = qi0 < lq;
+  const int qi = qi0 + (lane & 31);
+  const uint16_t* Q = p.q + (size_t)q0 * p.ldq + h * DH;
+  const uint16_t* K = p.k + (size_t)k0 * p.ldk + h * DH;
+  const uint16_t* V = p.v + (size_t)k0 * p.ldv + h * DH;
+  u32x4 qf[4];
+  load_frags(qf, Q, p.ldq, qi0, lq, lane);
+  float m = -INFINITY, lsum = 0.f;
+  f32x16 acc[2];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) { acc[0][e] = 0.f; acc[1][e] = 0.f; }
+  const int kend = p.causal ? min(lk, qstart + 64) : lk;
+  for (int kc = 0; kc < kend; kc += CH) {
+    __syncthreads();
+    stage_tile(Ks, K, p.ldk, kc, lk);
+    stage_tile(Vs, V, p.ldv, kc, lk);
+    __syncthreads();
+    if (!active) continue;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const int j0 = kc + kb * 32;
+      if (j0 >= kend) break;
+      f32x16 s;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) s = AMfma<T>::run(frag_direct(Ks, kb * 32, kk, lane), qf[kk], s);
+      float bm = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const bool ok = j < lk && (!p.causal || j <= qi);
+        s[r] = ok ? s[r] * p.scale : -INFINITY;
+        bm = fmaxf(bm, s[r]);
+      }
+      bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+      const float mn = fmaxf(m, bm);
+      // mn is finite from the first block on: key 0 is valid for every query
+      const float alpha = __expf(m - mn);
+      float ps = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[r] = __expf(s[r] - mn); ps += s[r]; }
+      lsum = lsum * alpha + ps;
+      m = mn;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { acc[0][e] *= alpha; acc[1][e] *= alpha; }
+      u32x4 pf[2];
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) pf[ks][w] = AMfma<T>::pack2(s[ks * 8 + 2 * w], s[ks * 8 + 2 * w + 1]);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) acc[db] = AMfma<T>::run(frag_tr(Vs, db * 32, kb * 32 + ks * 16, lane), pf[ks], acc[db]);
+    }
+  }
+  if (!active) return;
+  lsum += __shfl_xor(lsum, 32, 64);
+  if (qi < lq) {
+    const float inv = 1.f / lsum;
+    uint16_t* O = p.out + (size_t)(q0 + qi) * p.ldo + h * DH;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg)
+        store4<T>(O + db * 32 + rg * 8 + half * 4, acc[db][rg * 4] * inv, acc[db][rg * 4 + 1] * inv, acc[db][rg * 4 + 2] * inv,
+                  acc[db][rg * 4 + 3] * inv);
+    if (half == 0) p.lse[(size_t)h * p.total_q + q0 + qi] = m + logf(lsum);
+  }
+}
+
+// ---- backward: dQ ---------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(ATT_THREADS) void attn_bwd_dq_mfma_kernel(AttnP p) {
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[CH * PT];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[CH * PT];
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;
+  const int qstart = blockIdx.x * 64;
+  if (qstart >= lq) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
+  const int qi0 = qstart + wave * 32;
+  const bool active = qi0 < lq;
+  const int qi = qi0 + (lane & 31);
+  const uint16_t* K = p.k + (size_t)k0 * p.ldk + h * DH;
+  const uint16_t* V = p.v + (size_t)k0 * p.ldv + h * DH;
+  u32x4 qf[4], gf[4], of[4];
+  load_frags(qf, p.q + (size_t)q0 * p.ldq + h * DH, p.ldq, qi0, lq, lane);
+  load_frags(gf, p.d_o + (size_t)q0 * p.lddo + h * DH, p.lddo, qi0, lq, lane);
+  load_frags(of, p.o + (size_t)q0 * p.ldo + h * DH, p.ldo, qi0, lq, lane);
+  float delta = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) delta += dot8<T>(gf[kk], of[kk]);
+  delta += __shfl_xor(delta, 32, 64);
+  const float L = qi < lq ? p.lse[(size_t)h * p.total_q + q0 + qi] : 0.f;
+  f32x16 acc[2];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) { acc[0][e] = 0.f; acc[1][e] = 0.f; }
+  const int kend = p.causal ? min(lk, qstart + 64) : lk;
+  for (int kc = 0; kc < kend; kc += CH) {
+    __syncthreads();
+    stage_tile(Ks, K, p.ldk, kc, lk);
+    stage_tile(Vs, V, p.ldv, kc, lk);
+    __syncthreads();
+    if (!active) continue;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const int j0 = kc + kb * 32;
+      if (j0 >= kend) break;
+      f32x16 s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        s = AMfma<T>::run(frag_direct(Ks, kb * 32, kk, lane), qf[kk], s);
+        dp = AMfma<T>::run(frag_direct(Vs, kb * 32, kk, lane), gf[kk], dp);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const bool ok = j < lk && qi < lq && (!p.causal || j <= qi);
+        const float pr = ok ? __expf(s[r] * p.scale - L) : 0.f;
+        s[r] = pr * (dp[r] - delta);
+      }
+      u32x4 df[2];
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) df[ks][w] = AMfma<T>::pack2(s[ks * 8 + 2 * w], s[ks * 8 + 2 * w + 1]);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) acc[db] = AMfma<T>::run(frag_tr(Ks, db * 32, kb * 32 + ks * 16, lane), df[ks], acc[db]);
+    }
+  }
+  if (!active || qi >= lq) return;
+  uint16_t* DQ = p.dq + (size_t)(q0 + qi) * p.lddq + h * DH;
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg)
+      store4<T>(DQ + db * 32 + rg * 8 + half * 4, acc[db][rg * 4] * p.scale, acc[db][rg * 4 + 1] * p.scale,
+                acc[db][rg * 4 + 2] * p.scale, acc[db][rg * 4 + 3] * p.scale);
+}
+
+// ---- backward: dK, dV -------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(ATT_THREADS) void attn_bwd_dkv_mfma_kernel(AttnP p) {
+  __shared__ __attribute__((aligned(16))) uint16_t Qs[CH * PT];
+  __shared__ __attribute__((aligned(16))) uint16_t Gs[CH * PT];
+  __shared__ __attribute__((aligned(16))) float Ls[CH];
+  __shared__ __attribute__((aligned(16))) float Ds[CH];
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;
+  const int kstart = blockIdx.x * 64;
+  if (kstart >= lk) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
+  const int kj0 = kstart + wave * 32;
+  const bool active = kj0 < lk;
+  const int kj = kj0 + (lane & 31);
+  const uint16_t* Q = p.q + (size_t)q0 * p.ldq + h * DH;
+  const uint16_t* G = p.d_o + (size_t)q0 * p.lddo + h * DH;
+  const uint16_t* O = p.o + (size_t)q0 * p.ldo + h * DH;
+  u32x4 kf[4], vf[4];
+  load_frags(kf, p.k + (size_t)k0 * p.ldk + h * DH, p.ldk, kj0, lk, lane);
+  load_frags(vf, p.v + (size_t)k0 * p.ldv + h * DH, p.ldv, kj0, lk, lane);
+  f32x16 ak[2], av[2];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) { ak[0][e] = ak[1][e] = av[0][e] = av[1][e] = 0.f; }
+  const int qbeg = p.causal ? kstart : 0;     // queries before the chunk's first key see none of its keys
+  for (int qc = qbeg; qc < lq; qc += CH) {
+    __syncthreads();
+    // stage Q and dO; the 8 threads that share a row also form delta = dO . O for it
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = threadIdx.x + ATT_THREADS * i;
+      const int r = v >> 3, c = (v & 7) * 8;
+      u32x4 xq = {0u, 0u, 0u, 0u}, xg = xq, xo = xq;
+      if (qc + r < lq) {
+        xq = *reinterpret_cast<const u32x4*>(Q + (size_t)(qc + r) * p.ldq + c);
+        xg = *reinterpret_cast<const u32x4*>(G + (size_t)(qc + r) * p.lddo + c);
+        xo = *reinterpret_cast<const u32x4*>(O + (size_t)(qc + r) * p.ldo + c);
+      }
+      *reinterpret_cast<u32x4*>(Qs + r * PT + c) = xq;
+      *reinterpret_cast<u32x4*>(Gs + r * PT + c) = xg;
+      float dl = dot8<T>(xg, xo);
+      dl += __shfl_xor(dl, 1, 64);
+      dl += __shfl_xor(dl, 2, 64);
+      dl += __shfl_xor(dl, 4, 64);
+      if ((v & 7) == 0) {
+        Ds[r] = dl;
+        Ls[r] = qc + r < lq ? p.lse[(size_t)h * p.total_q + q0 + qc + r] : 0.f;
+      }
+    }
+    __syncthreads();
+    if (!active) continue;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const int i0 = qc + qb * 32;
+      if (i0 >= lq) break;
+      if (p.causal && i0 + 31 < kj0) continue;       // every query of this block precedes every key of this wavefront
+      f32x16 s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        s = AMfma<T>::run(frag_direct(Qs, qb * 32, kk, lane), kf[kk], s);
+        dp = AMfma<T>::run(frag_direct(Gs, qb * 32, kk, lane), vf[kk], dp);
+      }
+      u32x4 pf[2], df[2];
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const int il = qb * 32 + rg * 8 + half * 4;
+        const float4 l4 = *reinterpret_cast<const float4*>(Ls + il);
+        const float4 d4 = *reinterpret_cast<const float4*>(Ds + il);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
+        float pr[4], dsv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = qc + il + e;
+          const bool ok = i < lq && kj < lk && (!p.causal || kj <= i);
+          pr[e] = ok ? __expf(s[rg * 4 + e] * p.scale - lv[e]) : 0.f;
+          dsv[e] = pr[e] * (dp[rg * 4 + e] - dv[e]);
+        }
+        pf[rg >> 1][(rg & 1) * 2] = AMfma<T>::pack2(pr[0], pr[1]);
+        pf[rg >> 1][(rg & 1) * 2 + 1] = AMfma<T>::pack2(pr[2], pr[3]);
+        df[rg >> 1][(rg & 1) * 2] = AMfma<T>::pack2(dsv[0], dsv[1]);
+        df[rg >> 1][(rg & 1) * 2 + 1] = AMfma<T>::pack2(dsv[2], dsv[3]);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          av[db] = AMfma<T>::run(frag_tr(Gs, db * 32, qb * 32 + ks * 16, lane), pf[ks], av[db]);
+          ak[db] = AMfma<T>::run(frag_tr(Qs, db * 32, qb * 32 + ks * 16, lane), df[ks], ak[db]);
+        }
+    }
+  }
+  if (!active || kj >= lk) return;
+  uint16_t* DK = p.dk + (size_t)(k0 + kj) * p.lddk + h * DH;
+  uint16_t* DV = p.dv + (size_t)(k0 + kj) * p.lddv + h * DH;
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+      store4<T>(DK + db * 32 + rg * 8 + half * 4, ak[db][rg * 4] * p.scale, ak[db][rg * 4 + 1] * p.scale, ak[db][rg * 4 + 2] * p.scale,
+                ak[db][rg * 4 + 3] * p.scale);
+      store4<T>(DV + db * 32 + rg * 8 + half * 4, av[db][rg * 4], av[db][rg * 4 + 1], av[db][rg * 4 + 2], av[db][rg * 4 + 3]);
+    }
+}
+
+static bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+bool attention_mfma_supported(const AttnArgs& a, bool bwd) {
+  if (a.dt != F16 && a.dt != BF16) return false;
+  if (a.dh != DH) return false;
+  if (a.ldq % 8 || a.ldk % 8 || a.ldv % 8 || a.ldo % 8) return false;
+  if (!al16(a.q) || !al16(a.k) || !al16(a.v) || !al16(a.o)) return false;
+  if (bwd) {
+    if (a.lddo % 8 || a.lddq % 8 || a.lddk % 8 || a.lddv % 8) return false;
+    if (!al16(a.d_o) || !al16(a.dq) || !al16(a.dk) || !al16(a.dv)) return false;
+  }
+  return true;
+}
+
+static AttnP make_params(const AttnArgs& a) {
+  AttnP p;
+  p.q = (const uint16_t*)a.q; p.k = (const uint16_t*)a.k; p.v = (const uint16_t*)a.v; p.o = (const uint16_t*)a.o;
+  p.d_o = (const uint16_t*)a.d_o; p.out = (uint16_t*)a.o; p.dq = (uint16_t*)a.dq; p.dk = (uint16_t*)a.dk; p.dv = (uint16_t*)a.dv;
+  p.ldq = a.ldq; p.ldk = a.ldk; p.ldv = a.ldv; p.ldo = a.ldo; p.lddo = a.lddo; p.lddq = a.lddq; p.lddk = a.lddk; p.lddv = a.lddv;
+  p.lse = a.lse; p.q_off = a.q_off; p.k_off = a.k_off; p.total_q = a.total_q; p.causal = a.causal;
+  p.scale = 1.f / sqrtf((float)a.dh);
+  return p;
+}
+
+void launch_attention_fwd_mfma(hipStream_t s, const AttnArgs& a) {
+  const AttnP p = make_params(a);
+  dim3 grid((a.max_lq + 63) / 64, a.H, a.B), block(ATT_THREADS);
+  if (a.dt == F16) hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t>), grid, block, 0, s, p);
+  else hipLaunchKernelGGL((attn_fwd_mfma_kernel<bf16_t>), grid, block, 0, s, p);
+}
+
+void launch_attention_bwd_mfma(hipStream_t s, const AttnArgs& a) {
+  const AttnP p = make_params(a);
+  dim3 gq((a.max_lq + 63) / 64, a.H, a.B), gk((a.max_lk + 63) / 64, a.H, a.B), block(ATT_THREADS);
+  if (a.dt == F16) {
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<half_t>), gq, block, 0, s, p);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<half_t>), gk, block, 0, s, p);
+  } else {
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<bf16_t>), gq, block, 0, s, p);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<bf16_t>), gk, block, 0, s, p);
+  }
+}
+
+}  // namespace tfm

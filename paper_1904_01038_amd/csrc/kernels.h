@@ -59,6 +59,9 @@ struct AttnArgs {
 };
 void launch_attention_fwd(hipStream_t s, const AttnArgs& a);
 void launch_attention_bwd(hipStream_t s, const AttnArgs& a);
+bool attention_mfma_supported(const AttnArgs& a, bool bwd);
+void launch_attention_fwd_mfma(hipStream_t s, const AttnArgs& a);
+void launch_attention_bwd_mfma(hipStream_t s, const AttnArgs& a);
 void launch_attention_fwd_naive(hipStream_t s, const AttnArgs& a);
 void launch_attention_bwd_naive(hipStream_t s, const AttnArgs& a);
 

@@ -97,7 +97,7 @@ void launch_residual_layernorm_fwd(hipStream_t s, int dt, const void* x, const v
 // Column partial sums (dgamma = sum dn xhat, dbeta = sum dn, dbias = sum dropout-backward(ds)) are kept in registers
 // while a wavefront walks its rows, combined across the block's 4 wavefronts in LDS, and written once per block to
 // partial[block][3][d]; a second kernel adds the partials in a fixed order.
-constexpr int LNB_MAX_BLOCKS = 512;
+constexpr int LNB_MAX_BLOCKS = 256;
 
 template <typename T, int NCH>
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(
@@ -182,17 +182,28 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(
   }
 }
 
-// out_k[j] = sum_p partial[p][k][j], p in a fixed order; k < nk <= 3.
+// out_k[j] = sum_p partial[p][k][j], p in a fixed order; k < nk <= 3.  One block owns 32 columns of one k: 8 row
+// lanes stride over the partials (coalesced 128-byte reads), then LDS combines the 8 lanes in a fixed order.
 template <typename T>
-__global__ void reduce_partials_kernel(const float* __restrict__ partial, int np, int nk, int n, T* o0, T* o1, T* o2) {
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= n) return;
-  for (int k = 0; k < nk; ++k) {
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int np, int nk, int n, T* o0, T* o1,
+                                                              T* o2) {
+  __shared__ float sh[8][32];
+  const int cx = threadIdx.x & 31, py = threadIdx.x >> 5;
+  const int k = blockIdx.y;
+  const int j = blockIdx.x * 32 + cx;
+  float acc = 0.f;
+  if (j < n)
+    for (int p = py; p < np; p += 8) acc += partial[((size_t)p * nk + k) * n + j];
+  sh[py][cx] = acc;
+  __syncthreads();
+  if (py == 0 && j < n) {
     T* o = k == 0 ? o0 : (k == 1 ? o1 : o2);
-    if (!o) continue;
-    float acc = 0.f;
-    for (int p = 0; p < np; ++p) acc += partial[((size_t)p * nk + k) * n + j];
-    o[j] = from_f<T>(acc);
+    if (o) {
+      float t = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t += sh[i][cx];
+      o[j] = from_f<T>(t);
+    }
   }
 }
 
@@ -217,7 +228,7 @@ static void ln_bwd_dispatch(hipStream_t s, const void* dn, const void* add, cons
                      inv_keep)
   if (nch <= 1) LN_BWD(1); else if (nch == 2) LN_BWD(2); else if (nch == 3) LN_BWD(3); else LN_BWD(4);
 #undef LN_BWD
-  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((d + 255) / 256), dim3(256), 0, s, (const float*)scratch, nb, 3, d,
+  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((d + 31) / 32, 3), dim3(256), 0, s, (const float*)scratch, nb, 3, d,
                      (T*)dgamma, (T*)dbeta, (T*)dbias);
 }
 
@@ -269,7 +280,7 @@ static void colsum_dispatch(hipStream_t s, const void* x, int ld, int rows, int 
   const int ny = (rows + CS_ROWS_PER_BLOCK - 1) / CS_ROWS_PER_BLOCK;
   dim3 grid((n + 64 * LN_VEC - 1) / (64 * LN_VEC), ny);
   hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, s, (const T*)x, ld, rows, n, (float*)scratch);
-  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((n + 255) / 256), dim3(256), 0, s, (const float*)scratch, ny, 1, n,
+  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((n + 31) / 32, 1), dim3(256), 0, s, (const float*)scratch, ny, 1, n,
                      (T*)out, (T*)nullptr, (T*)nullptr);
 }
 

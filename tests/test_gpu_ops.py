@@ -82,3 +82,55 @@ def test_gemm_random_values_close_to_float64(prec):
         got = out.double().cpu().numpy()
         tol = (2 ** -10 if prec == "fp16" else 2 ** -7) * np.abs(ref) + 1e-3
         assert np.all(np.abs(got - ref) <= tol), form
+
+
+ATTN_CASES = [  # (query lengths, key lengths or None for self-attention, causal)
+    ([5, 1, 33, 64], None, False),
+    ([5, 1, 33, 64, 65, 100], None, True),
+    ([7, 45, 80, 130], [9, 31, 97, 150], False),
+    ([200, 3], None, True),
+]
+
+
+@pytest.mark.parametrize("prec,dh", [("fp32", 16), ("fp32", 64), ("fp16", 64), ("bf16", 64), ("fp16", 32)])
+@pytest.mark.parametrize("case", ATTN_CASES)
+def test_attention_forward_backward(prec, dh, case):
+    import torch
+    import paper_1904_01038_amd as T
+    from oracle.transformer import attention_fwd, attention_bwd
+    lq, lk, causal = case
+    lk = lq if lk is None else lk
+    H = 3
+    d = H * dh
+    dt = _dtypes()[prec]
+    rng = np.random.default_rng(len(lq) * 100 + dh)
+    Tq, Tk = sum(lq), sum(lk)
+    # q, k, v live in one [T, 3d] buffer like the fused projection output when the lengths agree
+    q = _t(rng.normal(size=(Tq, d)), dt)
+    k = _t(rng.normal(size=(Tk, d)), dt)
+    v = _t(rng.normal(size=(Tk, d)), dt)
+    do = _t(rng.normal(size=(Tq, d)), dt)
+    q_off = torch.tensor(np.concatenate([[0], np.cumsum(lq)]), dtype=torch.int32).cuda()
+    k_off = torch.tensor(np.concatenate([[0], np.cumsum(lk)]), dtype=torch.int32).cuda()
+    o = torch.zeros(Tq, d, dtype=dt, device="cuda")
+    lse = torch.zeros(H, Tq, dtype=torch.float32, device="cuda")
+    T.ops.attention_fwd(q, k, v, o, lse, q_off, k_off, H, dh, max(lq), max(lk), causal)
+    dq, dk, dv = (torch.zeros_like(x) for x in (q, k, v))
+    T.ops.attention_bwd(q, k, v, o, do, lse, dq, dk, dv, q_off, k_off, H, dh, max(lq), max(lk), Tk, causal)
+    qd, kd, vd, dod = (x.double().cpu().numpy() for x in (q, k, v, do))
+    tol = {"fp32": 2e-5, "fp16": 4e-3, "bf16": 3e-2}[prec]
+    for b in range(len(lq)):
+        qs, ks = slice(int(q_off[b]), int(q_off[b + 1])), slice(int(k_off[b]), int(k_off[b + 1]))
+        ctx, cache = attention_fwd(qd[qs], kd[ks], vd[ks], H, causal)
+        rq, rk, rv = attention_bwd(dod[qs], cache)
+        for name, got, ref in [("o", o[qs], ctx), ("dq", dq[qs], rq), ("dk", dk[ks], rk), ("dv", dv[ks], rv)]:
+            got = got.double().cpu().numpy()
+            scale = max(1.0, float(np.abs(ref).max()))
+            assert np.abs(got - ref).max() <= tol * scale, (b, name, np.abs(got - ref).max(), scale)
+        # log-sum-exp of the scaled scores
+        for h in range(H):
+            s = qd[qs, h * dh:(h + 1) * dh] @ kd[ks, h * dh:(h + 1) * dh].T / np.sqrt(dh)
+            if causal:
+                s = np.where(np.arange(s.shape[1])[None, :] <= np.arange(s.shape[0])[:, None], s, -np.inf)
+            ref = np.log(np.exp(s - s.max(1, keepdims=True)).sum(1)) + s.max(1)
+            assert np.abs(lse[h, qs].cpu().numpy() - ref).max() <= max(tol, 1e-4) * 4
