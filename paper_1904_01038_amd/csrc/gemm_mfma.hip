@@ -1,15 +1,19 @@
 // MFMA GEMM for gfx950: C[M,N] = epilogue(op(A) op(B)), fp16 or bf16 operands, fp32 accumulation in the matrix
 // cores (v_mfma_f32_32x32x16_{f16,bf16}).
 //
-// Tiling: one 256-thread block (4 wavefronts of 64 lanes, 2x2) owns a 128x128 output tile and walks K in steps of
-// 64; each wavefront owns 64x64 = 2x2 MFMA tiles (64 fp32 accumulators per lane).  Global memory is read with
-// 16-byte loads into registers one K-step ahead of the math and staged through LDS.
+// Tiling: one 256-thread block (4 wavefronts of 64 lanes, 2x2) owns a BM x 128 output tile (BM = 128 or 256) and
+// walks K in steps of 32; each wavefront owns (BM/2) x 64 = (BM/64) x 2 MFMA tiles.
+//
+// Pipeline: global memory is read with 16-byte range-checked buffer loads (out-of-range rows read as zero, so
+// ragged M, N and K need no branches) into registers three K-steps ahead of the math; LDS is double buffered, so
+// one barrier per K-step separates the write of step k+1 from the MFMAs of step k.
 //
 // Operand layouts.  The MFMA wants, per lane, 8 consecutive k of one row.  An operand whose contraction index is
 // contiguous in memory (A of "NT"/"NN", B of "NT") is staged as [row][k] with a padded pitch and read back with
 // one ds_read_b128 per fragment.  An operand whose contraction index is the slow one (B of "NN", both of "TN")
 // is staged as it lies in memory, [k][row], and read back with the CDNA4 LDS transpose read ds_read_b64_tr_b16:
-// a 16-lane group reads a 4(k) x 16(row) patch and each lane receives the 4 k-values of one row.
+// a 16-lane group reads a 4(k) x 16(row) patch and each lane receives the 4 k-values of one row.  Both pitches
+// are chosen so that the 16 lanes served together hit 16 distinct 16-byte bank groups.
 //
 // The accumulators are produced transposed (the B fragment is fed as the MFMA's first operand), so that a lane
 // holds 4 consecutive columns of one output row and the epilogue (bias, ReLU, ReLU-mask, residual) moves 8 bytes
@@ -17,6 +21,8 @@
 //
 // Block ids are re-mapped so that each XCD (blocks are dealt round-robin to the 8 XCDs, each with its own L2)
 // works on a contiguous run of tiles and re-uses the A/B panels it has pulled into its L2.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -29,11 +35,15 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int PITCH_D = BK + 8;        // [row][k] staging: 144-byte rows, conflict-free 16-byte reads
-constexpr int PITCH_T = 128 + 16;      // [k][row] staging: 288-byte rows, 4 consecutive k-rows hit distinct banks
-constexpr int TILE_HALFS = 128 * PITCH_D;   // == 64 * PITCH_T == 9216
-static_assert(128 * PITCH_D == 64 * PITCH_T, "both stagings use the same LDS footprint");
+constexpr int BN = 128, BK = 32;
+constexpr int PITCH_D = BK + 8;                         // [row][k] staging: 80-byte rows
+constexpr uint32_t OOB = 0x80000000u;                   // beyond any buffer this kernel accepts: reads as zero
+
+template <int ROWS> struct Geom {
+  static constexpr int NV = ROWS * BK / 8 / 256;        // 16-byte vectors per thread per K-step
+  static constexpr int PITCH_T = ROWS + 32;             // [k][row] staging: row bytes = 64 (mod 256)
+  static constexpr int HALFS = (ROWS * PITCH_D > BK * PITCH_T) ? ROWS * PITCH_D : BK * PITCH_T;
+};
 
 template <typename T> struct Mfma;
 template <> struct Mfma<half_t> {
@@ -57,51 +67,75 @@ struct MfmaGemmParams {
   const uint16_t* mask;
   const uint16_t* residual;
   int tiles_n, tiles_total;
+  uint32_t a_bytes, b_bytes;                             // extents for the range-checked loads
 };
 
-// Loads the 4 16-byte vectors a thread contributes to one operand tile (zero outside the matrix).
-// TR == false: memory is [rows, K] (k contiguous);  TR == true: memory is [K, rows] (row index contiguous).
-template <bool TR>
-__device__ __forceinline__ void load_tile(const uint16_t* __restrict__ P, int ld, int row0, int nrows, int k0, int K, u32x4 (&r)[4]) {
+// Per-thread byte offsets of its vectors in K-step 0, and the K-step stride.
+// TR == false: memory [rows, K] (k contiguous);  TR == true: memory [K, rows] (row index contiguous).
+template <int ROWS, bool TR>
+struct Loader {
+  uint32_t off[Geom<ROWS>::NV];
+  int kvec[Geom<ROWS>::NV];        // direct layout: first k of the vector (for the K-tail test)
+  uint32_t step;
+  int K;
+  __device__ __forceinline__ void init(int ld, int row0, int K_) {
+    K = K_;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int v = threadIdx.x + 256 * i;
-    int row, k;
-    if (!TR) { row = row0 + (v >> 3); k = k0 + (v & 7) * 8; } else { k = k0 + (v >> 4); row = row0 + (v & 15) * 8; }
-    const bool ok = row < nrows && k < K;
-    const size_t off = TR ? (size_t)k * ld + row : (size_t)row * ld + k;
-    r[i] = ok ? *reinterpret_cast<const u32x4*>(P + off) : u32x4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < Geom<ROWS>::NV; ++i) {
+      const int v = threadIdx.x + 256 * i;
+      if (!TR) {
+        const int row = row0 + (v >> 2);
+        kvec[i] = (v & 3) * 8;
+        off[i] = ((uint32_t)row * (uint32_t)ld + (uint32_t)kvec[i]) * 2u;
+      } else {
+        const int k = v / (ROWS / 8), row = row0 + (v % (ROWS / 8)) * 8;
+        kvec[i] = 0;
+        off[i] = ((uint32_t)k * (uint32_t)ld + (uint32_t)row) * 2u;
+      }
+    }
+    step = TR ? (uint32_t)BK * (uint32_t)ld * 2u : (uint32_t)BK * 2u;
   }
-}
-template <bool TR>
-__device__ __forceinline__ void store_tile(uint16_t* __restrict__ S, const u32x4 (&r)[4]) {
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int kt, u32x4 (&r)[Geom<ROWS>::NV]) const {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int v = threadIdx.x + 256 * i;
-    const int off = TR ? (v >> 4) * PITCH_T + (v & 15) * 8 : (v >> 3) * PITCH_D + (v & 7) * 8;
-    *reinterpret_cast<u32x4*>(S + off) = r[i];
+    for (int i = 0; i < Geom<ROWS>::NV; ++i) {
+      uint32_t o = off[i] + (uint32_t)kt * step;
+      if (!TR) { if (kt * BK + kvec[i] >= K) o = OOB; }                // k-tail inside a row is not caught by the range check
+      else { if (kt * BK + (int)((threadIdx.x + 256 * i) / (ROWS / 8)) >= K) o = OOB; }
+      r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)o, 0, 0);
+    }
   }
-}
-// Fragment of rows r0..r0+31, k = kk*16 .. kk*16+15 of the staged tile: lane l gets row r0 + l%32, k-group l/32.
-template <bool TR>
-__device__ __forceinline__ u32x4 read_frag(const uint16_t* S, int r0, int kk, int lane) {
-  if (!TR) {
-    return *reinterpret_cast<const u32x4*>(S + (r0 + (lane & 31)) * PITCH_D + kk * 16 + (lane >> 5) * 8);
-  } else {
-    const int s = lane & 15, ibase = lane & 16, kb = kk * 16 + (lane >> 5) * 8;
-    const uint16_t* p = S + (kb + (s >> 2)) * PITCH_T + r0 + ibase + 4 * (s & 3);
-    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * PITCH_T));
-    const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-    return u32x4{l2[0], l2[1], h2[0], h2[1]};
+  static __device__ __forceinline__ void store(uint16_t* S, const u32x4 (&r)[Geom<ROWS>::NV]) {
+#pragma unroll
+    for (int i = 0; i < Geom<ROWS>::NV; ++i) {
+      const int v = threadIdx.x + 256 * i;
+      const int o = TR ? (v / (ROWS / 8)) * Geom<ROWS>::PITCH_T + (v % (ROWS / 8)) * 8 : (v >> 2) * PITCH_D + (v & 3) * 8;
+      *reinterpret_cast<u32x4*>(S + o) = r[i];
+    }
   }
-}
+  // Fragment of rows r0..r0+31, k = kk*16 .. kk*16+15 of the staged tile: lane l gets row r0 + l%32, k-group l/32.
+  static __device__ __forceinline__ u32x4 frag(const uint16_t* S, int r0, int kk, int lane) {
+    if (!TR) {
+      return *reinterpret_cast<const u32x4*>(S + (r0 + (lane & 31)) * PITCH_D + kk * 16 + (lane >> 5) * 8);
+    } else {
+      const int s = lane & 15, ibase = lane & 16, kb = kk * 16 + (lane >> 5) * 8;
+      const uint16_t* p = S + (kb + (s >> 2)) * Geom<ROWS>::PITCH_T + r0 + ibase + 4 * (s & 3);
+      typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * Geom<ROWS>::PITCH_T));
+      const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+      return u32x4{l2[0], l2[1], h2[0], h2[1]};
+    }
+  }
+};
 
-template <typename T, bool ATR, bool BTR>
+template <typename T, int BM, bool ATR, bool BTR>
 __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaGemmParams p) {
-  __shared__ __attribute__((aligned(16))) uint16_t As[TILE_HALFS];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[TILE_HALFS];
+  constexpr int PF = BM == 128 ? 3 : 2;                  // K-steps held in registers ahead of the math
+  constexpr int TM = BM / 64;                            // MFMA tiles per wavefront along M
+  typedef Loader<BM, ATR> LA;
+  typedef Loader<BN, BTR> LB;
+  __shared__ __attribute__((aligned(16))) uint16_t As[2][Geom<BM>::HALFS];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[2][Geom<BN>::HALFS];
   // XCD-aware tile order: hardware deals block b to XCD b % 8; give each XCD a contiguous run of tile ids
   int tile;
   {
@@ -111,39 +145,60 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaGemmParams p) {
   const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
 
-  f32x16 acc[2][2];
+  f32x16 acc[TM][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  u32x4 ra[4], rb[4];
-  load_tile<ATR>(p.A, p.lda, m0, p.M, 0, p.K, ra);
-  load_tile<BTR>(p.B, p.ldb, n0, p.N, 0, p.K, rb);
+  const __amdgpu_buffer_rsrc_t ra_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, p.a_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rb_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, p.b_bytes, 0x00020000);
+  LA la;
+  LB lb;
+  la.init(p.lda, m0, p.K);
+  lb.init(p.ldb, n0, p.K);
   const int nk = (p.K + BK - 1) / BK;
-  for (int kt = 0; kt < nk; ++kt) {
-    store_tile<ATR>(As, ra);
-    store_tile<BTR>(Bs, rb);
-    __syncthreads();
-    if (kt + 1 < nk) {
-      load_tile<ATR>(p.A, p.lda, m0, p.M, (kt + 1) * BK, p.K, ra);
-      load_tile<BTR>(p.B, p.ldb, n0, p.N, (kt + 1) * BK, p.K, rb);
+
+  u32x4 ra[PF][Geom<BM>::NV], rb[PF][Geom<BN>::NV];
+#pragma unroll
+  for (int u = 0; u < PF; ++u) { la.load(ra_rsrc, u, ra[u]); lb.load(rb_rsrc, u, rb[u]); }
+  LA::store(As[0], ra[0]);
+  LB::store(Bs[0], rb[0]);
+  la.load(ra_rsrc, PF, ra[0]);
+  lb.load(rb_rsrc, PF, rb[0]);
+  __syncthreads();
+
+  // The trip count is rounded up to a multiple of the prefetch depth: K-steps beyond K read zeros (range check), so
+  // the extra MFMAs add nothing and the loop body stays branch-free.
+  const int nk_pad = (nk + PF - 1) / PF * PF;
+  for (int base = 0; base < nk_pad; base += PF) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int kt = base + u;
+      const int slot = (u + 1) % PF;                     // registers holding K-step kt+1
+      const int cur = kt & 1;
+      LA::store(As[cur ^ 1], ra[slot]);
+      LB::store(Bs[cur ^ 1], rb[slot]);
+      la.load(ra_rsrc, kt + 1 + PF, ra[slot]);
+      lb.load(rb_rsrc, kt + 1 + PF, rb[slot]);
+      const uint16_t* as = As[cur];
+      const uint16_t* bs = Bs[cur];
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        u32x4 fa[TM], fb[2];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = LA::frag(as, wm * (BM / 2) + i * 32, kk, lane);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) fb[j] = LB::frag(bs, wn * 64 + j * 32, kk, lane);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = Mfma<T>::run(fb[j], fa[i], acc[i][j]);   // transposed product: D'[n][m]
+      }
+      __syncthreads();
     }
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      u32x4 fa[2], fb[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) fa[i] = read_frag<ATR>(As, wm * 64 + i * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) fb[j] = read_frag<BTR>(Bs, wn * 64 + j * 32, kk, lane);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = Mfma<T>::run(fb[j], fa[i], acc[i][j]);   // transposed product: D'[n][m]
-    }
-    __syncthreads();
   }
 
   // epilogue: lane owns row m, and for each (j, rg) 4 consecutive columns
@@ -152,8 +207,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaGemmParams p) {
   const T* res = reinterpret_cast<const T*>(p.residual);
   T* C = reinterpret_cast<T*>(p.C);
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int m = m0 + wm * 64 + i * 32 + (lane & 31);
+  for (int i = 0; i < TM; ++i) {
+    const int m = m0 + wm * (BM / 2) + i * 32 + (lane & 31);
     if (m >= p.M) continue;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -195,6 +250,9 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaGemmParams p) {
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+// bytes spanned by a [rows, width] view with row stride ld (elements of 2 bytes)
+static uint64_t extent_bytes(int rows, int width, int ld) { return ((uint64_t)(rows - 1) * ld + width) * 2ull; }
+
 bool gemm_mfma_supported(const GemmArgs& a) {
   if (a.dt != F16 && a.dt != BF16) return false;
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return false;
@@ -206,26 +264,44 @@ bool gemm_mfma_supported(const GemmArgs& a) {
   if (a.bias && !aligned16(a.bias)) return false;
   if (a.mask && !aligned16(a.mask)) return false;
   if (a.residual && !aligned16(a.residual)) return false;
+  // 32-bit byte offsets in the range-checked loads, including the rows of a ragged last tile
+  const uint64_t lim = 0x7f000000ull;
+  const uint64_t ea = a_tr ? extent_bytes(a.K + 4 * BK, a.M + 256, a.lda) : extent_bytes(a.M + 256, a.K + 4 * BK, a.lda);
+  const uint64_t eb = b_tr ? extent_bytes(a.K + 4 * BK, a.N + 256, a.ldb) : extent_bytes(a.N + 256, a.K + 4 * BK, a.ldb);
+  if (ea >= lim || eb >= lim) return false;
   return true;
 }
 
-template <typename T>
-static void gemm_mfma_dispatch(hipStream_t s, const GemmArgs& a) {
+template <typename T, int BM>
+static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   MfmaGemmParams p;
   p.M = a.M; p.N = a.N; p.K = a.K;
   p.A = (const uint16_t*)a.A; p.lda = a.lda; p.B = (const uint16_t*)a.B; p.ldb = a.ldb; p.C = (uint16_t*)a.C; p.ldc = a.ldc;
   p.bias = (const uint16_t*)a.bias; p.relu = a.relu; p.mask = (const uint16_t*)a.mask; p.residual = (const uint16_t*)a.residual;
   p.tiles_n = (a.N + BN - 1) / BN;
   p.tiles_total = p.tiles_n * ((a.M + BM - 1) / BM);
+  p.a_bytes = (uint32_t)(a.form == 2 ? extent_bytes(a.K, a.M, a.lda) : extent_bytes(a.M, a.K, a.lda));
+  p.b_bytes = (uint32_t)(a.form == 0 ? extent_bytes(a.N, a.K, a.ldb) : extent_bytes(a.K, a.N, a.ldb));
   dim3 grid(p.tiles_total), block(256);
-  if (a.form == 0) hipLaunchKernelGGL((gemm_mfma_kernel<T, false, false>), grid, block, 0, s, p);
-  else if (a.form == 1) hipLaunchKernelGGL((gemm_mfma_kernel<T, false, true>), grid, block, 0, s, p);
-  else hipLaunchKernelGGL((gemm_mfma_kernel<T, true, true>), grid, block, 0, s, p);
+  if (a.form == 0) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, false, false>), grid, block, 0, s, p);
+  else if (a.form == 1) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, false, true>), grid, block, 0, s, p);
+  else hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, true, true>), grid, block, 0, s, p);
+}
+
+// 256-row tiles halve the B-panel traffic per flop; they pay off once there are enough of them to fill the chip.
+static int forced_bm() {                                 // tuning aid: TFM_GEMM_BM=128|256 overrides the choice
+  static int v = -1;
+  if (v < 0) { const char* e = getenv("TFM_GEMM_BM"); v = e ? atoi(e) : 0; }
+  return v;
 }
 
 void launch_gemm_mfma(hipStream_t s, const GemmArgs& a) {
-  if (a.dt == F16) gemm_mfma_dispatch<half_t>(s, a);
-  else gemm_mfma_dispatch<bf16_t>(s, a);
+  int bm = 128;
+  const long tiles256 = (long)((a.M + 255) / 256) * ((a.N + BN - 1) / BN);
+  if (tiles256 >= 400) bm = 256;
+  if (forced_bm() == 128 || forced_bm() == 256) bm = forced_bm();
+  if (a.dt == F16) { if (bm == 256) gemm_mfma_launch<half_t, 256>(s, a); else gemm_mfma_launch<half_t, 128>(s, a); }
+  else { if (bm == 256) gemm_mfma_launch<bf16_t, 256>(s, a); else gemm_mfma_launch<bf16_t, 128>(s, a); }
 }
 
 }  // namespace tfm
