@@ -155,6 +155,13 @@ int tfm_op_gemm(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K, co
                 const void* B, int32_t ldb, void* C, int32_t ldc, const void* bias, int32_t relu,
                 const void* mask, const void* residual, void* stream);
 
+/* Same as tfm_op_gemm with a caller-owned fp32 device workspace.  With it the "TN" form without epilogue may split K
+ * across blocks when the output has few tiles (weight gradients); partial tiles are added in a fixed order, so the
+ * result stays reproducible.  workspace may be NULL (then identical to tfm_op_gemm). */
+int tfm_op_gemm_ws(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K, const void* A, int32_t lda,
+                   const void* B, int32_t ldb, void* C, int32_t ldc, const void* bias, int32_t relu,
+                   const void* mask, const void* residual, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Multi-head attention over packed sentences.  q rows of sentence b are q_off[b]..q_off[b+1], keys/values
  * k_off[b]..k_off[b+1] (device int32 [B+1]).  Head h uses columns h*dh..(h+1)*dh.  o = softmax(q k^T/sqrt(dh)
  * [+ causal mask]) v; lse (device fp32 [H, q_off[B]]) receives the row log-sum-exp of the scaled scores. */

@@ -40,6 +40,8 @@ struct GemmArgs {
   int relu;
   const void* mask;          // [M, N] stride ldc or null: multiply by (mask > 0)
   const void* residual;      // [M, N] stride ldc or null: added last (must not alias C)
+  void* splitk_ws = nullptr; // optional fp32 workspace that allows split-K for small weight-gradient outputs
+  size_t splitk_ws_bytes = 0;
 };
 void launch_gemm(hipStream_t s, const GemmArgs& a);
 bool gemm_mfma_supported(const GemmArgs& a);

@@ -87,7 +87,8 @@ struct tfm_ctx {
   void *demb[2];           // gradient w.r.t. the embedding output of the encoder / decoder stream
   void *y, *dcur, *dsA, *dsB, *dy, *dctx, *dinter, *dq, *dkv, *dmemA, *dmemB, *logits;
   float *loss_rows, *nll_rows, *pe;
-  void *red_scratch, *scan_scratch;
+  void *red_scratch, *scan_scratch, *splitk_ws;
+  size_t splitk_bytes;
   int *labels, *uniq, *ustart, *uentries, *ibase;   // device ints (ibase = start of the int block)
   size_t int_block_ints;
   // host staging
@@ -264,6 +265,8 @@ size_t carve(tfm_ctx* c, char* base) {
   const size_t red = std::max(layernorm_bwd_scratch_bytes((int)R, (int)d), colsum_scratch_bytes((int)R, (int)wide));
   c->red_scratch = a.take(red);
   c->scan_scratch = a.take(scan_scratch_bytes(c->P));
+  c->splitk_bytes = c->dt == F32 ? 0 : (size_t)8 * 128 * 128 * 128 * sizeof(float);   // 8 slices of up to 128 tiles
+  c->splitk_ws = c->splitk_bytes ? a.take(c->splitk_bytes) : nullptr;
   // one block of ints, filled by a single host-to-device copy per step:
   // enc ids, pos [R each], off [B+1]; dec ids, pos, off; labels [R]; uniq [2R], ustart [2R+1], uentries [2R]
   const size_t Bc = (size_t)cf.max_sentences + 1;
@@ -312,6 +315,8 @@ void gemm(tfm_ctx* c, int form, int M, int N, int K, const void* A, int lda, con
           const void* bias = nullptr, int relu = 0, const void* mask = nullptr, const void* residual = nullptr) {
   if (M <= 0 || N <= 0) return;
   GemmArgs a{c->dt, form, M, N, K, A, lda, B, ldb, C, ldc, bias, relu, mask, residual};
+  a.splitk_ws = c->splitk_ws;
+  a.splitk_ws_bytes = c->splitk_bytes;
   run(c, TFM_PROF_GEMM, 2.0 * M * N * K, 0.0, [&] { launch_gemm(c->stream, a); });
 }
 
@@ -889,6 +894,18 @@ int tfm_op_gemm(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K, co
   if (dtype < 0 || dtype > 2 || form < 0 || form > 2 || M < 0 || N < 0 || K < 0 || !A || !B || !C) return TFM_EINVAL;
   if (lda < (form == 2 ? M : K) || ldb < (form == 0 ? K : N) || ldc < N) return TFM_EINVAL;
   GemmArgs a{dtype, form, M, N, K, A, lda, B, ldb, C, ldc, bias, relu, mask, residual};
+  launch_gemm((hipStream_t)stream, a);
+  return op_done();
+}
+
+int tfm_op_gemm_ws(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K, const void* A, int32_t lda, const void* B,
+                   int32_t ldb, void* C, int32_t ldc, const void* bias, int32_t relu, const void* mask, const void* residual,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  if (dtype < 0 || dtype > 2 || form < 0 || form > 2 || M < 0 || N < 0 || K < 0 || !A || !B || !C) return TFM_EINVAL;
+  if (lda < (form == 2 ? M : K) || ldb < (form == 0 ? K : N) || ldc < N) return TFM_EINVAL;
+  GemmArgs a{dtype, form, M, N, K, A, lda, B, ldb, C, ldc, bias, relu, mask, residual};
+  a.splitk_ws = workspace;
+  a.splitk_ws_bytes = workspace ? workspace_bytes : 0;
   launch_gemm((hipStream_t)stream, a);
   return op_done();
 }

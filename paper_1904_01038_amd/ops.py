@@ -23,10 +23,16 @@ def _check(rc, what):
         raise TfmError(rc, what + " failed")
 
 
-def gemm(form, A, B, C_out, M, N, K, lda=None, ldb=None, ldc=None, bias=None, relu=False, mask=None, residual=None):
+def gemm(form, A, B, C_out, M, N, K, lda=None, ldb=None, ldc=None, bias=None, relu=False, mask=None, residual=None,
+         workspace=None):
     lda = A.stride(0) if lda is None else lda
     ldb = B.stride(0) if ldb is None else ldb
     ldc = C_out.stride(0) if ldc is None else ldc
+    if workspace is not None:
+        _check(lib().tfm_op_gemm_ws(_dt(A), form, M, N, K, _p(A), lda, _p(B), ldb, _p(C_out), ldc, _p(bias), int(relu),
+                                    _p(mask), _p(residual), _p(workspace), workspace.numel() * workspace.element_size(),
+                                    _stream()), "tfm_op_gemm_ws")
+        return
     _check(lib().tfm_op_gemm(_dt(A), form, M, N, K, _p(A), lda, _p(B), ldb, _p(C_out), ldc, _p(bias), int(relu),
                              _p(mask), _p(residual), _stream()), "tfm_op_gemm")
 

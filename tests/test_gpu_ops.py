@@ -65,6 +65,34 @@ def test_gemm_forms_and_epilogues(prec, form, shape):
 
 
 @pytest.mark.parametrize("prec", ["fp16", "bf16"])
+@pytest.mark.parametrize("shape", [(256, 128, 1100), (1024, 1024, 3041), (136, 264, 4000), (384, 128, 1024)])
+def test_gemm_split_k_weight_gradient_is_exact_and_reproducible(prec, shape):
+    import torch
+    import paper_1904_01038_amd as T
+    M, N, K = shape
+    dt = _dtypes()[prec]
+    rng = np.random.default_rng(K)
+    A = rng.integers(-2, 3, (K, M)).astype(np.float64)         # "TN": A is [K, M]
+    B = rng.integers(-2, 3, (K, N)).astype(np.float64)
+    ref = A.T @ B
+    assert np.abs(ref).max() < 2048
+    tA, tB = _t(A, dt), _t(B, dt)
+    ws = torch.empty(8 * 128 * 128 * 128, dtype=torch.float32, device="cuda")
+    outs = []
+    for _ in range(2):
+        out = torch.zeros(M, N, dtype=dt, device="cuda")
+        T.ops.gemm(2, tA, tB, out, M, N, K, workspace=ws)
+        outs.append(out.float().cpu().numpy().astype(np.float64))
+    want = _t(ref, dt).float().cpu().numpy().astype(np.float64)
+    assert np.array_equal(outs[0], want)
+    assert np.array_equal(outs[0], outs[1])
+    small = torch.empty(16, dtype=torch.float32, device="cuda")   # a workspace that is too small falls back to one slice
+    out = torch.zeros(M, N, dtype=dt, device="cuda")
+    T.ops.gemm(2, tA, tB, out, M, N, K, workspace=small)
+    assert np.array_equal(out.float().cpu().numpy().astype(np.float64), want)
+
+
+@pytest.mark.parametrize("prec", ["fp16", "bf16"])
 def test_gemm_random_values_close_to_float64(prec):
     import torch
     import paper_1904_01038_amd as T
