@@ -87,9 +87,16 @@ void launch_sum_rows(hipStream_t s, const float* loss_rows, const float* nll_row
 void launch_embed_fwd(hipStream_t s, int dt, const void* E, const int* ids, const int* pos, const float* pe, void* out,
                       int rows, int d, uint64_t key, float p);
 // Adds sqrt(d) * dropout-backward(dx) of every occurrence of a token to its row of the embedding gradient.
-// uniq[u] = token id, start[u]..start[u+1] index `entries`; an entry is (stream << 30) | row.
-void launch_embed_bwd(hipStream_t s, int dt, void* gE, const int* uniq, const int* start, const int* entries, int n_uniq,
-                      const void* dx0, const void* dx1, int d, uint64_t key0, uint64_t key1, float p);
+// The host supplies occurrence lists cut into segments (see embed.hip); an entry is (stream << 30) | row.
+constexpr int EMB_SEG = 32;
+struct EmbedBwdArgs {
+  int dt; void* gE; float* partial;                  // partial: fp32 [rows of multi-segment tokens, d]
+  const int *seg_tok, *seg_beg, *seg_end, *seg_dst;  // per segment: token, entry range, partial row or -1
+  const int* entries; int n_seg;
+  const int *mt_tok, *mt_row0, *mt_n; int n_multi;   // per multi-segment token: token, first partial row, count
+  const void *dx0, *dx1; int d; uint64_t key0, key1; float p;
+};
+void launch_embed_bwd(hipStream_t s, const EmbedBwdArgs& a);
 
 size_t scan_scratch_bytes(int64_t n);
 // flag/sumsq of x[n] -> result[0], result[1] (fp32) and, if st != null, st->scan_flag / scan_sumsq and

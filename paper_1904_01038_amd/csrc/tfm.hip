@@ -89,7 +89,9 @@ struct tfm_ctx {
   float *loss_rows, *nll_rows, *pe;
   void *red_scratch, *scan_scratch, *splitk_ws;
   size_t splitk_bytes;
-  int *labels, *uniq, *ustart, *uentries, *ibase;   // device ints (ibase = start of the int block)
+  int *labels, *uentries, *ibase;                   // device ints (ibase = start of the int block)
+  int *seg_tok, *seg_beg, *seg_end, *seg_dst, *mt_tok, *mt_row0, *mt_n;
+  float* emb_partial;
   size_t int_block_ints;
   // host staging
   int* stage[STAGE_SLOTS];
@@ -97,6 +99,7 @@ struct tfm_ctx {
   bool stage_used[STAGE_SLOTS];
   int stage_next;
   std::vector<int> count;  // counting sort over the vocabulary
+  std::vector<int> uniq, ustart;
   // window state (host mirror of what the host itself decides)
   int window_mb;
   long long window_tokens;
@@ -268,16 +271,21 @@ size_t carve(tfm_ctx* c, char* base) {
   c->splitk_bytes = c->dt == F32 ? 0 : (size_t)8 * 128 * 128 * 128 * sizeof(float);   // 8 slices of up to 128 tiles
   c->splitk_ws = c->splitk_bytes ? a.take(c->splitk_bytes) : nullptr;
   // one block of ints, filled by a single host-to-device copy per step:
-  // enc ids, pos [R each], off [B+1]; dec ids, pos, off; labels [R]; uniq [2R], ustart [2R+1], uentries [2R]
+  // enc ids, pos [R each], off [B+1]; dec ids, pos, off; labels [R]; occurrence entries [2R];
+  // segments: tok, beg, end, dst [NS each]; multi-segment tokens: tok, row0, n [NM each]
   const size_t Bc = (size_t)cf.max_sentences + 1;
-  c->int_block_ints = 2 * (2 * R + Bc) + R + 2 * R + (2 * R + 1) + 2 * R;
+  const size_t NS = 2 * R + 2 * R / EMB_SEG + 2, NM = 2 * R / EMB_SEG + 2;
+  c->emb_partial = (float*)a.take((2 * NM) * d * sizeof(float));
+  c->int_block_ints = 2 * (2 * R + Bc) + R + 2 * R + 4 * NS + 3 * NM;
   c->ibase = (int*)a.take(c->int_block_ints * 4);
   int* p = c->ibase;
   auto nxt = [&](size_t n) { int* r = base ? p : nullptr; p += n; return r; };
   c->enc.ids = nxt(R); c->enc.pos = nxt(R); c->enc.off = nxt(Bc);
   c->dec.ids = nxt(R); c->dec.pos = nxt(R); c->dec.off = nxt(Bc);
   c->labels = nxt(R);
-  c->uniq = nxt(2 * R); c->ustart = nxt(2 * R + 1); c->uentries = nxt(2 * R);
+  c->uentries = nxt(2 * R);
+  c->seg_tok = nxt(NS); c->seg_beg = nxt(NS); c->seg_end = nxt(NS); c->seg_dst = nxt(NS);
+  c->mt_tok = nxt(NM); c->mt_row0 = nxt(NM); c->mt_n = nxt(NM);
   return (a.off + 255) & ~(size_t)255;
 }
 
@@ -752,7 +760,10 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   int* e_ids = hb; int* e_pos = e_ids + R; int* e_off = e_pos + R;
   int* d_ids = e_off + Bc; int* d_pos = d_ids + R; int* d_off = d_pos + R;
   int* labels = d_off + Bc;
-  int* uniq = labels + R; int* ustart = uniq + 2 * R; int* uent = ustart + 2 * R + 1;
+  const size_t NS = 2 * R + 2 * R / EMB_SEG + 2, NM = 2 * R / EMB_SEG + 2;
+  int* uent = labels + R;
+  int* seg_tok = uent + 2 * R; int* seg_beg = seg_tok + NS; int* seg_end = seg_beg + NS; int* seg_dst = seg_end + NS;
+  int* mt_tok = seg_dst + NS; int* mt_row0 = mt_tok + NM; int* mt_n = mt_row0 + NM;
   StepCtx s{c};
   s.B = B; s.Ts = (int)Ts; s.Tt = (int)Tt; s.step = c->train_steps;
   s.tlen.assign(tgt_lens, tgt_lens + B);
@@ -778,9 +789,13 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   }
   d_off[B] = r;
   // token -> occurrences (counting sort over the vocabulary; order: encoder rows, then decoder rows, ascending)
-  int nu = 0;
+  int nu = 0, n_seg = 0, n_multi = 0;
   {
     std::vector<int>& cnt = c->count;
+    c->uniq.resize(2 * R + 1);
+    c->ustart.resize(2 * R + 2);
+    int* uniq = c->uniq.data();
+    int* ustart = c->ustart.data();
     for (int i = 0; i < (int)Ts; ++i) if (cnt[e_ids[i]]++ == 0) uniq[nu++] = e_ids[i];
     for (int i = 0; i < (int)Tt; ++i) if (cnt[d_ids[i]]++ == 0) uniq[nu++] = d_ids[i];
     std::sort(uniq, uniq + nu);
@@ -790,6 +805,19 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
     for (int i = 0; i < (int)Ts; ++i) uent[cnt[e_ids[i]]++] = i;
     for (int i = 0; i < (int)Tt; ++i) uent[cnt[d_ids[i]]++] = (1 << 30) | i;
     for (int u = 0; u < nu; ++u) cnt[uniq[u]] = 0;
+    // cut every token's occurrence list into segments of at most EMB_SEG entries
+    int prow = 0;
+    for (int u = 0; u < nu; ++u) {
+      const int b0 = ustart[u], e0 = ustart[u + 1], ns = (e0 - b0 + EMB_SEG - 1) / EMB_SEG;
+      if (ns > 1) { mt_tok[n_multi] = uniq[u]; mt_row0[n_multi] = prow; mt_n[n_multi] = ns; ++n_multi; }
+      for (int k = 0; k < ns; ++k) {
+        seg_tok[n_seg] = uniq[u];
+        seg_beg[n_seg] = b0 + k * EMB_SEG;
+        seg_end[n_seg] = std::min(e0, b0 + (k + 1) * EMB_SEG);
+        seg_dst[n_seg] = ns > 1 ? prow++ : -1;
+        ++n_seg;
+      }
+    }
   }
   HIP_TRY(c, hipMemcpyAsync(c->ibase, hb, c->int_block_ints * 4, hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipEventRecord(c->stage_ev[slot], c->stream));
@@ -827,8 +855,13 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   void* denc = nullptr;
   if (has_enc) denc = stream_bwd(s, c->enc, &dmem_cur, &dmem_other, &dmem_valid, dmem_cur);
   run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * d * ((double)Ts + Tt + 2.0 * nu), [&] {
-    launch_embed_bwd(c->stream, c->dt, c->g, c->uniq, c->ustart, c->uentries, nu, denc, ddec, d, site_key(s, 0, -1, 0),
-                     site_key(s, 1, -1, 0), cf.dropout);
+    EmbedBwdArgs ea{};
+    ea.dt = c->dt; ea.gE = c->g; ea.partial = c->emb_partial;
+    ea.seg_tok = c->seg_tok; ea.seg_beg = c->seg_beg; ea.seg_end = c->seg_end; ea.seg_dst = c->seg_dst;
+    ea.entries = c->uentries; ea.n_seg = n_seg;
+    ea.mt_tok = c->mt_tok; ea.mt_row0 = c->mt_row0; ea.mt_n = c->mt_n; ea.n_multi = n_multi;
+    ea.dx0 = denc; ea.dx1 = ddec; ea.d = d; ea.key0 = site_key(s, 0, -1, 0); ea.key1 = site_key(s, 1, -1, 0); ea.p = cf.dropout;
+    launch_embed_bwd(c->stream, ea);
   });
 
   // ---- inf/nan scan of this sub-batch's gradient (+ accumulation from the second sub-batch on)
