@@ -114,29 +114,46 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(
 #pragma unroll
     for (int i = 0; i < LN_VEC; ++i) ag[c][i] = ab[c][i] = ac[c][i] = 0.f;
   }
-  for (int row = blockIdx.x * 4 + w; row < rows; row += gridDim.x * 4) {
+  // The next row's operands are fetched into registers before the current row's reductions, so a wavefront always has
+  // a full row of loads in flight.
+  float a[NCH][LN_VEC], b[NCH][LN_VEC], t[NCH][LN_VEC];
+  const int rstep = gridDim.x * 4;
+  int row = blockIdx.x * 4 + w;
+  auto fetch = [&](int r, float (&fa)[NCH][LN_VEC], float (&fb)[NCH][LN_VEC], float (&ft)[NCH][LN_VEC]) {
+    const size_t base = (size_t)r * d;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int col = (lane + 64 * c) * LN_VEC;
+      if (col < d) {
+        load_f<T, LN_VEC>(dn + base + col, fa[c]);
+        load_f<T, LN_VEC>(sres + base + col, fb[c]);
+        if (add) load_f<T, LN_VEC>(add + base + col, ft[c]);
+      }
+    }
+  };
+  if (row < rows) fetch(row, a, b, t);
+  for (; row < rows; row += rstep) {
     const size_t base = (size_t)row * d;
     const float mu = mean[row], rs = rstd[row];
-    float xh[NCH][LN_VEC], dxh[NCH][LN_VEC];
+    float xh[NCH][LN_VEC], dxh[NCH][LN_VEC], tt[NCH][LN_VEC];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
       const int col = (lane + 64 * c) * LN_VEC;
       if (col < d) {
-        float a[LN_VEC], b[LN_VEC];
-        load_f<T, LN_VEC>(dn + base + col, a);
-        load_f<T, LN_VEC>(sres + base + col, b);
 #pragma unroll
         for (int i = 0; i < LN_VEC; ++i) {
-          xh[c][i] = (b[i] - mu) * rs;
-          dxh[c][i] = a[i] * g[c][i];
+          xh[c][i] = (b[c][i] - mu) * rs;
+          dxh[c][i] = a[c][i] * g[c][i];
           s1 += dxh[c][i];
           s2 += dxh[c][i] * xh[c][i];
-          ag[c][i] += a[i] * xh[c][i];
-          ab[c][i] += a[i];
+          ag[c][i] += a[c][i] * xh[c][i];
+          ab[c][i] += a[c][i];
+          tt[c][i] = t[c][i];
         }
       }
     }
+    if (row + rstep < rows) fetch(row + rstep, a, b, t);
     const float c1 = wave_sum(s1) / (float)d, c2 = wave_sum(s2) / (float)d;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
@@ -146,10 +163,8 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(
 #pragma unroll
         for (int i = 0; i < LN_VEC; ++i) o[i] = rs * (dxh[c][i] - c1 - xh[c][i] * c2);
         if (add) {
-          float t[LN_VEC];
-          load_f<T, LN_VEC>(add + base + col, t);
 #pragma unroll
-          for (int i = 0; i < LN_VEC; ++i) o[i] += t[i];
+          for (int i = 0; i < LN_VEC; ++i) o[i] += tt[c][i];
         }
         store_f<T, LN_VEC>(ds + base + col, o);
         if (thr) {
@@ -192,8 +207,17 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
   const int k = blockIdx.y;
   const int j = blockIdx.x * 32 + cx;
   float acc = 0.f;
-  if (j < n)
-    for (int p = py; p < np; p += 8) acc += partial[((size_t)p * nk + k) * n + j];
+  if (j < n) {
+    int p = py;
+    for (; p + 56 < np; p += 64) {                      // 8 loads in flight per thread; the order of the adds is fixed
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = partial[((size_t)(p + 8 * u) * nk + k) * n + j];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; p < np; p += 8) acc += partial[((size_t)p * nk + k) * n + j];
+  }
   sh[py][cx] = acc;
   __syncthreads();
   if (py == 0 && j < n) {

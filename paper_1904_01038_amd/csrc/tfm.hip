@@ -110,6 +110,7 @@ struct tfm_ctx {
   std::vector<ProfRec> recs;
   std::vector<hipEvent_t> ev_pool;
   tfm_prof_entry prof_acc[TFM_PROF_CLASSES];
+  float prof_overhead_ms;  // elapsed time of an empty event pair, subtracted from every bracket
 };
 
 namespace {
@@ -308,6 +309,8 @@ void prof_collect(tfm_ctx* c) {
   for (ProfRec& r : c->recs) {
     float ms = 0.f;
     hipEventElapsedTime(&ms, r.a, r.b);
+    ms -= c->prof_overhead_ms;
+    if (ms < 0.f) ms = 0.f;
     tfm_prof_entry& e = c->prof_acc[r.cls];
     e.launches += 1; e.ms += ms; e.flops += r.flops; e.bytes += r.bytes;
     c->ev_pool.push_back(r.a); c->ev_pool.push_back(r.b);
@@ -513,6 +516,26 @@ int tfm_debug_set_loss_multiplier(tfm_ctx* c, float mult) {
 int tfm_profile_enable(tfm_ctx* c, int32_t on) {
   if (!c) return TFM_EINVAL;
   c->prof = on != 0;
+  if (c->prof) {
+    // calibrate: the time between two events recorded back to back is bracket overhead, not kernel time
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    std::vector<float> t;
+    hipEvent_t a, b;
+    HIP_TRY(c, hipEventCreate(&a));
+    HIP_TRY(c, hipEventCreate(&b));
+    for (int i = 0; i < 33; ++i) {
+      HIP_TRY(c, hipEventRecord(a, c->stream));
+      HIP_TRY(c, hipEventRecord(b, c->stream));
+      HIP_TRY(c, hipEventSynchronize(b));
+      float ms = 0.f;
+      HIP_TRY(c, hipEventElapsedTime(&ms, a, b));
+      t.push_back(ms);
+    }
+    std::sort(t.begin(), t.end());
+    c->prof_overhead_ms = t[t.size() / 2];
+    c->ev_pool.push_back(a);
+    c->ev_pool.push_back(b);
+  }
   return TFM_OK;
 }
 
