@@ -1,21 +1,12 @@
 // Chooses, per call, between the MFMA kernels and the shape-agnostic vector-ALU kernels.
-#include <stdlib.h>
-
 #include "kernels.h"
 #include "common.h"
 
 namespace tfm {
 
-static int env_flag(const char* name) {
-  const char* e = getenv(name);
-  return e ? atoi(e) : 0;
-}
-
 void launch_gemm(hipStream_t s, const GemmArgs& a) {
-  static const int use_dma = env_flag("TFM_GEMM_DMA");
-  if (!gemm_mfma_supported(a)) { launch_gemm_naive(s, a); return; }
-  if (use_dma && a.form == 0) launch_gemm_nt_dma(s, a);
-  else launch_gemm_mfma(s, a);
+  if (gemm_mfma_supported(a)) launch_gemm_mfma(s, a);
+  else launch_gemm_naive(s, a);
 }
 
 void launch_attention_fwd(hipStream_t s, const AttnArgs& a) {

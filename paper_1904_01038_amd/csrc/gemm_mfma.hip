@@ -1,26 +1,30 @@
 // MFMA GEMM for gfx950: C[M,N] = epilogue(op(A) op(B)), fp16 or bf16 operands, fp32 accumulation in the matrix
 // cores (v_mfma_f32_32x32x16_{f16,bf16}).
 //
-// Tiling: one 256-thread block (4 wavefronts of 64 lanes, 2x2) owns a BM x 128 output tile (BM = 128 or 256) and
-// walks K in steps of 32; each wavefront owns (BM/2) x 64 = (BM/64) x 2 MFMA tiles.
+// Measured on MI355X, what bounds these GEMMs is neither the matrix pipe nor LDS but the rate at which tiles can
+// be pulled from L2 into the CUs (about 8 TB/s in aggregate), so the design minimises bytes fetched per flop and
+// keeps the fetch path as cheap as possible:
 //
-// Pipeline: global memory is read with 16-byte range-checked buffer loads (out-of-range rows read as zero, so
-// ragged M, N and K need no branches) into registers three K-steps ahead of the math; LDS is double buffered, so
-// one barrier per K-step separates the write of step k+1 from the MFMAs of step k.
-//
-// Operand layouts.  The MFMA wants, per lane, 8 consecutive k of one row.  An operand whose contraction index is
-// contiguous in memory (A of "NT"/"NN", B of "NT") is staged as [row][k] with a padded pitch and read back with
-// one ds_read_b128 per fragment.  An operand whose contraction index is the slow one (B of "NN", both of "TN")
-// is staged as it lies in memory, [k][row], and read back with the CDNA4 LDS transpose read ds_read_b64_tr_b16:
-// a 16-lane group reads a 4(k) x 16(row) patch and each lane receives the 4 k-values of one row.  Both pitches
-// are chosen so that the 16 lanes served together hit 16 distinct 16-byte bank groups.
-//
-// The accumulators are produced transposed (the B fragment is fed as the MFMA's first operand), so that a lane
-// holds 4 consecutive columns of one output row and the epilogue (bias, ReLU, ReLU-mask, residual) moves 8 bytes
-// per access.
-//
-// Block ids are re-mapped so that each XCD (blocks are dealt round-robin to the 8 XCDs, each with its own L2)
-// works on a contiguous run of tiles and re-uses the A/B panels it has pulled into its L2.
+//  * Tiles: BM x BN output tile per block, K walked in steps of 32.  128x128 (4 wavefronts, 64x64 each) for outputs
+//    with few tiles, 256x256 (8 wavefronts, 128x64 each) for large outputs: a 256x256 tile fetches half as many
+//    bytes per flop as a 128x128 one.
+//  * Fetch: CDNA4 direct-to-LDS buffer loads (buffer_load_dwordx4 ... lds): no staging registers and no ds_write on
+//    the load path; range-checked, so ragged M, N, K read zeros without branches.  A 3-stage LDS ring keeps two
+//    K-steps in flight; one barrier per K-step.  The loads are issued as assembly and tracked with s_waitcnt vmcnt by
+//    hand, because the compiler would otherwise drain every outstanding direct-to-LDS load before each LDS read.
+//  * LDS layout: unpadded tiles (the direct-to-LDS path writes 1 KB per wavefront contiguously), XOR-swizzled on the
+//    global-address side so that fragment reads are bank-conflict free.  An operand whose contraction index is
+//    contiguous in memory (A of "NT"/"NN", B of "NT") is staged [row][k] and read with ds_read_b128; an operand
+//    whose contraction index is the slow one (B of "NN", both of "TN") is staged as it lies, [k][row], and read with
+//    the LDS transpose read ds_read_b64_tr_b16 (a 16-lane group reads a 4(k) x 16(row) patch, each lane receives
+//    the 4 k-values of one row).
+//  * Math: fragments of the next half K-step are read while the MFMAs of the current one execute (software pipeline
+//    across the barrier, pinned with scheduling fences).  Accumulators are produced transposed (B fragment first), so
+//    a lane holds 4 consecutive columns of one output row and the epilogue moves 8 bytes per access.
+//  * Block ids are re-mapped so that each XCD (blocks are dealt round-robin to the 8 XCDs, each with its own L2) works
+//    on a contiguous run of tiles.
+//  * Weight-gradient shapes with few output tiles split K across blockIdx.y; fp32 partial tiles are added in a fixed
+//    order by a second kernel (no atomics, reproducible).
 #include <stdlib.h>
 
 #include "common.h"
@@ -34,16 +38,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void* lds_ptr;
 
-constexpr int BN = 128;
+constexpr int BK = 32, STAGES = 3;
 constexpr uint32_t OOB = 0x80000000u;                   // beyond any buffer this kernel accepts: reads as zero
-
-template <int ROWS, int BK> struct Geom {
-  static constexpr int NV = ROWS * BK / 8 / 256;        // 16-byte vectors per thread per K-step
-  static constexpr int PITCH_D = BK + 8;                // [row][k] staging: 80- or 144-byte rows
-  static constexpr int PITCH_T = ROWS + 32;             // [k][row] staging: row bytes = 64 (mod 256)
-  static constexpr int HALFS = (ROWS * PITCH_D > BK * PITCH_T) ? ROWS * PITCH_D : BK * PITCH_T;
-};
 
 template <typename T> struct Mfma;
 template <> struct Mfma<half_t> {
@@ -72,74 +70,80 @@ struct MfmaGemmParams {
   uint32_t a_bytes, b_bytes;                             // extents for the range-checked loads
 };
 
-// Per-thread byte offsets of its vectors in K-step 0, and the K-step stride.
-// TR == false: memory [rows, K] (k contiguous);  TR == true: memory [K, rows] (row index contiguous).
-template <int ROWS, int BK, bool TR>
-struct Loader {
-  typedef Geom<ROWS, BK> G;
-  static constexpr int VPR = BK / 8;                     // vectors per row in the [row][k] layout
-  uint32_t off[G::NV];
-  int kvec[G::NV];        // direct layout: first k of the vector (for the K-tail test)
-  uint32_t step;
-  int K;
-  __device__ __forceinline__ void init(int ld, int row0, int K_) {
-    K = K_;
+// One operand's path from global memory through the LDS ring into MFMA fragments.
+//   ROWS: tile rows (M or N extent of the block tile);  NW: wavefronts in the block;  TR: see the file comment.
+// A direct-to-LDS load writes the wavefront's 64 x 16 bytes contiguously, so load g of a stage fills bytes
+// [g*1024, (g+1)*1024) of the tile; each lane chooses WHICH global vector it fetches so that the tile ends up swizzled:
+//   [row][k] tile, 64-byte rows:     16-byte slot s of row r holds k-vector    s ^ ((r >> 2) & 3)
+//   [k][row] tile, ROWS*2-byte rows: 16-byte slot s of k-row k holds row-vector s ^ ((k & 3) << 2)
+template <int ROWS, int NW, bool TR>
+struct Operand {
+  static constexpr int LOADS = ROWS / 16 / NW;           // direct-to-LDS loads per wavefront per stage
+  static constexpr int TILE_BYTES = ROWS * BK * 2;
+  static constexpr int ROW_BYTES = ROWS * 2;             // [k][row] layout only
+  uint32_t off[LOADS];                                   // byte offset of this lane's vector in K-step 0
+  int kfirst[LOADS];                                     // its k index inside the K-step (for the K-tail test)
+  uint32_t step;                                         // byte stride between K-steps
+  int kend;
+
+  __device__ __forceinline__ void init(int ld, int row0, int kend_, int wave, int lane) {
+    kend = kend_;
 #pragma unroll
-    for (int i = 0; i < G::NV; ++i) {
-      const int v = threadIdx.x + 256 * i;
+    for (int i = 0; i < LOADS; ++i) {
+      const int g = wave * LOADS + i;
       if (!TR) {
-        const int row = row0 + v / VPR;
-        kvec[i] = (v % VPR) * 8;
-        off[i] = ((uint32_t)row * (uint32_t)ld + (uint32_t)kvec[i]) * 2u;
+        const int row = g * 16 + (lane >> 2);
+        kfirst[i] = ((lane & 3) ^ ((row >> 2) & 3)) * 8;
+        off[i] = ((uint32_t)(row0 + row) * (uint32_t)ld + (uint32_t)kfirst[i]) * 2u;
       } else {
-        const int k = v / (ROWS / 8), row = row0 + (v % (ROWS / 8)) * 8;
-        kvec[i] = 0;
-        off[i] = ((uint32_t)k * (uint32_t)ld + (uint32_t)row) * 2u;
+        const int byte = g * 1024 + lane * 16;
+        const int k = byte / ROW_BYTES, slot = (byte % ROW_BYTES) / 16;
+        const int vec = slot ^ ((k & 3) << 2);
+        kfirst[i] = k;
+        off[i] = ((uint32_t)k * (uint32_t)ld + (uint32_t)(row0 + vec * 8)) * 2u;
       }
     }
     step = TR ? (uint32_t)BK * (uint32_t)ld * 2u : (uint32_t)BK * 2u;
   }
-  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int kt, u32x4 (&r)[G::NV]) const {
+  // Issued as assembly on purpose (see the file comment).  lds_stage: LDS byte address of the stage's tile.
+  __device__ __forceinline__ void issue(const u32x4& rsrc, int kt, uint32_t lds_stage, int wave) const {
 #pragma unroll
-    for (int i = 0; i < G::NV; ++i) {
-      uint32_t o = off[i] + (uint32_t)kt * step;
-      if (!TR) { if (kt * BK + kvec[i] >= K) o = OOB; }                // k-tail inside a row is not caught by the range check
-      else { if (kt * BK + (int)((threadIdx.x + 256 * i) / (ROWS / 8)) >= K) o = OOB; }
-      r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)o, 0, 0);
+    for (int i = 0; i < LOADS; ++i) {
+      const uint32_t o = (kt * BK + kfirst[i] < kend) ? off[i] + (uint32_t)kt * step : OOB;
+      const uint32_t dst = lds_stage + (uint32_t)(wave * LOADS + i) * 1024u;
+      asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(__builtin_amdgcn_readfirstlane(dst)), "v"(o),
+                   "s"(rsrc)
+                   : "memory");
     }
   }
-  static __device__ __forceinline__ void store(uint16_t* S, const u32x4 (&r)[G::NV]) {
-#pragma unroll
-    for (int i = 0; i < G::NV; ++i) {
-      const int v = threadIdx.x + 256 * i;
-      const int o = TR ? (v / (ROWS / 8)) * G::PITCH_T + (v % (ROWS / 8)) * 8 : (v / VPR) * G::PITCH_D + (v % VPR) * 8;
-      *reinterpret_cast<u32x4*>(S + o) = r[i];
-    }
-  }
-  // Fragment of rows r0..r0+31, k = kk*16 .. kk*16+15 of the staged tile: lane l gets row r0 + l%32, k-group l/32.
-  static __device__ __forceinline__ u32x4 frag(const uint16_t* S, int r0, int kk, int lane) {
+  // Fragment of tile rows r0..r0+31 for k = kk*16 .. kk*16+15: lane l gets row r0 + l%32, k-group l/32 (8 k-values).
+  static __device__ __forceinline__ u32x4 frag(const unsigned char* S, int r0, int kk, int lane) {
     if (!TR) {
-      return *reinterpret_cast<const u32x4*>(S + (r0 + (lane & 31)) * G::PITCH_D + kk * 16 + (lane >> 5) * 8);
+      const int row = r0 + (lane & 31);
+      const int slot = (kk * 2 + (lane >> 5)) ^ ((row >> 2) & 3);
+      return *reinterpret_cast<const u32x4*>(S + row * 64 + slot * 16);
     } else {
-      const int s = lane & 15, ibase = lane & 16, kb = kk * 16 + (lane >> 5) * 8;
-      const uint16_t* p = S + (kb + (s >> 2)) * G::PITCH_T + r0 + ibase + 4 * (s & 3);
+      const int s = lane & 15, ibase = lane & 16;
+      const int k = kk * 16 + (lane >> 5) * 8 + (s >> 2);
+      const int seg = ((r0 + ibase) >> 4) ^ ((s >> 2) << 1);           // 32-byte segment, swizzled by k & 3
+      const unsigned char* p = S + k * ROW_BYTES + seg * 32 + (s & 3) * 8;
       typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * G::PITCH_T));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * ROW_BYTES));
       const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
       return u32x4{l2[0], l2[1], h2[0], h2[1]};
     }
   }
 };
 
-template <typename T, int BM, int BK, int PF, bool ATR, bool BTR>
-__global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaGemmParams p) {
-  // BK: K-step; PF: K-steps held in registers ahead of the math
-  constexpr int TM = BM / 64;                            // MFMA tiles per wavefront along M
-  typedef Loader<BM, BK, ATR> LA;
-  typedef Loader<BN, BK, BTR> LB;
-  __shared__ __attribute__((aligned(16))) uint16_t As[2][Geom<BM, BK>::HALFS];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[2][Geom<BN, BK>::HALFS];
+template <typename T, int BM, int BN, int WM, int WN, bool ATR, bool BTR>
+__global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfma_kernel(MfmaGemmParams p) {
+  constexpr int NW = WM * WN;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;    // MFMA tiles per wavefront
+  typedef Operand<BM, NW, ATR> OA;
+  typedef Operand<BN, NW, BTR> OB;
+  __shared__ __attribute__((aligned(1024))) unsigned char As[STAGES][OA::TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char Bs[STAGES][OB::TILE_BYTES];
   // XCD-aware tile order: hardware deals block b to XCD b % 8; give each XCD a contiguous run of tile ids
   int tile;
   {
@@ -147,78 +151,89 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaGemmParams p) {
     tile = x * q + (x < r ? x : r) + (b >> 3);
   }
   const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave / WN, wn = wave % WN;
 
-  f32x16 acc[TM][2];
+  // raw buffer descriptors: base, stride 0, byte extent, format word
+  const u32x4 ra = {(uint32_t)(uintptr_t)p.A, (uint32_t)((uintptr_t)p.A >> 32) & 0xffffu, p.a_bytes, 0x00020000u};
+  const u32x4 rb = {(uint32_t)(uintptr_t)p.B, (uint32_t)((uintptr_t)p.B >> 32) & 0xffffu, p.b_bytes, 0x00020000u};
+  // split-K: this block covers K-steps kt0 .. ; everything at or beyond kend reads as zero
+  const int kt0 = blockIdx.y * p.ksteps_per_split;
+  const int kend = min(p.K, (kt0 + p.ksteps_per_split) * BK);
+  const int nk = max(0, (kend - kt0 * BK + BK - 1) / BK);
+  OA oa;
+  OB ob;
+  oa.init(p.lda, m0, kend, wave, lane);
+  ob.init(p.ldb, n0, kend, wave, lane);
+  const uint32_t lds_a = (uint32_t)(uintptr_t)(lds_ptr)(&As[0][0]), lds_b = (uint32_t)(uintptr_t)(lds_ptr)(&Bs[0][0]);
+  auto issue = [&](int kt, int stage) {
+    oa.issue(ra, kt0 + kt, lds_a + stage * OA::TILE_BYTES, wave);
+    ob.issue(rb, kt0 + kt, lds_b + stage * OB::TILE_BYTES, wave);
+  };
+
+  f32x16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const __amdgpu_buffer_rsrc_t ra_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, p.a_bytes, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rb_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, p.b_bytes, 0x00020000);
-  LA la;
-  LB lb;
-  // split-K: this block covers K-steps [kt0, kt0 + nk); everything beyond its slice reads as zero
-  const int kt0 = blockIdx.y * p.ksteps_per_split;
-  const int kend = min(p.K, (kt0 + p.ksteps_per_split) * BK);
-  la.init(p.lda, m0, kend);
-  lb.init(p.ldb, n0, kend);
-  const int nk = max(0, (kend - kt0 * BK + BK - 1) / BK);
-
-  u32x4 ra[PF][Geom<BM, BK>::NV], rb[PF][Geom<BN, BK>::NV];
+  auto read_frags = [&](int stage, int kk, u32x4 (&fa)[TM], u32x4 (&fb)[TN]) {
 #pragma unroll
-  for (int u = 0; u < PF; ++u) { la.load(ra_rsrc, kt0 + u, ra[u]); lb.load(rb_rsrc, kt0 + u, rb[u]); }
-  LA::store(As[0], ra[0]);
-  LB::store(Bs[0], rb[0]);
-  la.load(ra_rsrc, kt0 + PF, ra[0]);
-  lb.load(rb_rsrc, kt0 + PF, rb[0]);
+    for (int i = 0; i < TM; ++i) fa[i] = OA::frag(As[stage], wm * (BM / WM) + i * 32, kk, lane);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[j] = OB::frag(Bs[stage], wn * (BN / WN) + j * 32, kk, lane);
+  };
+  auto mfmas = [&](const u32x4 (&fa)[TM], const u32x4 (&fb)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::run(fb[j], fa[i], acc[i][j]);   // transposed product: D'[n][m]
+  };
+
+  constexpr int WAIT = OA::LOADS + OB::LOADS;            // loads per wavefront per K-step
+  static_assert(WAIT <= 15, "vmcnt immediate");
+  issue(0, 0);
+  issue(1, 1);
+  u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  __builtin_amdgcn_s_waitcnt(0x0F70 | WAIT);             // K-step 0 has landed (K-step 1 may be in flight)
   __syncthreads();
-
-  // The trip count is rounded up to a multiple of the prefetch depth: K-steps beyond K read zeros (range check), so
-  // the extra MFMAs add nothing and the loop body stays branch-free.
-  const int nk_pad = (nk + PF - 1) / PF * PF;
-  for (int base = 0; base < nk_pad; base += PF) {
+  issue(2, 2);
+  read_frags(0, 0, fa0, fb0);
+  read_frags(0, 1, fa1, fb1);
+  // The trip count is rounded up to the ring size: K-steps beyond the slice read zeros, so the extra MFMAs add nothing.
+  const int nk3 = (nk + STAGES - 1) / STAGES * STAGES;
+  for (int base = 0; base < nk3; base += STAGES) {
 #pragma unroll
-    for (int u = 0; u < PF; ++u) {
+    for (int u = 0; u < STAGES; ++u) {
       const int kt = base + u;
-      const int slot = (u + 1) % PF;                     // registers holding K-step kt+1
-      const int cur = kt & 1;
-      LA::store(As[cur ^ 1], ra[slot]);
-      LB::store(Bs[cur ^ 1], rb[slot]);
-      la.load(ra_rsrc, kt0 + kt + 1 + PF, ra[slot]);
-      lb.load(rb_rsrc, kt0 + kt + 1 + PF, rb[slot]);
-      const uint16_t* as = As[cur];
-      const uint16_t* bs = Bs[cur];
-#pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk) {
-        u32x4 fa[TM], fb[2];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[i] = LA::frag(as, wm * (BM / 2) + i * 32, kk, lane);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) fb[j] = LB::frag(bs, wn * 64 + j * 32, kk, lane);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j) acc[i][j] = Mfma<T>::run(fb[j], fa[i], acc[i][j]);   // transposed product: D'[n][m]
-      }
-      __syncthreads();
+      // (the scheduling fences keep the compiler from sinking the LDS reads back next to the MFMAs that use them)
+      mfmas(fa0, fb0);
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_waitcnt(0x0F70 | WAIT);         // K-step kt+1 has landed (kt+2 may be in flight)
+      __syncthreads();                                   // ... for every wavefront, and stage u is no longer read
+      read_frags((u + 1) % STAGES, 0, fa0, fb0);
+      issue(kt + 3, u);
+      __builtin_amdgcn_sched_barrier(0);
+      mfmas(fa1, fb1);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags((u + 1) % STAGES, 1, fa1, fb1);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);                    // drain the trailing (zero-fill) loads before LDS is released
 
   if (p.partial) {                                        // split-K: raw fp32 tile, summed by splitk_reduce_kernel
     float* P = p.partial + (size_t)blockIdx.y * p.M * p.N;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      const int m = m0 + wm * (BM / 2) + i * 32 + (lane & 31);
+      const int m = m0 + wm * (BM / WM) + i * 32 + (lane & 31);
       if (m >= p.M) continue;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
-          const int n = n0 + wn * 64 + j * 32 + rg * 8 + (lane >> 5) * 4;
+          const int n = n0 + wn * (BN / WN) + j * 32 + rg * 8 + (lane >> 5) * 4;
           if (n >= p.N) continue;
           float4 v = {acc[i][j][rg * 4], acc[i][j][rg * 4 + 1], acc[i][j][rg * 4 + 2], acc[i][j][rg * 4 + 3]};
           *reinterpret_cast<float4*>(P + (size_t)m * p.N + n) = v;
@@ -233,13 +248,13 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaGemmParams p) {
   T* C = reinterpret_cast<T*>(p.C);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wm * (BM / 2) + i * 32 + (lane & 31);
+    const int m = m0 + wm * (BM / WM) + i * 32 + (lane & 31);
     if (m >= p.M) continue;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < TN; ++j) {
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
-        const int n = n0 + wn * 64 + j * 32 + rg * 8 + (lane >> 5) * 4;
+        const int n = n0 + wn * (BN / WN) + j * 32 + rg * 8 + (lane >> 5) * 4;
         if (n >= p.N) continue;
         float v[4];
 #pragma unroll
@@ -313,7 +328,7 @@ bool gemm_mfma_supported(const GemmArgs& a) {
   return true;
 }
 
-template <typename T, int BM, int BK, int PF>
+template <typename T, int BM, int BN, int WM, int WN>
 static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   MfmaGemmParams p;
   p.M = a.M; p.N = a.N; p.K = a.K;
@@ -334,10 +349,10 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   }
   p.ksteps_per_split = (nk + splits - 1) / splits;
   p.partial = splits > 1 ? (float*)a.splitk_ws : nullptr;
-  dim3 grid(p.tiles_total, splits), block(256);
-  if (a.form == 0) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BK, PF, false, false>), grid, block, 0, s, p);
-  else if (a.form == 1) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BK, PF, false, true>), grid, block, 0, s, p);
-  else hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BK, PF, true, true>), grid, block, 0, s, p);
+  dim3 grid(p.tiles_total, splits), block(64 * WM * WN);
+  if (a.form == 0) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, false, false>), grid, block, 0, s, p);
+  else if (a.form == 1) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, false, true>), grid, block, 0, s, p);
+  else hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, true, true>), grid, block, 0, s, p);
   if (splits > 1) {
     const size_t quads = ((size_t)a.M * a.N + 3) / 4;
     hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, (const float*)a.splitk_ws, splits,
@@ -345,29 +360,32 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   }
 }
 
-// 256-row tiles halve the B-panel traffic per flop; they pay off once there are enough of them to fill the chip.
-static int forced_bm() {                                 // tuning aid: TFM_GEMM_BM=128|256 overrides the choice
+static int forced_tile() {                               // tuning aid: TFM_GEMM_TILE=1|3 overrides the choice
   static int v = -1;
-  if (v < 0) { const char* e = getenv("TFM_GEMM_BM"); v = e ? atoi(e) : 0; }
+  if (v < 0) { const char* e = getenv("TFM_GEMM_TILE"); v = e ? atoi(e) : 0; }
   return v;
 }
 
-void launch_gemm_mfma(hipStream_t s, const GemmArgs& a) {
-  int bm = 128;
-  const long tiles256 = (long)((a.M + 255) / 256) * ((a.N + BN - 1) / BN);
-  if (tiles256 >= 400) bm = 256;
-  if (forced_bm() == 128 || forced_bm() == 256) bm = forced_bm();
-  static int bk64 = -1;
-  if (bk64 < 0) { const char* e = getenv("TFM_GEMM_BK"); bk64 = (e && atoi(e) == 64) ? 1 : 0; }
-  if (a.dt == F16) {
-    if (bm == 256) gemm_mfma_launch<half_t, 256, 32, 2>(s, a);
-    else if (bk64) gemm_mfma_launch<half_t, 128, 64, 2>(s, a);
-    else gemm_mfma_launch<half_t, 128, 32, 3>(s, a);
-  } else {
-    if (bm == 256) gemm_mfma_launch<bf16_t, 256, 32, 2>(s, a);
-    else if (bk64) gemm_mfma_launch<bf16_t, 128, 64, 2>(s, a);
-    else gemm_mfma_launch<bf16_t, 128, 32, 3>(s, a);
+// Tile choice.  Bigger tiles fetch fewer bytes per flop but need enough tiles to occupy the chip (measured on the
+// projection shapes of the big Transformer: 256x256 wins from about 150 tiles on).
+//   1: 128x128 (4 wavefronts)   3: 256x256 (8 wavefronts)
+static int choose_tile(const GemmArgs& a) {
+  if (forced_tile() == 1 || forced_tile() == 3) return forced_tile();
+  const long t3 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
+  return t3 >= 150 ? 3 : 1;
+}
+
+template <typename T>
+static void gemm_mfma_dispatch(hipStream_t s, const GemmArgs& a) {
+  switch (choose_tile(a)) {
+    case 3: gemm_mfma_launch<T, 256, 256, 2, 4>(s, a); break;
+    default: gemm_mfma_launch<T, 128, 128, 2, 2>(s, a); break;
   }
+}
+
+void launch_gemm_mfma(hipStream_t s, const GemmArgs& a) {
+  if (a.dt == F16) gemm_mfma_dispatch<half_t>(s, a);
+  else gemm_mfma_dispatch<bf16_t>(s, a);
 }
 
 }  // namespace tfm

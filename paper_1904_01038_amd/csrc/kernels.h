@@ -47,7 +47,6 @@ void launch_gemm(hipStream_t s, const GemmArgs& a);
 bool gemm_mfma_supported(const GemmArgs& a);
 void launch_gemm_naive(hipStream_t s, const GemmArgs& a);
 void launch_gemm_mfma(hipStream_t s, const GemmArgs& a);      // requires gemm_mfma_supported(a)
-void launch_gemm_nt_dma(hipStream_t s, const GemmArgs& a);    // form 0 only; requires gemm_mfma_supported(a)
 
 struct AttnArgs {
   int dt;
