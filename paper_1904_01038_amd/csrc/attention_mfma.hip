@@ -11,8 +11,8 @@
 //
 // Forward: grid (query chunks of 64, heads, sentences), 2 wavefronts x 32 queries, online softmax over key chunks,
 //          stores the row log-sum-exp.
-// Backward: (1) dQ kernel, same decomposition, recomputes P from the saved log-sum-exp;
-//           (2) dK/dV kernel, grid over key chunks of 64, loops over query chunks.  No atomics.
+// Backward (one launch): blocks [0, nq) along x compute dQ with the forward's decomposition, recomputing P from the
+//           saved log-sum-exp; blocks [nq, nq+nk) own 64-key chunks and loop over query chunks for dK/dV.  No atomics.
 #include "common.h"
 #include "kernels.h"
 
@@ -207,12 +207,10 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_fwd_mfma_kernel(AttnP p) {
 
 // ---- backward: dQ ---------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(ATT_THREADS) void attn_bwd_dq_mfma_kernel(AttnP p) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[CH * PT];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[CH * PT];
+__device__ __forceinline__ void attn_bwd_dq_body(const AttnP& p, int chunk, uint16_t* Ks, uint16_t* Vs) {
   const int b = blockIdx.z, h = blockIdx.y;
   const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;
-  const int qstart = blockIdx.x * 64;
+  const int qstart = chunk * 64;
   if (qstart >= lq) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int qi0 = qstart + wave * 32;
@@ -281,14 +279,10 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_bwd_dq_mfma_kernel(AttnP p) 
 
 // ---- backward: dK, dV -------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(ATT_THREADS) void attn_bwd_dkv_mfma_kernel(AttnP p) {
-  __shared__ __attribute__((aligned(16))) uint16_t Qs[CH * PT];
-  __shared__ __attribute__((aligned(16))) uint16_t Gs[CH * PT];
-  __shared__ __attribute__((aligned(16))) float Ls[CH];
-  __shared__ __attribute__((aligned(16))) float Ds[CH];
+__device__ __forceinline__ void attn_bwd_dkv_body(const AttnP& p, int chunk, uint16_t* Qs, uint16_t* Gs, float* Ls, float* Ds) {
   const int b = blockIdx.z, h = blockIdx.y;
   const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;
-  const int kstart = blockIdx.x * 64;
+  const int kstart = chunk * 64;
   if (kstart >= lk) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int kj0 = kstart + wave * 32;
@@ -385,6 +379,18 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_bwd_dkv_mfma_kernel(AttnP p)
     }
 }
 
+// One launch for the whole backward: the first nq_chunks blocks along x compute dQ, the rest dK/dV; the two halves are
+// independent, so they run side by side instead of one after the other.
+template <typename T>
+__global__ __launch_bounds__(ATT_THREADS) void attn_bwd_mfma_kernel(AttnP p, int nq_chunks) {
+  __shared__ __attribute__((aligned(16))) uint16_t S0[CH * PT];
+  __shared__ __attribute__((aligned(16))) uint16_t S1[CH * PT];
+  __shared__ __attribute__((aligned(16))) float Ls[CH];
+  __shared__ __attribute__((aligned(16))) float Ds[CH];
+  if ((int)blockIdx.x < nq_chunks) attn_bwd_dq_body<T>(p, blockIdx.x, S0, S1);
+  else attn_bwd_dkv_body<T>(p, blockIdx.x - nq_chunks, S0, S1, Ls, Ds);
+}
+
 static bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 bool attention_mfma_supported(const AttnArgs& a, bool bwd) {
@@ -418,14 +424,10 @@ void launch_attention_fwd_mfma(hipStream_t s, const AttnArgs& a) {
 
 void launch_attention_bwd_mfma(hipStream_t s, const AttnArgs& a) {
   const AttnP p = make_params(a);
-  dim3 gq((a.max_lq + 63) / 64, a.H, a.B), gk((a.max_lk + 63) / 64, a.H, a.B), block(ATT_THREADS);
-  if (a.dt == F16) {
-    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<half_t>), gq, block, 0, s, p);
-    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<half_t>), gk, block, 0, s, p);
-  } else {
-    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<bf16_t>), gq, block, 0, s, p);
-    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<bf16_t>), gk, block, 0, s, p);
-  }
+  const int nq = (a.max_lq + 63) / 64, nk = (a.max_lk + 63) / 64;
+  dim3 grid(nq + nk, a.H, a.B), block(ATT_THREADS);
+  if (a.dt == F16) hipLaunchKernelGGL((attn_bwd_mfma_kernel<half_t>), grid, block, 0, s, p, nq);
+  else hipLaunchKernelGGL((attn_bwd_mfma_kernel<bf16_t>), grid, block, 0, s, p, nq);
 }
 
 }  // namespace tfm

@@ -95,16 +95,18 @@ void launch_residual_layernorm_fwd(hipStream_t s, int dt, const void* x, const v
 // ---- backward -----------------------------------------------------------------------------------------------------------
 // Per row: xhat = (s - mean) rstd; dxhat = dn * gamma; ds = rstd (dxhat - mean(dxhat) - xhat mean(dxhat xhat)) + add.
 // Column partial sums (dgamma = sum dn xhat, dbeta = sum dn, dbias = sum dropout-backward(ds)) are kept in registers
-// while a wavefront walks its rows, combined across the block's 4 wavefronts in LDS, and written once per block to
-// partial[block][3][d]; a second kernel adds the partials in a fixed order.
+// while a wavefront walks its rows, combined across the block's 8 wavefronts in LDS (one quantity at a time, so the
+// LDS footprint stays at 8 rows), and written once per block to partial[block][3][d]; a second kernel adds the
+// partials in a fixed order.  One block per CU, 8 wavefronts each, keeps enough rows in flight to cover HBM latency.
 constexpr int LNB_MAX_BLOCKS = 256;
+constexpr int LNB_WAVES = 8;
 
 template <typename T, int NCH>
-__global__ __launch_bounds__(256) void layernorm_bwd_kernel(
+__global__ __launch_bounds__(64 * LNB_WAVES) void layernorm_bwd_kernel(
     const T* __restrict__ dn, const T* __restrict__ add, const T* __restrict__ sres, const float* __restrict__ mean,
     const float* __restrict__ rstd, const T* __restrict__ gamma, T* __restrict__ ds, T* __restrict__ ds_drop,
     float* __restrict__ partial, int rows, int d, uint64_t key, uint32_t thr, float inv_keep) {
-  extern __shared__ float lds[];     // [3][4][d]
+  extern __shared__ float lds[];     // [LNB_WAVES][d]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   float g[NCH][LN_VEC], ag[NCH][LN_VEC], ab[NCH][LN_VEC], ac[NCH][LN_VEC];
 #pragma unroll
@@ -117,8 +119,8 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(
   // The next row's operands are fetched into registers before the current row's reductions, so a wavefront always has
   // a full row of loads in flight.
   float a[NCH][LN_VEC], b[NCH][LN_VEC], t[NCH][LN_VEC];
-  const int rstep = gridDim.x * 4;
-  int row = blockIdx.x * 4 + w;
+  const int rstep = gridDim.x * LNB_WAVES;
+  int row = blockIdx.x * LNB_WAVES + w;
   auto fetch = [&](int r, float (&fa)[NCH][LN_VEC], float (&fb)[NCH][LN_VEC], float (&ft)[NCH][LN_VEC]) {
     const size_t base = (size_t)r * d;
 #pragma unroll
@@ -178,22 +180,23 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(
     }
   }
 #pragma unroll
-  for (int c = 0; c < NCH; ++c) {
-    const int col = (lane + 64 * c) * LN_VEC;
-    if (col < d) {
+  for (int k = 0; k < 3; ++k) {
+    __syncthreads();
 #pragma unroll
-      for (int i = 0; i < LN_VEC; ++i) {
-        lds[(0 * 4 + w) * d + col + i] = ag[c][i];
-        lds[(1 * 4 + w) * d + col + i] = ab[c][i];
-        lds[(2 * 4 + w) * d + col + i] = ac[c][i];
+    for (int c = 0; c < NCH; ++c) {
+      const int col = (lane + 64 * c) * LN_VEC;
+      if (col < d) {
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i) lds[w * d + col + i] = k == 0 ? ag[c][i] : (k == 1 ? ab[c][i] : ac[c][i]);
       }
     }
-  }
-  __syncthreads();
-  for (int j = threadIdx.x; j < 3 * d; j += 256) {
-    const int k = j / d, col = j - k * d;
-    const float t = (lds[(k * 4 + 0) * d + col] + lds[(k * 4 + 1) * d + col]) + (lds[(k * 4 + 2) * d + col] + lds[(k * 4 + 3) * d + col]);
-    partial[((size_t)blockIdx.x * 3 + k) * d + col] = t;
+    __syncthreads();
+    for (int col = threadIdx.x; col < d; col += 64 * LNB_WAVES) {
+      float t = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < LNB_WAVES; ++ww) t += lds[ww * d + col];
+      partial[((size_t)blockIdx.x * 3 + k) * d + col] = t;
+    }
   }
 }
 
@@ -232,7 +235,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 }
 
 static int lnb_blocks(int rows) {
-  int b = (rows + 3) / 4;
+  int b = (rows + LNB_WAVES - 1) / LNB_WAVES;
   return b > LNB_MAX_BLOCKS ? LNB_MAX_BLOCKS : (b < 1 ? 1 : b);
 }
 size_t layernorm_bwd_scratch_bytes(int rows, int d) { return (size_t)lnb_blocks(rows) * 3 * d * sizeof(float); }
@@ -244,10 +247,10 @@ static void ln_bwd_dispatch(hipStream_t s, const void* dn, const void* add, cons
   const uint32_t thr = (p > 0.f && ds_drop) ? drop_threshold(p) : 0u;
   const float inv_keep = 1.f / (1.f - p);
   const int nb = lnb_blocks(rows);
-  const size_t shm = (size_t)12 * d * sizeof(float);
+  const size_t shm = (size_t)LNB_WAVES * d * sizeof(float);
   const int nch = (d + 511) / 512;
 #define LN_BWD(N)                                                                                                       \
-  hipLaunchKernelGGL((layernorm_bwd_kernel<T, N>), dim3(nb), dim3(256), shm, s, (const T*)dn, (const T*)add,             \
+  hipLaunchKernelGGL((layernorm_bwd_kernel<T, N>), dim3(nb), dim3(64 * LNB_WAVES), shm, s, (const T*)dn, (const T*)add,             \
                      (const T*)sres, mean, rstd, (const T*)gamma, (T*)ds, (T*)ds_drop, (float*)scratch, rows, d, key, thr, \
                      inv_keep)
   if (nch <= 1) LN_BWD(1); else if (nch == 2) LN_BWD(2); else if (nch == 3) LN_BWD(3); else LN_BWD(4);
