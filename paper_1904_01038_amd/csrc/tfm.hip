@@ -328,7 +328,9 @@ void gemm(tfm_ctx* c, int form, int M, int N, int K, const void* A, int lda, con
   GemmArgs a{c->dt, form, M, N, K, A, lda, B, ldb, C, ldc, bias, relu, mask, residual};
   a.splitk_ws = c->splitk_ws;
   a.splitk_ws_bytes = c->splitk_bytes;
-  run(c, TFM_PROF_GEMM, 2.0 * M * N * K, 0.0, [&] { launch_gemm(c->stream, a); });
+  // algorithmic bytes: each operand read once, the result written once (plus the epilogue's mask/residual reads)
+  const double bytes = (double)c->esz * ((double)M * K + (double)K * N + (double)M * N * (1.0 + (mask ? 1.0 : 0.0) + (residual ? 1.0 : 0.0)));
+  run(c, TFM_PROF_GEMM, 2.0 * M * N * K, bytes, [&] { launch_gemm(c->stream, a); });
 }
 
 double attn_flops(const std::vector<int>& lq, const std::vector<int>& lk, int d, bool causal) {
