@@ -136,9 +136,16 @@ def main():
         classes[name] = e
     g = prof["gemm"]
     achieved = g["flops"] / (g["ms"] * 1e-3) / 1e12 if g["ms"] > 0 else 0.0
+    # HBM-side bytes per GEMM launch from the committed rocprofv3 counter runs of this workload (null if none)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "train_step_%s_%s_hbm_traffic.json" % (args.workload, prec_name))
+    if os.path.exists(tpath):
+        t = json.load(open(tpath))["gemm"]
+        traffic = (t["fetch_kib_raw"] * t["read_factor"] + t["write_kib_raw"] * t["write_factor"]) * 1024.0 / t["launches"]
     peak = FP32_PEAK_TFLOPS if prec == T.FP32 else MFMA_PEAK_TFLOPS
     roofline = {"kernel": "gemm (all projection, vocabulary and gradient GEMMs)", "bound": "mfma" if prec != T.FP32 else "alu",
-                "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
+                "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1),
                 "avg_launch_ms": g["ms"] / max(g["launches"], 1), "launches_per_step": g["launches"] / args.profile_steps,
                 "classes": classes}
 
