@@ -5,12 +5,12 @@
 // be pulled from L2 into the CUs (about 8 TB/s in aggregate), so the design minimises bytes fetched per flop and
 // keeps the fetch path as cheap as possible:
 //
-//  * Tiles: BM x BN output tile per block, K walked in steps of 32.  128x128 (4 wavefronts, 64x64 each) for outputs
-//    with few tiles, 256x256 (8 wavefronts, 128x64 each) for large outputs: a 256x256 tile fetches half as many
-//    bytes per flop as a 128x128 one.
+//  * Tiles: BM x BN output tile per block, K walked in steps of 32 or 64.  128x128 (4 wavefronts, 64x64 each) for
+//    outputs with few tiles, 256x256 (8 wavefronts, 128x64 each) for large outputs: a 256x256 tile fetches half as
+//    many bytes per flop as a 128x128 one.  A K-step of 64 fetches whole 128-byte lines per row.
 //  * Fetch: CDNA4 direct-to-LDS buffer loads (buffer_load_dwordx4 ... lds): no staging registers and no ds_write on
-//    the load path; range-checked, so ragged M, N, K read zeros without branches.  A 3-stage LDS ring keeps two
-//    K-steps in flight; one barrier per K-step.  The loads are issued as assembly and tracked with s_waitcnt vmcnt by
+//    the load path; range-checked, so ragged M, N, K read zeros without branches.  A 2- or 3-stage LDS ring keeps one
+//    or two K-steps in flight; one barrier per K-step.  The loads are issued as assembly and tracked with s_waitcnt vmcnt by
 //    hand, because the compiler would otherwise drain every outstanding direct-to-LDS load before each LDS read.
 //  * LDS layout: unpadded tiles (the direct-to-LDS path writes 1 KB per wavefront contiguously), XOR-swizzled on the
 //    global-address side so that fragment reads are bank-conflict free.  An operand whose contraction index is
@@ -40,7 +40,6 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
-constexpr int BK = 32, STAGES = 3;
 constexpr uint32_t OOB = 0x80000000u;                   // beyond any buffer this kernel accepts: reads as zero
 
 template <typename T> struct Mfma;
@@ -74,13 +73,18 @@ struct MfmaGemmParams {
 //   ROWS: tile rows (M or N extent of the block tile);  NW: wavefronts in the block;  TR: see the file comment.
 // A direct-to-LDS load writes the wavefront's 64 x 16 bytes contiguously, so load g of a stage fills bytes
 // [g*1024, (g+1)*1024) of the tile; each lane chooses WHICH global vector it fetches so that the tile ends up swizzled:
-//   [row][k] tile, 64-byte rows:     16-byte slot s of row r holds k-vector    s ^ ((r >> 2) & 3)
+//   [row][k] tile, 2*BK-byte rows:   16-byte slot s of row r holds k-vector    s ^ swz(r)
 //   [k][row] tile, ROWS*2-byte rows: 16-byte slot s of k-row k holds row-vector s ^ ((k & 3) << 2)
-template <int ROWS, int NW, bool TR>
+template <int ROWS, int BK, int NW, bool TR>
 struct Operand {
-  static constexpr int LOADS = ROWS / 16 / NW;           // direct-to-LDS loads per wavefront per stage
   static constexpr int TILE_BYTES = ROWS * BK * 2;
+  static constexpr int LOADS = TILE_BYTES / 1024 / NW;   // direct-to-LDS loads per wavefront per stage
   static constexpr int ROW_BYTES = ROWS * 2;             // [k][row] layout only
+  static constexpr int KROW_BYTES = BK * 2;              // [row][k] layout only: 64 or 128
+  static constexpr int VPR = BK / 8;                     // 16-byte vectors per [row][k] row: 4 or 8
+  // swizzle of the [row][k] layout: slot ^= f(row) with f chosen so that 16 consecutive rows cover 16 distinct
+  // 16-byte bank groups: 64-byte rows: (row >> 2) & 3;  128-byte rows: (row >> 1) & 7
+  static __device__ __forceinline__ int swz(int row) { return BK == 32 ? ((row >> 2) & 3) : ((row >> 1) & 7); }
   uint32_t off[LOADS];                                   // byte offset of this lane's vector in K-step 0
   int kfirst[LOADS];                                     // its k index inside the K-step (for the K-tail test)
   uint32_t step;                                         // byte stride between K-steps
@@ -92,8 +96,8 @@ struct Operand {
     for (int i = 0; i < LOADS; ++i) {
       const int g = wave * LOADS + i;
       if (!TR) {
-        const int row = g * 16 + (lane >> 2);
-        kfirst[i] = ((lane & 3) ^ ((row >> 2) & 3)) * 8;
+        const int row = g * (64 / VPR) + lane / VPR;
+        kfirst[i] = ((lane % VPR) ^ swz(row)) * 8;
         off[i] = ((uint32_t)(row0 + row) * (uint32_t)ld + (uint32_t)kfirst[i]) * 2u;
       } else {
         const int byte = g * 1024 + lane * 16;
@@ -120,8 +124,8 @@ struct Operand {
   static __device__ __forceinline__ u32x4 frag(const unsigned char* S, int r0, int kk, int lane) {
     if (!TR) {
       const int row = r0 + (lane & 31);
-      const int slot = (kk * 2 + (lane >> 5)) ^ ((row >> 2) & 3);
-      return *reinterpret_cast<const u32x4*>(S + row * 64 + slot * 16);
+      const int slot = (kk * 2 + (lane >> 5)) ^ swz(row);
+      return *reinterpret_cast<const u32x4*>(S + row * KROW_BYTES + slot * 16);
     } else {
       const int s = lane & 15, ibase = lane & 16;
       const int k = kk * 16 + (lane >> 5) * 8 + (s >> 2);
@@ -136,12 +140,14 @@ struct Operand {
   }
 };
 
-template <typename T, int BM, int BN, int WM, int WN, bool ATR, bool BTR>
+template <typename T, int BM, int BN, int WM, int WN, int BK, int STAGES, bool ATR, bool BTR>
 __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfma_kernel(MfmaGemmParams p) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;    // MFMA tiles per wavefront
-  typedef Operand<BM, NW, ATR> OA;
-  typedef Operand<BN, NW, BTR> OB;
+  constexpr int KK = BK / 16;                            // MFMA sub-steps per K-step (2 or 4)
+  constexpr int D = STAGES - 1;                          // K-steps in flight ahead of the one being consumed
+  typedef Operand<BM, BK, NW, ATR> OA;
+  typedef Operand<BN, BK, NW, BTR> OB;
   __shared__ __attribute__((aligned(1024))) unsigned char As[STAGES][OA::TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char Bs[STAGES][OB::TILE_BYTES];
   // XCD-aware tile order: hardware deals block b to XCD b % 8; give each XCD a contiguous run of tile ids
@@ -191,34 +197,41 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
       for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::run(fb[j], fa[i], acc[i][j]);   // transposed product: D'[n][m]
   };
 
-  constexpr int WAIT = OA::LOADS + OB::LOADS;            // loads per wavefront per K-step
+  constexpr int WAIT = (OA::LOADS + OB::LOADS) * (D - 1);   // loads that may still be in flight when a K-step must have landed
   static_assert(WAIT <= 15, "vmcnt immediate");
-  issue(0, 0);
-  issue(1, 1);
+#pragma unroll
+  for (int t = 0; t < D; ++t) issue(t, t);
   u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  __builtin_amdgcn_s_waitcnt(0x0F70 | WAIT);             // K-step 0 has landed (K-step 1 may be in flight)
+  __builtin_amdgcn_s_waitcnt(0x0F70 | WAIT);             // K-step 0 has landed
   __syncthreads();
-  issue(2, 2);
+  issue(D, D % STAGES);
   read_frags(0, 0, fa0, fb0);
   read_frags(0, 1, fa1, fb1);
+  // Software pipeline: sub-step j runs its MFMAs from register set j%2 while set j%2 is refilled with sub-step j+2
+  // (of the same stage, or after the barrier of the next one).  LDS latency is therefore always covered by matrix work.
   // The trip count is rounded up to the ring size: K-steps beyond the slice read zeros, so the extra MFMAs add nothing.
-  const int nk3 = (nk + STAGES - 1) / STAGES * STAGES;
-  for (int base = 0; base < nk3; base += STAGES) {
+  const int nkr = (nk + STAGES - 1) / STAGES * STAGES;
+  for (int base = 0; base < nkr; base += STAGES) {
 #pragma unroll
     for (int u = 0; u < STAGES; ++u) {
       const int kt = base + u;
-      // (the scheduling fences keep the compiler from sinking the LDS reads back next to the MFMAs that use them)
-      mfmas(fa0, fb0);
-      __builtin_amdgcn_sched_barrier(0);
-      __builtin_amdgcn_s_waitcnt(0x0F70 | WAIT);         // K-step kt+1 has landed (kt+2 may be in flight)
-      __syncthreads();                                   // ... for every wavefront, and stage u is no longer read
-      read_frags((u + 1) % STAGES, 0, fa0, fb0);
-      issue(kt + 3, u);
-      __builtin_amdgcn_sched_barrier(0);
-      mfmas(fa1, fb1);
-      __builtin_amdgcn_sched_barrier(0);
-      read_frags((u + 1) % STAGES, 1, fa1, fb1);
-      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < KK; ++j) {
+        // (the scheduling fences keep the compiler from sinking the LDS reads back next to the MFMAs that use them)
+        if (j % 2 == 0) mfmas(fa0, fb0); else mfmas(fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (j + 2 < KK) {
+          if (j % 2 == 0) read_frags(u, j + 2, fa0, fb0); else read_frags(u, j + 2, fa1, fb1);
+        } else if (j == KK - 2) {
+          __builtin_amdgcn_s_waitcnt(0x0F70 | WAIT);     // K-step kt+1 has landed for this wavefront ...
+          __syncthreads();                               // ... and for all of them; stage u is no longer read
+          read_frags((u + 1) % STAGES, 0, fa0, fb0);
+          issue(kt + 1 + D, u);
+        } else {
+          read_frags((u + 1) % STAGES, 1, fa1, fb1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);                    // drain the trailing (zero-fill) loads before LDS is released
@@ -328,7 +341,7 @@ bool gemm_mfma_supported(const GemmArgs& a) {
   return true;
 }
 
-template <typename T, int BM, int BN, int WM, int WN>
+template <typename T, int BM, int BN, int WM, int WN, int BK, int STAGES>
 static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   MfmaGemmParams p;
   p.M = a.M; p.N = a.N; p.K = a.K;
@@ -350,9 +363,9 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   p.ksteps_per_split = (nk + splits - 1) / splits;
   p.partial = splits > 1 ? (float*)a.splitk_ws : nullptr;
   dim3 grid(p.tiles_total, splits), block(64 * WM * WN);
-  if (a.form == 0) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, false, false>), grid, block, 0, s, p);
-  else if (a.form == 1) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, false, true>), grid, block, 0, s, p);
-  else hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, true, true>), grid, block, 0, s, p);
+  if (a.form == 0) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, false, false>), grid, block, 0, s, p);
+  else if (a.form == 1) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, false, true>), grid, block, 0, s, p);
+  else hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, true, true>), grid, block, 0, s, p);
   if (splits > 1) {
     const size_t quads = ((size_t)a.M * a.N + 3) / 4;
     hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, (const float*)a.splitk_ws, splits,
@@ -360,26 +373,31 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   }
 }
 
-static int forced_tile() {                               // tuning aid: TFM_GEMM_TILE=1|3 overrides the choice
+static int forced_tile() {                               // tuning aid: TFM_GEMM_TILE=<config id> overrides the choice
   static int v = -1;
   if (v < 0) { const char* e = getenv("TFM_GEMM_TILE"); v = e ? atoi(e) : 0; }
   return v;
 }
 
-// Tile choice.  Bigger tiles fetch fewer bytes per flop but need enough tiles to occupy the chip (measured on the
-// projection shapes of the big Transformer: 256x256 wins from about 150 tiles on).
-//   1: 128x128 (4 wavefronts)   3: 256x256 (8 wavefronts)
+// Configuration choice, from measurements on the projection shapes of the big Transformer (M ~ 3264 tokens):
+//   id  tile     K-step  ring   resident blocks per CU
+//    1  128x128    32     3      3      small K: more blocks in flight hide the short K loop's ramp
+//   12  128x128    64     3      1      K >= 3072: whole 128-byte lines per row and two K-steps in flight
+//   13  256x256    64     2      1      >= 150 tiles of 256x256: half the bytes fetched per flop
 static int choose_tile(const GemmArgs& a) {
-  if (forced_tile() == 1 || forced_tile() == 3) return forced_tile();
+  if (forced_tile() > 0) return forced_tile();
   const long t3 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
-  return t3 >= 150 ? 3 : 1;
+  if (t3 >= 150) return 13;
+  if (a.K >= 3072) return 12;
+  return 1;
 }
 
 template <typename T>
 static void gemm_mfma_dispatch(hipStream_t s, const GemmArgs& a) {
   switch (choose_tile(a)) {
-    case 3: gemm_mfma_launch<T, 256, 256, 2, 4>(s, a); break;
-    default: gemm_mfma_launch<T, 128, 128, 2, 2>(s, a); break;
+    case 13: gemm_mfma_launch<T, 256, 256, 2, 4, 64, 2>(s, a); break;
+    case 12: gemm_mfma_launch<T, 128, 128, 2, 2, 64, 3>(s, a); break;
+    default: gemm_mfma_launch<T, 128, 128, 2, 2, 32, 3>(s, a); break;
   }
 }
 
