@@ -20,7 +20,8 @@
 //    the 4 k-values of one row).
 //  * Math: fragments of the next half K-step are read while the MFMAs of the current one execute (software pipeline
 //    across the barrier, pinned with scheduling fences).  Accumulators are produced transposed (B fragment first), so
-//    a lane holds 4 consecutive columns of one output row and the epilogue moves 8 bytes per access.
+//    a lane holds 4 consecutive columns of one output row; the epilogue bounces 32-row strips through LDS so that the
+//    bias / ReLU / ReLU-mask / residual reads and the stores are whole 128-byte lines.
 //  * Block ids are re-mapped so that each XCD (blocks are dealt round-robin to the 8 XCDs, each with its own L2) works
 //    on a contiguous run of tiles.
 //  * Weight-gradient shapes with few output tiles split K across blockIdx.y; fp32 partial tiles are added in a fixed
@@ -236,66 +237,80 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);                    // drain the trailing (zero-fill) loads before LDS is released
 
-  if (p.partial) {                                        // split-K: raw fp32 tile, summed by splitk_reduce_kernel
-    float* P = p.partial + (size_t)blockIdx.y * p.M * p.N;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int m = m0 + wm * (BM / WM) + i * 32 + (lane & 31);
-      if (m >= p.M) continue;
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-          const int n = n0 + wn * (BN / WN) + j * 32 + rg * 8 + (lane >> 5) * 4;
-          if (n >= p.N) continue;
-          float4 v = {acc[i][j][rg * 4], acc[i][j][rg * 4 + 1], acc[i][j][rg * 4 + 2], acc[i][j][rg * 4 + 3]};
-          *reinterpret_cast<float4*>(P + (size_t)m * p.N + n) = v;
-        }
-    }
-    return;
-  }
-  // epilogue: lane owns row m, and for each (j, rg) 4 consecutive columns
+  // Epilogue.  The accumulators hold, per lane, 4 consecutive columns of one row, which would make every store an
+  // 8-byte fragment of a different cache line.  Each wavefront therefore bounces one 32 x (TN*32) strip at a time through
+  // its own slice of LDS (free now: every wavefront is past its last fragment read) and re-reads it so that a lane owns
+  // 16 consecutive columns of a row and 4 lanes cover a whole 128-byte line of the output.
+  __syncthreads();
+  constexpr int SW = TN * 32;                             // strip width in columns
+  constexpr int SP = SW + 4;                              // padded pitch in floats: conflict-free for both passes
+  static_assert(NW * 32 * SP * 4 <= STAGES * (OA::TILE_BYTES + OB::TILE_BYTES), "epilogue staging must fit in the ring");
+  float* strip = reinterpret_cast<float*>(&As[0][0]) + wave * (32 * SP);
+  static_assert(sizeof(As) % 16 == 0, "Bs follows As contiguously");
+  constexpr int LPR = SW / 16;                            // lanes per row when re-reading (4 for a 64-column strip)
+  constexpr int RPP = 64 / LPR;                           // rows per pass
   const T* bias = reinterpret_cast<const T*>(p.bias);
   const T* mask = reinterpret_cast<const T*>(p.mask);
   const T* res = reinterpret_cast<const T*>(p.residual);
   T* C = reinterpret_cast<T*>(p.C);
+  float* P = p.partial ? p.partial + (size_t)blockIdx.y * p.M * p.N : nullptr;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wm * (BM / WM) + i * 32 + (lane & 31);
-    if (m >= p.M) continue;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
-        const int n = n0 + wn * (BN / WN) + j * 32 + rg * 8 + (lane >> 5) * 4;
-        if (n >= p.N) continue;
-        float v[4];
+        float4 v = {acc[i][j][rg * 4], acc[i][j][rg * 4 + 1], acc[i][j][rg * 4 + 2], acc[i][j][rg * 4 + 3]};
+        *reinterpret_cast<float4*>(strip + (lane & 31) * SP + j * 32 + rg * 8 + (lane >> 5) * 4) = v;
+      }
+    // (LDS operations of one wavefront complete in order: the reads below see the writes above)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][rg * 4 + e];
+    for (int ps = 0; ps < 32 / RPP; ++ps) {
+      const int r = ps * RPP + lane / LPR, c = (lane % LPR) * 16;
+      float v[16];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 t = *reinterpret_cast<const float4*>(strip + r * SP + c + q * 4);
+        v[q * 4] = t.x; v[q * 4 + 1] = t.y; v[q * 4 + 2] = t.z; v[q * 4 + 3] = t.w;
+      }
+      const int m = m0 + wm * (BM / WM) + i * 32 + r;
+      const int n = n0 + wn * (BN / WN) + c;
+      if (m >= p.M) continue;
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {                    // two groups of 8 columns, each entirely inside or outside N
+        const int nn = n + hf * 8;
+        if (nn >= p.N) continue;
+        float w[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = v[hf * 8 + e];
+        if (P) {                                          // split-K: raw fp32 tile, summed by splitk_reduce_kernel
+          store_f<float, 8>(P + (size_t)m * p.N + nn, w);
+          continue;
+        }
         if (bias) {
-          float b[4];
-          load_f<T, 4>(bias + n, b);
+          float bb[8];
+          load_f<T, 8>(bias + nn, bb);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += b[e];
+          for (int e = 0; e < 8; ++e) w[e] += bb[e];
         }
         if (p.relu) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+          for (int e = 0; e < 8; ++e) w[e] = fmaxf(w[e], 0.f);
         }
-        const size_t o = (size_t)m * p.ldc + n;
+        const size_t o = (size_t)m * p.ldc + nn;
         if (mask) {
-          float k[4];
-          load_f<T, 4>(mask + o, k);
+          float k[8];
+          load_f<T, 8>(mask + o, k);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = k[e] > 0.f ? v[e] : 0.f;
+          for (int e = 0; e < 8; ++e) w[e] = k[e] > 0.f ? w[e] : 0.f;
         }
         if (res) {
-          float k[4];
-          load_f<T, 4>(res + o, k);
+          float k[8];
+          load_f<T, 8>(res + o, k);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += k[e];
+          for (int e = 0; e < 8; ++e) w[e] += k[e];
         }
-        store_f<T, 4>(C + o, v);
+        store_f<T, 8>(C + o, w);
       }
     }
   }
