@@ -127,6 +127,12 @@ int tfm_train_step(tfm_ctx* ctx, const int32_t* src, const int32_t* tgt, const i
  * too-small scale is then reported by the next call that synchronises). */
 int tfm_apply_update(tfm_ctx* ctx, float lr, tfm_update_out* out);
 
+/* The backward pass enqueues weight-gradient GEMMs and bias column sums on a second stream that the context owns
+ * (non-blocking, default priority), ordered against hip_stream with events and joined before tfm_train_step's
+ * inf/nan scan, so callers see one stream's semantics.  on = 0 puts everything on hip_stream; the results are
+ * bit-identical either way.  Default: on. */
+int tfm_set_overlap(tfm_ctx* ctx, int32_t on);
+
 /* Test hook: the NEXT tfm_train_step multiplies its loss scale by mult (forces an overflow with 1e6 or inf). */
 int tfm_debug_set_loss_multiplier(tfm_ctx* ctx, float mult);
 

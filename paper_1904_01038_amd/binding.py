@@ -80,6 +80,7 @@ def lib():
         L.tfm_train_step.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, C.POINTER(StepOut)]
         L.tfm_apply_update.argtypes = [vp, f32, C.POINTER(UpdateOut)]
         L.tfm_debug_set_loss_multiplier.argtypes = [vp, f32]
+        L.tfm_set_overlap.argtypes = [vp, i32]
         L.tfm_profile_enable.argtypes = [vp, i32]
         L.tfm_profile_read.argtypes = [vp, C.POINTER(ProfEntry), i32]
         L.tfm_op_gemm.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, vp]
@@ -220,6 +221,9 @@ class Tfm:
             return None
         return dict(skipped=out.skipped, loss_scale_after=out.loss_scale_after, clean_steps=out.clean_steps,
                     num_updates=out.num_updates, grad_norm=out.grad_norm, ntokens_total=out.ntokens_total)
+
+    def set_overlap(self, on):
+        self._check(self._L.tfm_set_overlap(self._h, 1 if on else 0))
 
     def debug_set_loss_multiplier(self, mult):
         self._check(self._L.tfm_debug_set_loss_multiplier(self._h, mult))

@@ -73,6 +73,13 @@ struct ProfRec { int cls; hipEvent_t a, b; double flops, bytes; };
 struct tfm_ctx {
   tfm_config cfg;
   hipStream_t stream;
+  // Weight gradients and bias column sums have no consumer before the end of the backward pass, so they run on a
+  // second stream beside the chain of input gradients and fill the compute units that chain leaves idle.
+  hipStream_t side;
+  bool overlap;
+  std::vector<hipEvent_t> sync_ev;                  // ordering events, handed out in sequence within a step
+  size_t sync_used;
+  hipEvent_t side_s1, side_blk;                     // side-stream marks of the block just enqueued (null: none)
   char err[256];
   int dt;                  // compute dtype
   size_t esz;              // its size
@@ -88,6 +95,7 @@ struct tfm_ctx {
   void *y, *dcur, *dsA, *dsB, *dy, *dctx, *dinter, *dq, *dkv, *dmemA, *dmemB, *logits;
   float *loss_rows, *nll_rows, *pe;
   void *red_scratch, *scan_scratch, *splitk_ws;
+  void *red_scratch_side, *splitk_ws_side;          // the side stream's own reduction scratch
   size_t splitk_bytes;
   int *labels, *uentries, *ibase;                   // device ints (ibase = start of the int block)
   int *seg_tok, *seg_beg, *seg_end, *seg_dst, *mt_tok, *mt_row0, *mt_n;
@@ -268,9 +276,11 @@ size_t carve(tfm_ctx* c, char* base) {
   c->pe = (float*)a.take((size_t)cf.max_len * d * 4);
   const size_t red = std::max(layernorm_bwd_scratch_bytes((int)R, (int)d), colsum_scratch_bytes((int)R, (int)wide));
   c->red_scratch = a.take(red);
+  c->red_scratch_side = a.take(colsum_scratch_bytes((int)R, (int)wide));
   c->scan_scratch = a.take(scan_scratch_bytes(c->P));
   c->splitk_bytes = c->dt == F32 ? 0 : (size_t)8 * 128 * 128 * 128 * sizeof(float);   // 8 slices of up to 128 tiles
   c->splitk_ws = c->splitk_bytes ? a.take(c->splitk_bytes) : nullptr;
+  c->splitk_ws_side = c->splitk_bytes ? a.take(c->splitk_bytes) : nullptr;
   // one block of ints, filled by a single host-to-device copy per step:
   // enc ids, pos [R each], off [B+1]; dec ids, pos, off; labels [R]; occurrence entries [2R];
   // segments: tok, beg, end, dst [NS each]; multi-segment tokens: tok, row0, n [NM each]
@@ -292,17 +302,41 @@ size_t carve(tfm_ctx* c, char* base) {
 
 // ---- profiling wrapper -------------------------------------------------------------------------------------------------
 template <typename F>
-void run(tfm_ctx* c, int cls, double flops, double bytes, F&& launch) {
+void run(tfm_ctx* c, int cls, double flops, double bytes, F&& launch, hipStream_t stream) {
   if (!c->prof) { launch(); return; }
   auto get_ev = [&]() {
     if (!c->ev_pool.empty()) { hipEvent_t e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
     hipEvent_t e; hipEventCreate(&e); return e;
   };
   ProfRec r{cls, get_ev(), get_ev(), flops, bytes};
-  hipEventRecord(r.a, c->stream);
+  hipEventRecord(r.a, stream);
   launch();
-  hipEventRecord(r.b, c->stream);
+  hipEventRecord(r.b, stream);
   c->recs.push_back(r);
+}
+template <typename F>
+void run(tfm_ctx* c, int cls, double flops, double bytes, F&& launch) { run(c, cls, flops, bytes, launch, c->stream); }
+
+// ---- ordering between the two streams -----------------------------------------------------------------------------------
+hipEvent_t mark(tfm_ctx* c, hipStream_t on) {
+  if (c->sync_used == c->sync_ev.size()) {
+    hipEvent_t e = nullptr;
+    hipEventCreateWithFlags(&e, hipEventDisableTiming);
+    c->sync_ev.push_back(e);
+  }
+  hipEvent_t e = c->sync_ev[c->sync_used++];
+  hipEventRecord(e, on);
+  return e;
+}
+// what has been enqueued on `from` so far happens before what is enqueued on `to` from now on
+inline void order(tfm_ctx* c, hipStream_t from, hipStream_t to) { hipStreamWaitEvent(to, mark(c, from), 0); }
+inline hipStream_t wstream(tfm_ctx* c) { return c->overlap ? c->side : c->stream; }
+// main -> side: the operands of the weight-gradient work enqueued next are ready
+inline void side_begin(tfm_ctx* c) { if (c->overlap) order(c, c->stream, c->side); }
+// main waits for a side mark (before it overwrites what that side work reads)
+inline void main_wait(tfm_ctx* c, hipEvent_t& e) {
+  if (c->overlap && e) hipStreamWaitEvent(c->stream, e, 0);
+  e = nullptr;
 }
 
 void prof_collect(tfm_ctx* c) {
@@ -323,14 +357,20 @@ inline void* wh(tfm_ctx* c, int i) { return (char*)c->Wh + c->params[i].off * c-
 inline void* gr(tfm_ctx* c, int i) { return (char*)c->g + c->params[i].off * c->esz; }
 
 void gemm(tfm_ctx* c, int form, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C, int ldc,
-          const void* bias = nullptr, int relu = 0, const void* mask = nullptr, const void* residual = nullptr) {
+          const void* bias = nullptr, int relu = 0, const void* mask = nullptr, const void* residual = nullptr, bool side = false) {
   if (M <= 0 || N <= 0) return;
   GemmArgs a{c->dt, form, M, N, K, A, lda, B, ldb, C, ldc, bias, relu, mask, residual};
-  a.splitk_ws = c->splitk_ws;
+  side = side && c->overlap;
+  hipStream_t stream = side ? c->side : c->stream;
+  a.splitk_ws = side ? c->splitk_ws_side : c->splitk_ws;
   a.splitk_ws_bytes = c->splitk_bytes;
   // algorithmic bytes: each operand read once, the result written once (plus the epilogue's mask/residual reads)
   const double bytes = (double)c->esz * ((double)M * K + (double)K * N + (double)M * N * (1.0 + (mask ? 1.0 : 0.0) + (residual ? 1.0 : 0.0)));
-  run(c, TFM_PROF_GEMM, 2.0 * M * N * K, bytes, [&] { launch_gemm(c->stream, a); });
+  run(c, TFM_PROF_GEMM, 2.0 * M * N * K, bytes, [&] { launch_gemm(stream, a); }, stream);
+}
+// weight gradient dW[M,N] = A^T B over K rows, on the side stream
+inline void wgrad(tfm_ctx* c, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C, int ldc) {
+  gemm(c, 2, M, N, K, A, lda, B, ldb, C, ldc, nullptr, 0, nullptr, nullptr, true);
 }
 
 double attn_flops(const std::vector<int>& lq, const std::vector<int>& lk, int d, bool causal) {
@@ -379,6 +419,12 @@ int tfm_create(const tfm_config* cfg, void* ws, size_t bytes, void* hip_stream, 
   c->count.assign(cfg->vocab, 0);
   c->next_mult = 1.f;
   auto cleanup = [&](int code) { tfm_destroy(c); return code; };
+  if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) {
+    c->side = nullptr;
+    fail(nullptr, TFM_EHIP, "cannot create the side stream");
+    return cleanup(TFM_EHIP);
+  }
+  c->overlap = true;
   // zero parameters, moments, gradients and the accumulator (they are contiguous at the start of the workspace)
   hipError_t e = hipMemsetAsync(ws, 0, (char*)c->st - (char*)ws + sizeof(DevState), c->stream);
   if (e != hipSuccess) { fail(nullptr, TFM_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); return cleanup(TFM_EHIP); }
@@ -410,6 +456,8 @@ int tfm_create(const tfm_config* cfg, void* ws, size_t bytes, void* hip_stream, 
 void tfm_destroy(tfm_ctx* c) {
   if (!c) return;
   hipStreamSynchronize(c->stream);
+  if (c->side) { hipStreamSynchronize(c->side); hipStreamDestroy(c->side); }
+  for (hipEvent_t e : c->sync_ev) hipEventDestroy(e);
   for (int i = 0; i < STAGE_SLOTS; ++i) {
     if (c->stage[i]) hipHostFree(c->stage[i]);
     if (c->stage_ev[i]) hipEventDestroy(c->stage_ev[i]);
@@ -506,6 +554,12 @@ int tfm_set_scaler(tfm_ctx* c, float loss_scale, int32_t clean_steps, int64_t nu
   h.loss_scale = loss_scale; h.clean_steps = clean_steps; h.num_updates = num_updates;
   HIP_TRY(c, hipMemcpyAsync(c->st, &h, sizeof(h), hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return TFM_OK;
+}
+
+int tfm_set_overlap(tfm_ctx* c, int32_t on) {
+  if (!c) return TFM_EINVAL;
+  c->overlap = on != 0;
   return TFM_OK;
 }
 
@@ -640,8 +694,11 @@ void stream_fwd(const StepCtx& s, Stream& st) {
   }
 }
 
+// bias gradient, on the side stream
 void colsum(tfm_ctx* c, const void* x, int ld, int rows, int n, void* out) {
-  run(c, TFM_PROF_NORM, 0.0, (double)c->esz * rows * n, [&] { launch_colsum(c->stream, c->dt, x, ld, rows, n, out, c->red_scratch); });
+  hipStream_t stream = wstream(c);
+  void* scratch = c->overlap ? c->red_scratch_side : c->red_scratch;
+  run(c, TFM_PROF_NORM, 0.0, (double)c->esz * rows * n, [&] { launch_colsum(stream, c->dt, x, ld, rows, n, out, scratch); }, stream);
 }
 
 // backward of sub-layer k given dy; writes the gradient w.r.t. its input (plus `residual` if given) to dout
@@ -651,40 +708,55 @@ void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const voi
   Block& b = st.blocks[k];
   const int d = c->cfg.d_model, F = c->cfg.d_ffn, T = st.rows;
   const std::vector<int>& len = st.id ? s.tlen : s.slen;
+  // Side stream, part 1: the output projection's weight gradient needs only dy.  Part 2: the input projection's
+  // weight and bias gradients need the gradient this block writes into dinter / dq / dkv.  The main stream waits for
+  // part 2 of the PREVIOUS block right before it overwrites those buffers, and for part 1 of this block before the
+  // next LayerNorm backward overwrites dy (see stream_bwd).
+  side_begin(c);
   if (b.kind == SELF) {
-    gemm(c, 2, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d);
+    wgrad(c, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d);
+    if (c->overlap) c->side_s1 = mark(c, c->side);
     gemm(c, 1, T, d, d, dy, d, wh(c, b.w_o), d, c->dctx, d);
     const char* qkv = (const char*)b.inter;
     char* dqkv = (char*)c->dinter;
+    main_wait(c, c->side_blk);
     attention(s, true, st, st, len, len, qkv, 3 * d, qkv + d * c->esz, 3 * d, qkv + 2 * d * c->esz, 3 * d, b.ctx, b.lse, st.id == 1,
               c->dctx, dqkv, 3 * d, dqkv + d * c->esz, 3 * d, dqkv + 2 * d * c->esz, 3 * d);
-    gemm(c, 2, 3 * d, d, T, dqkv, 3 * d, fin, d, gr(c, b.w_a), d);
+    side_begin(c);
+    wgrad(c, 3 * d, d, T, dqkv, 3 * d, fin, d, gr(c, b.w_a), d);
     colsum(c, dqkv, 3 * d, T, 3 * d, gr(c, b.b_a));
     gemm(c, 1, T, d, 3 * d, dqkv, 3 * d, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
   } else if (b.kind == CROSS) {
     Stream& en = c->enc;
     const void* mem = en.norm[en.blocks.size()];
-    gemm(c, 2, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d);
+    wgrad(c, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d);
+    if (c->overlap) c->side_s1 = mark(c, c->side);
     gemm(c, 1, T, d, d, dy, d, wh(c, b.w_o), d, c->dctx, d);
     const char* kv = (const char*)b.kv;
     char* dkv = (char*)c->dkv;
+    main_wait(c, c->side_blk);
     attention(s, true, st, en, s.tlen, s.slen, b.inter, d, kv, 2 * d, kv + d * c->esz, 2 * d, b.ctx, b.lse, false, c->dctx,
               c->dq, d, dkv, 2 * d, dkv + d * c->esz, 2 * d);
-    gemm(c, 2, d, d, T, c->dq, d, fin, d, gr(c, b.w_a), d);
+    side_begin(c);
+    wgrad(c, d, d, T, c->dq, d, fin, d, gr(c, b.w_a), d);
     colsum(c, c->dq, d, T, d, gr(c, b.b_a));
-    gemm(c, 1, T, d, d, c->dq, d, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
-    gemm(c, 2, 2 * d, d, en.rows, dkv, 2 * d, mem, d, gr(c, b.w_kv), d);
+    wgrad(c, 2 * d, d, en.rows, dkv, 2 * d, mem, d, gr(c, b.w_kv), d);
     colsum(c, dkv, 2 * d, en.rows, 2 * d, gr(c, b.b_kv));
+    gemm(c, 1, T, d, d, c->dq, d, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
     gemm(c, 1, en.rows, d, 2 * d, dkv, 2 * d, wh(c, b.w_kv), d, *dmem_other, d, nullptr, 0, nullptr, *dmem_valid ? *dmem_cur : nullptr);
     std::swap(*dmem_cur, *dmem_other);
     *dmem_valid = true;
   } else {
-    gemm(c, 2, d, F, T, dy, d, b.inter, F, gr(c, b.w_o), F);
+    wgrad(c, d, F, T, dy, d, b.inter, F, gr(c, b.w_o), F);
+    if (c->overlap) c->side_s1 = mark(c, c->side);
+    main_wait(c, c->side_blk);
     gemm(c, 1, T, F, d, dy, d, wh(c, b.w_o), F, c->dinter, F, nullptr, 0, b.inter, nullptr);
-    gemm(c, 2, F, d, T, c->dinter, F, fin, d, gr(c, b.w_a), d);
+    side_begin(c);
+    wgrad(c, F, d, T, c->dinter, F, fin, d, gr(c, b.w_a), d);
     colsum(c, c->dinter, F, T, F, gr(c, b.b_a));
     gemm(c, 1, T, d, F, c->dinter, F, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
   }
+  if (c->overlap) c->side_blk = mark(c, c->side);
 }
 
 void ln_bwd(tfm_ctx* c, const void* dn, const void* add, const void* sres, const float* mean, const float* rstd, int g, int b,
@@ -711,6 +783,7 @@ void* stream_bwd(const StepCtx& s, Stream& st, void** dmem_cur, void** dmem_othe
   if (!pre) {
     for (int k = K - 1; k >= 0; --k) {
       Block& b = st.blocks[k];
+      main_wait(c, c->side_s1);                // the previous block's first weight gradient still reads dy / dsA
       ln_bwd(c, dn, nullptr, st.resid[k + 1], st.mean[k + 1], st.rstd[k + 1], b.ln_g, b.ln_b, c->dsA, c->dy, b.b_o, T, block_key(s, st, k));
       const void* dy = drop ? c->dy : c->dsA;
       void* out = k == 0 ? c->demb[st.id] : c->dcur;
@@ -728,6 +801,7 @@ void* stream_bwd(const StepCtx& s, Stream& st, void** dmem_cur, void** dmem_othe
     const int b = idx < K ? st.blocks[idx].ln_b : st.lnf_b;
     const int bias = idx >= 1 ? st.blocks[idx - 1].b_o : -1;
     if (idx == 0) ds = c->demb[st.id];
+    main_wait(c, c->side_s1);
     ln_bwd(c, dn, dR, st.resid[idx], st.mean[idx], st.rstd[idx], g, b, ds, idx >= 1 ? c->dy : nullptr, bias, T,
            idx >= 1 ? block_key(s, st, idx - 1) : 0);
     if (idx == 0) return ds;
@@ -871,7 +945,10 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   });
 
   // ---- backward
-  gemm(c, 2, V, d, (int)Tt, c->logits, V, top, d, c->g, d);               // embedding gradient, output side
+  c->sync_used = 0;
+  c->side_s1 = c->side_blk = nullptr;
+  side_begin(c);
+  wgrad(c, V, d, (int)Tt, c->logits, V, top, d, c->g, d);                  // embedding gradient, output side
   gemm(c, 1, (int)Tt, d, V, c->logits, V, c->Wh, d, c->dcur, d);
   void* dmem_cur = c->dmemA;
   void* dmem_other = c->dmemB;
@@ -879,6 +956,8 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   void* ddec = stream_bwd(s, de, &dmem_cur, &dmem_other, &dmem_valid, c->dcur);
   void* denc = nullptr;
   if (has_enc) denc = stream_bwd(s, c->enc, &dmem_cur, &dmem_other, &dmem_valid, dmem_cur);
+  if (c->overlap) order(c, c->side, c->stream);                            // join: every weight gradient is in g
+  c->side_s1 = c->side_blk = nullptr;
   run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * d * ((double)Ts + Tt + 2.0 * nu), [&] {
     EmbedBwdArgs ea{};
     ea.dt = c->dt; ea.gE = c->g; ea.partial = c->emb_partial;

@@ -110,3 +110,22 @@ def test_state_round_trips_and_loss_scale_floor():
     assert L.tfm_set_adam(gpu2._h, i, 1, a.ctypes.data_as(C.c_void_p), a.size) == 0
     assert np.array_equal(gpu2.get_adam(1)["dec.0.ffn.w1"].ravel(), a)
     assert not gpu2.get_adam(0)["dec.0.ffn.w1"].any()
+
+
+def test_side_stream_gives_bit_identical_gradients():
+    import paper_1904_01038_amd as T
+    batches = make_batches("base", 3, shape=HSHAPE, max_tokens=1500, lo=20, hi=90)
+    runs = []
+    for on in (True, False):
+        gpu, _ = make_pair(HSHAPE, T.FP16, dropout=0.1, init_loss_scale=4.0, max_sentences=64, max_len=96, max_tokens=2048, seed=5)
+        gpu.set_overlap(on)
+        outs = []
+        for b in batches:                               # two accumulated sub-batches, an update, then a third step
+            outs.append(gpu.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens, sync=False))
+            if len(outs) == 2:
+                gpu.apply_update(1e-3, sync=False)
+        runs.append((gpu.get_grads(), gpu.get_params()))
+        gpu.close()
+    for k in runs[0][0]:
+        assert np.array_equal(runs[0][0][k], runs[1][0][k]), k
+        assert np.array_equal(runs[0][1][k], runs[1][1][k]), k
