@@ -64,7 +64,7 @@ struct MfmaGemmParams {
   int relu;
   const uint16_t* mask;
   const uint16_t* residual;
-  int tiles_n, tiles_total;
+  int tiles_n, tiles_m, tiles_total, group_m;
   int ksteps_per_split;                                  // split-K: K-steps per blockIdx.y slice
   float* partial;                                        // split-K: fp32 partial tiles [split][M][N], else null
   uint32_t a_bytes, b_bytes;                             // extents for the range-checked loads
@@ -157,7 +157,16 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
     const int b = blockIdx.x, nb = p.tiles_total, q = nb >> 3, r = nb & 7, x = b & 7;
     tile = x * q + (x < r ? x : r) + (b >> 3);
   }
-  const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+  // Tile ids run column-major inside bands of group_m tile rows, so the run of ids an XCD works on at one time
+  // covers a compact patch of the output and shares its A and B panels in that XCD's L2.
+  int tm, tn;
+  {
+    const int per_band = p.group_m * p.tiles_n, band = tile / per_band, in_band = tile - band * per_band;
+    const int gm = min(p.group_m, p.tiles_m - band * p.group_m);
+    tm = band * p.group_m + in_band % gm;
+    tn = in_band / gm;
+  }
+  const int m0 = tm * BM, n0 = tn * BN;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave / WN, wn = wave % WN;
 
   // raw buffer descriptors: base, stride 0, byte extent, format word
@@ -363,7 +372,12 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   p.A = (const uint16_t*)a.A; p.lda = a.lda; p.B = (const uint16_t*)a.B; p.ldb = a.ldb; p.C = (uint16_t*)a.C; p.ldc = a.ldc;
   p.bias = (const uint16_t*)a.bias; p.relu = a.relu; p.mask = (const uint16_t*)a.mask; p.residual = (const uint16_t*)a.residual;
   p.tiles_n = (a.N + BN - 1) / BN;
-  p.tiles_total = p.tiles_n * ((a.M + BM - 1) / BM);
+  p.tiles_m = (a.M + BM - 1) / BM;
+  p.tiles_total = p.tiles_n * p.tiles_m;
+  {
+    static const int g_env = [] { const char* e = getenv("TFM_GEMM_GROUP"); return e ? atoi(e) : 0; }();
+    p.group_m = g_env > 0 ? g_env : 8;
+  }
   p.a_bytes = (uint32_t)(a.form == 2 ? extent_bytes(a.K, a.M, a.lda) : extent_bytes(a.M, a.K, a.lda));
   p.b_bytes = (uint32_t)(a.form == 0 ? extent_bytes(a.N, a.K, a.ldb) : extent_bytes(a.K, a.N, a.ldb));
   // Split-K for weight-gradient shapes whose output has too few tiles to fill the chip: slices of K go to

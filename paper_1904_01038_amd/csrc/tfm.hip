@@ -80,6 +80,15 @@ struct tfm_ctx {
   std::vector<hipEvent_t> sync_ev;                  // ordering events, handed out in sequence within a step
   size_t sync_used;
   hipEvent_t side_s1, side_blk;                     // side-stream marks of the block just enqueued (null: none)
+  // The Adam step also runs on the side stream, cut into chunks in the order the forward pass first touches the
+  // parameters (the flat order), so the next sub-batch's forward pass starts while later layers are still being
+  // updated: it waits chunk by chunk.  Every other entry point first waits for the whole update.
+  struct Chunk { int64_t off, n; int last_param; };
+  std::vector<Chunk> chunks;
+  std::vector<int> chunk_of;                        // parameter index -> chunk
+  std::vector<hipEvent_t> adam_ev;                  // one per chunk
+  bool adam_pending;
+  int adam_waited;                                  // chunks the main stream already waits for
   char err[256];
   int dt;                  // compute dtype
   size_t esz;              // its size
@@ -352,6 +361,18 @@ void prof_collect(tfm_ctx* c) {
   c->recs.clear();
 }
 
+// main stream: the pending Adam update of parameter pi (and of everything before it in flat order) has finished
+inline void need(tfm_ctx* c, int pi) {
+  if (!c->adam_pending) return;
+  const int ch = c->chunk_of[pi];
+  if (ch >= c->adam_waited) {
+    hipStreamWaitEvent(c->stream, c->adam_ev[ch], 0);
+    c->adam_waited = ch + 1;
+    if (c->adam_waited == (int)c->chunks.size()) c->adam_pending = false;
+  }
+}
+inline void adam_join(tfm_ctx* c) { if (c->adam_pending) need(c, (int)c->params.size() - 1); }
+
 // ---- small helpers over the flat parameter buffers ----------------------------------------------------------------------
 inline void* wh(tfm_ctx* c, int i) { return (char*)c->Wh + c->params[i].off * c->esz; }
 inline void* gr(tfm_ctx* c, int i) { return (char*)c->g + c->params[i].off * c->esz; }
@@ -425,6 +446,25 @@ int tfm_create(const tfm_config* cfg, void* ws, size_t bytes, void* hip_stream, 
     return cleanup(TFM_EHIP);
   }
   c->overlap = true;
+  {
+    // chunk boundaries: the embedding, then one chunk per block (its parameters are contiguous), final norms with
+    // the block before them
+    std::vector<int> first;                         // first parameter of each chunk
+    first.push_back(0);
+    for (Stream* st : {&c->enc, &c->dec})
+      for (Block& b : st->blocks) first.push_back(b.w_a);
+    std::sort(first.begin(), first.end());
+    c->chunk_of.assign(c->params.size(), 0);
+    for (size_t k = 0; k < first.size(); ++k) {
+      const int p0 = first[k], p1 = k + 1 < first.size() ? first[k + 1] : (int)c->params.size();
+      const int64_t o0 = c->params[p0].off, o1 = p1 < (int)c->params.size() ? c->params[p1].off : c->P;
+      c->chunks.push_back({o0, o1 - o0, p1 - 1});
+      for (int i = p0; i < p1; ++i) c->chunk_of[i] = (int)k;
+      hipEvent_t e = nullptr;
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { fail(nullptr, TFM_EHIP, "cannot create events"); return cleanup(TFM_EHIP); }
+      c->adam_ev.push_back(e);
+    }
+  }
   // zero parameters, moments, gradients and the accumulator (they are contiguous at the start of the workspace)
   hipError_t e = hipMemsetAsync(ws, 0, (char*)c->st - (char*)ws + sizeof(DevState), c->stream);
   if (e != hipSuccess) { fail(nullptr, TFM_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); return cleanup(TFM_EHIP); }
@@ -458,6 +498,7 @@ void tfm_destroy(tfm_ctx* c) {
   hipStreamSynchronize(c->stream);
   if (c->side) { hipStreamSynchronize(c->side); hipStreamDestroy(c->side); }
   for (hipEvent_t e : c->sync_ev) hipEventDestroy(e);
+  for (hipEvent_t e : c->adam_ev) hipEventDestroy(e);
   for (int i = 0; i < STAGE_SLOTS; ++i) {
     if (c->stage[i]) hipHostFree(c->stage[i]);
     if (c->stage_ev[i]) hipEventDestroy(c->stage_ev[i]);
@@ -483,6 +524,7 @@ int tfm_param_info(const tfm_ctx* c, int32_t i, char name[64], int64_t shape[2])
 }
 
 static int check_param(tfm_ctx* c, int32_t i, const void* host, int64_t n) {
+  if (c) adam_join(c);
   if (!c) return TFM_EINVAL;
   if (i < 0 || i >= (int)c->params.size()) return fail(c, TFM_EINVAL, "parameter index %d out of range", i);
   if (!host || n != c->params[i].numel()) return fail(c, TFM_EINVAL, "parameter %d has %lld elements, got %lld", i, (long long)c->params[i].numel(), (long long)n);
@@ -536,6 +578,7 @@ int tfm_set_adam(tfm_ctx* c, int32_t i, int32_t which, const float* host, int64_
 
 int tfm_get_scaler(tfm_ctx* c, float* loss_scale, int32_t* clean_steps, int64_t* num_updates) {
   if (!c) return TFM_EINVAL;
+  adam_join(c);
   DevState h;
   HIP_TRY(c, hipMemcpyAsync(&h, c->st, sizeof(h), hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -547,6 +590,7 @@ int tfm_get_scaler(tfm_ctx* c, float* loss_scale, int32_t* clean_steps, int64_t*
 
 int tfm_set_scaler(tfm_ctx* c, float loss_scale, int32_t clean_steps, int64_t num_updates) {
   if (!c) return TFM_EINVAL;
+  adam_join(c);
   if (!(loss_scale > 0.f) || clean_steps < 0 || num_updates < 0) return fail(c, TFM_EINVAL, "bad scaler state");
   DevState h;
   HIP_TRY(c, hipMemcpyAsync(&h, c->st, sizeof(h), hipMemcpyDeviceToHost, c->stream));
@@ -559,11 +603,13 @@ int tfm_set_scaler(tfm_ctx* c, float loss_scale, int32_t clean_steps, int64_t nu
 
 int tfm_set_overlap(tfm_ctx* c, int32_t on) {
   if (!c) return TFM_EINVAL;
+  adam_join(c);
   c->overlap = on != 0;
   return TFM_OK;
 }
 
 int tfm_debug_set_loss_multiplier(tfm_ctx* c, float mult) {
+  if (c) adam_join(c);
   if (!c) return TFM_EINVAL;
   c->next_mult = mult;
   return TFM_OK;
@@ -571,6 +617,7 @@ int tfm_debug_set_loss_multiplier(tfm_ctx* c, float mult) {
 
 int tfm_profile_enable(tfm_ctx* c, int32_t on) {
   if (!c) return TFM_EINVAL;
+  adam_join(c);
   c->prof = on != 0;
   if (c->prof) {
     // calibrate: the time between two events recorded back to back is bracket overhead, not kernel time
@@ -597,6 +644,7 @@ int tfm_profile_enable(tfm_ctx* c, int32_t on) {
 
 int tfm_profile_read(tfm_ctx* c, tfm_prof_entry out[TFM_PROF_CLASSES], int32_t reset) {
   if (!c || !out) return TFM_EINVAL;
+  adam_join(c);
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   prof_collect(c);
   std::memcpy(out, c->prof_acc, sizeof(c->prof_acc));
@@ -647,6 +695,7 @@ void sublayer_fwd(const StepCtx& s, Stream& st, int k, const void* fin, void* y)
   Block& b = st.blocks[k];
   const int d = c->cfg.d_model, F = c->cfg.d_ffn, T = st.rows;
   const std::vector<int>& len = st.id ? s.tlen : s.slen;
+  need(c, b.ln_b);                                 // the block's parameters are one Adam chunk
   if (b.kind == SELF) {
     gemm(c, 0, T, 3 * d, d, fin, d, wh(c, b.w_a), d, b.inter, 3 * d, wh(c, b.b_a));
     const char* qkv = (const char*)b.inter;
@@ -669,6 +718,7 @@ void sublayer_fwd(const StepCtx& s, Stream& st, int k, const void* fin, void* y)
 void ln_fwd(tfm_ctx* c, const void* x, const void* y, int g, int b, void* s_out, void* n_out, float* mean, float* rstd,
             int rows, uint64_t key) {
   const int d = c->cfg.d_model;
+  need(c, b);
   const double bytes = (double)c->esz * rows * d * (1.0 + (y ? 1.0 : 0.0) + (s_out ? 1.0 : 0.0) + 1.0);
   run(c, TFM_PROF_NORM, 0.0, bytes, [&] {
     launch_residual_layernorm_fwd(c->stream, c->dt, x, y, wh(c, g), wh(c, b), s_out, n_out, mean, rstd, rows, d, key, c->cfg.dropout);
@@ -680,6 +730,7 @@ void stream_fwd(const StepCtx& s, Stream& st) {
   const int K = (int)st.blocks.size(), d = c->cfg.d_model, T = st.rows;
   const bool pre = c->cfg.pre_norm != 0;
   void* emb = pre ? st.resid[0] : st.norm[0];
+  need(c, 0);
   run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * T * d * 2.0, [&] {
     launch_embed_fwd(c->stream, c->dt, c->Wh, st.ids, st.pos, c->pe, emb, T, d, site_key(s, st.id, -1, 0), c->cfg.dropout);
   });
@@ -935,6 +986,7 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   Stream& de = c->dec;
   const int Kd = (int)de.blocks.size();
   const void* top = de.norm[Kd];
+  adam_join(c);                                    // every parameter has been touched by now; nothing is left pending
   gemm(c, 0, (int)Tt, V, d, top, d, c->Wh, d, c->logits, V);
   const float mult = c->next_mult;
   c->next_mult = 1.f;
@@ -991,6 +1043,7 @@ int tfm_apply_update(tfm_ctx* c, float lr, tfm_update_out* out) {
   if (!c) return TFM_EINVAL;
   if (c->window_mb == 0) return fail(c, TFM_ESTATE, "no sub-batch has been accumulated");
   if (!std::isfinite(lr)) return fail(c, TFM_EINVAL, "learning rate is not finite");
+  adam_join(c);
   const tfm_config& cf = c->cfg;
   const bool single = c->window_mb == 1;
   // the scan of a single sub-batch already produced the sum of squares; an accumulated window is scanned again
@@ -1006,12 +1059,31 @@ int tfm_apply_update(tfm_ctx* c, float lr, tfm_update_out* out) {
   a.g = single ? c->g : (const void*)c->G; a.gdt = single ? c->dt : (int)F32;
   a.half_copy = c->dt == F32 ? nullptr : c->Wh; a.hdt = c->dt;
   a.lr = lr; a.beta1 = cf.adam_beta1; a.beta2 = cf.adam_beta2; a.eps = cf.adam_eps; a.st = c->st;
-  run(c, TFM_PROF_OPTIM, 0.0, (double)c->P * (24.0 + (single ? c->esz : 4.0) + (c->dt == F32 ? 0.0 : 2.0)), [&] { launch_adam(c->stream, a); });
+  const double bpp = 24.0 + (single ? c->esz : 4.0) + (c->dt == F32 ? 0.0 : 2.0);
+  if (!c->overlap) {
+    run(c, TFM_PROF_OPTIM, 0.0, (double)c->P * bpp, [&] { launch_adam(c->stream, a); });
+  } else {
+    c->sync_used = 0;
+    order(c, c->stream, c->side);                  // the step scalars are in the device state
+    const size_t gsz = single ? c->esz : 4;
+    for (size_t k = 0; k < c->chunks.size(); ++k) {
+      const tfm_ctx::Chunk& ch = c->chunks[k];
+      AdamArgs b = a;
+      b.w = c->W + ch.off; b.m = c->M + ch.off; b.v = c->V + ch.off; b.n = ch.n;
+      b.g = (const char*)a.g + ch.off * gsz;
+      b.half_copy = a.half_copy ? (char*)a.half_copy + ch.off * c->esz : nullptr;
+      run(c, TFM_PROF_OPTIM, 0.0, (double)ch.n * bpp, [&] { launch_adam(c->side, b); }, c->side);
+      hipEventRecord(c->adam_ev[k], c->side);
+    }
+    c->adam_pending = true;
+    c->adam_waited = 0;
+  }
   const long long ntok = c->window_tokens;
   c->window_mb = 0;
   c->window_tokens = 0;
   HIP_TRY(c, hipGetLastError());
   if (out) {
+    adam_join(c);
     DevState h;
     HIP_TRY(c, hipMemcpyAsync(&h, c->st, sizeof(h), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
