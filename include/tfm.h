@@ -219,6 +219,37 @@ int tfm_op_dropout_mask(uint64_t key, float p, uint8_t* out, int64_t n, void* st
  * sub 0 self-attention, 1 cross-attention, 2 feed-forward) at a training step. */
 uint64_t tfm_dropout_key(uint64_t seed, uint64_t step, int32_t stream, int32_t layer, int32_t sub);
 
+/* ---- Steps on either side of the training step (host code, host pointers) --------------------------------- */
+
+/* Inverse-square-root learning-rate schedule (Components, Learning Rate Schedulers; the schedule of the
+ * Transformer paper it cites): update t = 1, 2, ... gets
+ *   t <= warmup:  init_lr + (peak_lr - init_lr) * t / warmup        (linear warm-up)
+ *   t >  warmup:  peak_lr * sqrt(warmup / t)
+ * With init_lr = 0 and peak_lr = (d_model * warmup)^-1/2 this is d_model^-1/2 * min(t^-1/2, t * warmup^-3/2).
+ * warmup = 0 means no warm-up: peak_lr / sqrt(max(t, 1)).  Returns NaN for t < 0 or warmup < 0. */
+double tfm_lr_inverse_sqrt(int64_t t, int64_t warmup, double peak_lr, double init_lr);
+
+/* Token-capped batches of sentences of similar length (Implementation, Batching).  Sentences are ordered by
+ * (max(src_len, tgt_len), index) ascending and cut greedily: a batch takes the next sentence while
+ * (sentences + 1) * (longest sentence so far in the batch, counting the candidate) <= max_tokens and
+ * sentences < max_sentences.  If multiple > 1, a batch that closed with at least `multiple` sentences keeps the
+ * largest multiple of `multiple` and hands the rest to the next batch; no sentence is dropped.
+ *   src_lens   host int32 [n] or NULL (language model: only tgt_lens counts)
+ *   tgt_lens   host int32 [n], every length >= 1 and <= max_tokens, else TFM_EINVAL
+ *   order      host int64 [n]      out: sentence indices, batch after batch
+ *   batch_begin host int64 [n + 1] out: batch b is order[batch_begin[b] .. batch_begin[b+1]); entries after
+ *              n_batches are not written
+ * The content of every batch is a pure function of the lengths, so it stays the same from epoch to epoch. */
+int tfm_batch_by_length(const int32_t* src_lens, const int32_t* tgt_lens, int64_t n, int32_t max_tokens,
+                        int32_t max_sentences, int32_t multiple, int64_t* order, int64_t* batch_begin,
+                        int64_t* n_batches);
+
+/* The order in which an epoch visits the batches (Implementation, Batching: batches are shuffled every epoch).
+ * perm (host int64 [n_batches]) receives a permutation of 0..n_batches-1 that depends only on (seed, epoch):
+ * a Fisher-Yates shuffle, i = n-1 down to 1, swapping position i with position r_i mod (i + 1), where r_i is the
+ * 64-bit splitmix64 finaliser of seed + 0x9E3779B97F4A7C15 * (epoch * 2^32 + i + 1). */
+int tfm_shuffle_batches(int64_t n_batches, uint64_t seed, uint64_t epoch, int64_t* perm);
+
 #ifdef __cplusplus
 }
 #endif

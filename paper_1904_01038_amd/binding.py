@@ -82,6 +82,10 @@ def lib():
         L.tfm_debug_set_loss_multiplier.argtypes = [vp, f32]
         L.tfm_set_overlap.argtypes = [vp, i32]
         L.tfm_profile_enable.argtypes = [vp, i32]
+        L.tfm_lr_inverse_sqrt.argtypes = [i64, i64, C.c_double, C.c_double]
+        L.tfm_lr_inverse_sqrt.restype = C.c_double
+        L.tfm_batch_by_length.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, C.POINTER(i64)]
+        L.tfm_shuffle_batches.argtypes = [i64, u64, u64, vp]
         L.tfm_profile_read.argtypes = [vp, C.POINTER(ProfEntry), i32]
         L.tfm_op_gemm.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, vp]
         L.tfm_op_gemm_ws.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, vp, C.c_size_t, vp]
@@ -236,3 +240,30 @@ class Tfm:
         self._check(self._L.tfm_profile_read(self._h, arr, 1 if reset else 0))
         return {n: dict(launches=arr[i].launches, ms=arr[i].ms, flops=arr[i].flops, bytes=arr[i].bytes)
                 for i, n in enumerate(PROF_CLASSES)}
+
+
+def lr_inverse_sqrt(t, warmup, peak_lr, init_lr=0.0):
+    return lib().tfm_lr_inverse_sqrt(int(t), int(warmup), float(peak_lr), float(init_lr))
+
+
+def batch_by_length(src_lens, tgt_lens, max_tokens, max_sentences, multiple=1):
+    """List of int64 index arrays, one per batch."""
+    tl = _i32(tgt_lens)
+    sl = _i32(src_lens)
+    n = len(tl)
+    order = np.empty(n, dtype=np.int64)
+    begin = np.empty(n + 1, dtype=np.int64)
+    nb = C.c_int64()
+    rc = lib().tfm_batch_by_length(_ptr(sl), _ptr(tl), n, max_tokens, max_sentences, multiple, _ptr(order), _ptr(begin),
+                                   C.byref(nb))
+    if rc:
+        raise TfmError(rc, "tfm_batch_by_length: invalid argument")
+    return [order[begin[b]:begin[b + 1]] for b in range(nb.value)]
+
+
+def shuffle_batches(n_batches, seed, epoch):
+    perm = np.empty(n_batches, dtype=np.int64)
+    rc = lib().tfm_shuffle_batches(n_batches, seed, epoch, _ptr(perm))
+    if rc:
+        raise TfmError(rc, "tfm_shuffle_batches: invalid argument")
+    return perm
