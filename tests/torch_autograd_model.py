@@ -82,3 +82,31 @@ def loss_and_grads(shape, params, batch, label_smoothing):
         total = total + F.cross_entropy(z, tgt, reduction="sum", label_smoothing=label_smoothing)
     total.backward()
     return float(total), {k: v.grad.numpy() for k, v in P.items()}
+
+
+def next_token_logprobs(shape, params, src, dec_in):
+    """log-softmax over the vocabulary at every decoder position, for one sentence (no dropout)."""
+    P = {k: torch.tensor(v, dtype=torch.float64) for k, v in params.items()}
+    d, H = shape.d_model, shape.n_heads
+    mem = None
+    if shape.enc_layers:
+        src = torch.tensor(src, dtype=torch.long)
+        x = math.sqrt(d) * P["embed"][src] + _pe(len(src), d)
+        for i in range(shape.enc_layers):
+            pre = f"enc.{i}"
+            x = _block(P, shape, pre + ".ln_self", x, lambda u: _mha(P, pre + ".self", u, u, H, False, False))
+            x = _block(P, shape, pre + ".ln_ffn", x, lambda u: _ffn(P, pre + ".ffn", u))
+        if shape.pre_norm:
+            x = _ln(P, "enc.ln_final", x)
+        mem = x
+    dec_in = torch.tensor(dec_in, dtype=torch.long)
+    y = math.sqrt(d) * P["embed"][dec_in] + _pe(len(dec_in), d)
+    for i in range(shape.dec_layers):
+        pre = f"dec.{i}"
+        y = _block(P, shape, pre + ".ln_self", y, lambda u: _mha(P, pre + ".self", u, u, H, True, False))
+        if shape.enc_layers:
+            y = _block(P, shape, pre + ".ln_cross", y, lambda u: _mha(P, pre + ".cross", u, mem, H, False, True))
+        y = _block(P, shape, pre + ".ln_ffn", y, lambda u: _ffn(P, pre + ".ffn", u))
+    if shape.pre_norm:
+        y = _ln(P, "dec.ln_final", y)
+    return F.log_softmax(y @ P["embed"].T, dim=-1).numpy()
