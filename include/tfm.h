@@ -219,6 +219,41 @@ int tfm_op_dropout_mask(uint64_t key, float p, uint8_t* out, int64_t n, void* st
  * sub 0 self-attention, 1 cross-attention, 2 feed-forward) at a training step. */
 uint64_t tfm_dropout_key(uint64_t seed, uint64_t step, int32_t stream, int32_t layer, int32_t sub);
 
+/* ---- Incremental decoding (Implementation, Inference) ------------------------------------------------------
+ * Step-wise prediction with the states of previously generated tokens cached per active beam: a step feeds ONE
+ * new token per row and returns the distribution over the next one.  Rows are sentences x beam, row = sentence *
+ * beam + slot.  The decoder borrows the context's parameters (their current half/fp32 model copy), stream and
+ * encoder buffers: do not interleave it with a window of tfm_train_step calls that has not been closed by
+ * tfm_apply_update.  Dropout is off.  The search itself (which beams continue, length penalty, stopping) is the
+ * caller's: it passes, per row, the token to feed and the row whose history this row continues. */
+typedef struct tfm_decoder tfm_decoder;
+
+/* max_rows: sentences x beam; max_steps <= config.max_len: positions a hypothesis may reach; max_src_tokens: source
+ * tokens of a batch (ignored for a decoder-only model); topk in [1, 16]: candidates returned per row and step. */
+int tfm_decoder_workspace_bytes(const tfm_ctx* ctx, int32_t max_rows, int32_t max_steps, int32_t max_src_tokens,
+                                int32_t topk, size_t* bytes);
+/* dev_workspace: device memory, 256-byte aligned, owned by the caller, alive until tfm_decoder_destroy. */
+int tfm_decoder_create(tfm_ctx* ctx, void* dev_workspace, size_t bytes, int32_t max_rows, int32_t max_steps,
+                       int32_t max_src_tokens, int32_t topk, tfm_decoder** out);
+void tfm_decoder_destroy(tfm_decoder* dec);
+
+/* Start a batch of B sentences with `beam` rows each: runs the encoder once over the sources (host int32
+ * [B, Ls] right-padded, lengths [B]; both NULL for a decoder-only model) and projects its output to every decoder
+ * layer's cross-attention keys and values; empties the caches. */
+int tfm_decoder_begin(tfm_decoder* dec, const int32_t* src, const int32_t* src_lens, int32_t B, int32_t Ls,
+                      int32_t beam);
+
+/* Step t = 0, 1, ...: row r consumes token prev[r] at position t (t = 0: the caller passes eos); its history is
+ * the one row parent[r] had after the previous step (same sentence; NULL = every row continues itself).
+ * prev, parent: host int32 [rows].  Outputs, host, [rows, topk]: the topk largest log-probabilities of the next
+ * token (fp32, natural log, computed from the logits in the compute dtype), best first, equal values in ascending
+ * id order, and their token ids.  Synchronises. */
+int tfm_decoder_step(tfm_decoder* dec, const int32_t* prev, const int32_t* parent, float* top_logp,
+                     int32_t* top_id);
+
+/* Test access: log-probabilities over the whole vocabulary of the last step, host fp32 [rows, vocab]. */
+int tfm_decoder_get_logprobs(tfm_decoder* dec, float* host, int64_t n);
+
 /* ---- Steps on either side of the training step (host code, host pointers) --------------------------------- */
 
 /* Inverse-square-root learning-rate schedule (Components, Learning Rate Schedulers; the schedule of the

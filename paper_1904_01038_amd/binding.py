@@ -82,6 +82,13 @@ def lib():
         L.tfm_debug_set_loss_multiplier.argtypes = [vp, f32]
         L.tfm_set_overlap.argtypes = [vp, i32]
         L.tfm_profile_enable.argtypes = [vp, i32]
+        L.tfm_decoder_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(C.c_size_t)]
+        L.tfm_decoder_create.argtypes = [vp, vp, C.c_size_t, i32, i32, i32, i32, C.POINTER(vp)]
+        L.tfm_decoder_destroy.argtypes = [vp]
+        L.tfm_decoder_destroy.restype = None
+        L.tfm_decoder_begin.argtypes = [vp, vp, vp, i32, i32, i32]
+        L.tfm_decoder_step.argtypes = [vp, vp, vp, vp, vp]
+        L.tfm_decoder_get_logprobs.argtypes = [vp, vp, i64]
         L.tfm_lr_inverse_sqrt.argtypes = [i64, i64, C.c_double, C.c_double]
         L.tfm_lr_inverse_sqrt.restype = C.c_double
         L.tfm_batch_by_length.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, C.POINTER(i64)]
@@ -164,6 +171,9 @@ class Tfm:
             raise TfmError(rc, self._L.tfm_last_error(self._h).decode())
 
     def close(self):
+        for dec in getattr(self, "_decoders", []):
+            dec.close()                      # a decoder uses the context's stream until it is destroyed
+        self._decoders = []
         if getattr(self, "_h", None):
             self._L.tfm_destroy(self._h)
             self._h = None
@@ -240,6 +250,60 @@ class Tfm:
         self._check(self._L.tfm_profile_read(self._h, arr, 1 if reset else 0))
         return {n: dict(launches=arr[i].launches, ms=arr[i].ms, flops=arr[i].flops, bytes=arr[i].bytes)
                 for i, n in enumerate(PROF_CLASSES)}
+
+
+class Decoder:
+    """Incremental decoding on top of a training context's parameters (argument marshalling only)."""
+
+    def __init__(self, ctx: "Tfm", max_rows, max_steps, max_src_tokens, topk):
+        import torch
+        self._L, self.ctx, self.topk = lib(), ctx, topk
+        n = C.c_size_t()
+        rc = self._L.tfm_decoder_workspace_bytes(ctx._h, max_rows, max_steps, max_src_tokens, topk, C.byref(n))
+        if rc:
+            raise TfmError(rc, "tfm_decoder_workspace_bytes: invalid sizes")
+        self.workspace = torch.empty(n.value + 256, dtype=torch.uint8, device="cuda")
+        aligned = (self.workspace.data_ptr() + 255) // 256 * 256
+        h = C.c_void_p()
+        ctx._check(self._L.tfm_decoder_create(ctx._h, C.c_void_p(aligned), n.value, max_rows, max_steps, max_src_tokens,
+                                              topk, C.byref(h)))
+        self._h = h
+        self.rows = 0
+        if not hasattr(ctx, "_decoders"):
+            ctx._decoders = []
+        ctx._decoders.append(self)
+
+    def begin(self, src, src_lens, beam, n_sentences=None):
+        src, src_lens = _i32(src), _i32(src_lens)
+        B = len(src_lens) if src_lens is not None else n_sentences
+        Ls = 0 if src is None else src.shape[1]
+        self.ctx._check(self._L.tfm_decoder_begin(self._h, _ptr(src), _ptr(src_lens), B, Ls, beam))
+        self.rows = B * beam
+
+    def step(self, prev, parent=None):
+        prev, parent = _i32(prev), _i32(parent)
+        assert len(prev) == self.rows and (parent is None or len(parent) == self.rows)
+        lp = np.empty((self.rows, self.topk), dtype=np.float32)
+        ids = np.empty((self.rows, self.topk), dtype=np.int32)
+        self.ctx._check(self._L.tfm_decoder_step(self._h, _ptr(prev), _ptr(parent), _ptr(lp), _ptr(ids)))
+        return lp, ids
+
+    def logprobs(self):
+        V = self.ctx.cfg.vocab
+        out = np.empty((self.rows, V), dtype=np.float32)
+        self.ctx._check(self._L.tfm_decoder_get_logprobs(self._h, _ptr(out), out.size))
+        return out
+
+    def close(self):
+        if self._h:
+            self._L.tfm_decoder_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def lr_inverse_sqrt(t, warmup, peak_lr, init_lr=0.0):

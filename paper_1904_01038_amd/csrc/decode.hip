@@ -1,0 +1,214 @@
+// Kernels of the incremental decoding step (Implementation, Inference): the states of previously generated tokens
+// are cached per active beam and re-used, so a step computes one new position per beam.
+//
+// Cache layout.  Self-attention keys and values of decoder layer l live in K_l, V_l [rows][max_steps][d]: row r writes
+// position t of ITS OWN row at step t and never moves anything.  When the search re-orders the beams, only an
+// ancestry table changes: anc[r][s] is the physical row that holds position s of the hypothesis now living in row r
+// (anc_new[r][s] = anc_old[parent[r]][s] for s < t, anc_new[r][t] = r).  Beams that share a prefix therefore read the
+// same cache lines (L2 hits) and a re-ordering costs rows * t integers instead of a copy of every layer's cache.
+// Cross-attention keys and values are projected once per source sentence and shared by its beams.
+#include "common.h"
+#include "kernels.h"
+
+namespace tfm {
+
+__global__ __launch_bounds__(256) void ancestry_kernel(const int* __restrict__ anc_old, int* __restrict__ anc_new,
+                                                       const int* __restrict__ parent, int rows, int max_steps, int t) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows * (t + 1)) return;
+  const int r = i / (t + 1), s = i - r * (t + 1);
+  anc_new[(size_t)r * max_steps + s] = s < t ? anc_old[(size_t)parent[r] * max_steps + s] : r;
+}
+void launch_ancestry(hipStream_t s, const int* anc_old, int* anc_new, const int* parent, int rows, int max_steps, int t) {
+  const int n = rows * (t + 1);
+  hipLaunchKernelGGL(ancestry_kernel, dim3((n + 255) / 256), dim3(256), 0, s, anc_old, anc_new, parent, rows, max_steps, t);
+}
+
+// K[r][t][:] = qkv[r][d .. 2d), V[r][t][:] = qkv[r][2d .. 3d)
+template <typename T>
+__global__ __launch_bounds__(256) void cache_append_kernel(const T* __restrict__ qkv, T* __restrict__ Kc, T* __restrict__ Vc,
+                                                           int rows, int d, int max_steps, int t) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows * d) return;
+  const int r = i / d, e = i - r * d;
+  const size_t dst = ((size_t)r * max_steps + t) * d + e;
+  Kc[dst] = qkv[(size_t)r * 3 * d + d + e];
+  Vc[dst] = qkv[(size_t)r * 3 * d + 2 * d + e];
+}
+void launch_cache_append(hipStream_t s, int dt, const void* qkv, void* Kc, void* Vc, int rows, int d, int max_steps, int t) {
+  const int n = rows * d;
+  dim3 grid((n + 255) / 256), block(256);
+  if (dt == F32) hipLaunchKernelGGL(cache_append_kernel<float>, grid, block, 0, s, (const float*)qkv, (float*)Kc, (float*)Vc, rows, d, max_steps, t);
+  else if (dt == F16) hipLaunchKernelGGL(cache_append_kernel<half_t>, grid, block, 0, s, (const half_t*)qkv, (half_t*)Kc, (half_t*)Vc, rows, d, max_steps, t);
+  else hipLaunchKernelGGL(cache_append_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)qkv, (bf16_t*)Kc, (bf16_t*)Vc, rows, d, max_steps, t);
+}
+
+// One wavefront per (row, head): a single query against n positions.
+//   phase 1  lane = position: score = q . K[pos] / sqrt(dh), kept in LDS together with the row's address
+//   phase 2  softmax over the positions (fp32)
+//   phase 3  lane = feature: out[e] = sum_pos p[pos] V[pos][e]; a V row of one head is one 128-byte line at dh = 64
+template <typename T, int VEC>
+__global__ __launch_bounds__(64) void decode_attention_kernel(DecodeAttnArgs p) {
+  extern __shared__ float smem[];
+  const int r = blockIdx.x, h = blockIdx.y, lane = threadIdx.x, dh = p.dh;
+  int n, base = 0;
+  if (p.anc) n = p.t + 1;
+  else { const int s = r / p.beam; base = p.src_off[s]; n = p.src_off[s + 1] - base; }
+  float* sc = smem;                                    // [n_max] scores, then probabilities
+  int* rowi = reinterpret_cast<int*>(smem + p.n_max);  // [n_max] element offset of the position's K row / V row
+  float* qs = smem + 2 * p.n_max;                      // [dh]
+  const T* q = reinterpret_cast<const T*>(p.q) + (size_t)r * p.ldq + h * dh;
+  for (int e = lane; e < dh; e += 64) qs[e] = to_f<T>(q[e]);
+  const T* K = reinterpret_cast<const T*>(p.k);
+  const T* V = reinterpret_cast<const T*>(p.v);
+  __syncthreads();
+  const float scale = rsqrtf((float)dh);
+  float lmax = -INFINITY;
+  for (int s = lane; s < n; s += 64) {
+    // element offset of (position s, head h) from the K and V bases (both have the same strides)
+    const long long off = p.anc ? ((long long)p.anc[(size_t)r * p.max_steps + s] * p.max_steps + s) * p.row_stride + h * dh
+                                : (long long)(base + s) * p.row_stride + h * dh;
+    const T* kr = K + off;
+    float acc = 0.f;
+    for (int e = 0; e < dh; e += VEC) {
+      float kv[VEC];
+      load_f<T, VEC>(kr + e, kv);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc += qs[e + i] * kv[i];
+    }
+    acc *= scale;
+    sc[s] = acc;
+    // offsets fit in 32 bits: the host checks that every cache and projection holds fewer than 2^31 elements
+    rowi[s] = (int)off;
+    lmax = fmaxf(lmax, acc);
+  }
+  const float m = wave_max(lmax);
+  float lsum = 0.f;
+  for (int s = lane; s < n; s += 64) {
+    const float e = __expf(sc[s] - m);
+    sc[s] = e;
+    lsum += e;
+  }
+  const float inv = 1.f / wave_sum(lsum);
+  __syncthreads();
+  T* out = reinterpret_cast<T*>(p.o) + (size_t)r * p.ldo + h * dh;
+  for (int e = lane; e < dh; e += 64) {
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    int s = 0;
+    for (; s + 4 <= n; s += 4) {
+      a0 += sc[s] * to_f<T>(V[rowi[s] + e]);
+      a1 += sc[s + 1] * to_f<T>(V[rowi[s + 1] + e]);
+      a2 += sc[s + 2] * to_f<T>(V[rowi[s + 2] + e]);
+      a3 += sc[s + 3] * to_f<T>(V[rowi[s + 3] + e]);
+    }
+    for (; s < n; ++s) a0 += sc[s] * to_f<T>(V[rowi[s] + e]);
+    out[e] = from_f<T>((a0 + a1 + a2 + a3) * inv);
+  }
+}
+
+void launch_decode_attention(hipStream_t s, const DecodeAttnArgs& a) {
+  if (a.rows <= 0) return;
+  dim3 grid(a.rows, a.H), block(64);
+  const size_t smem = (size_t)(2 * a.n_max + a.dh) * sizeof(float);
+  const bool vec = a.dh % 8 == 0;
+#define DA(T, VEC) hipLaunchKernelGGL((decode_attention_kernel<T, VEC>), grid, block, smem, s, a)
+  if (a.dt == F32) { if (vec) DA(float, 8); else DA(float, 1); }
+  else if (a.dt == F16) { if (vec) DA(half_t, 8); else DA(half_t, 1); }
+  else { if (vec) DA(bf16_t, 8); else DA(bf16_t, 1); }
+#undef DA
+}
+
+// Per row: log-sum-exp of the logits and the K best tokens.  Order: larger value first, equal values by ascending id.
+__device__ __forceinline__ bool better(float v, int i, float w, int j) { return v > w || (v == w && i < j); }
+
+template <typename T, int K>
+__global__ __launch_bounds__(256) void row_topk_kernel(const T* __restrict__ z, int ldz, int V, float* __restrict__ top_logp,
+                                                       int* __restrict__ top_id, float* __restrict__ lse_out, int k_out) {
+  __shared__ float sh[16];
+  __shared__ float cand_v[4];
+  __shared__ int cand_i[4], cand_owner[4];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const T* zr = z + (size_t)row * ldz;
+  float bv[K];
+  int bi[K];
+#pragma unroll
+  for (int i = 0; i < K; ++i) { bv[i] = -INFINITY; bi[i] = 0x7fffffff; }
+  float m = -INFINITY, ssum = 0.f;
+  for (int col = tid; col < V; col += 256) {
+    const float v = to_f<T>(zr[col]);
+    if (v > m) { ssum = ssum * __expf(m - v) + 1.f; m = v; } else { ssum += __expf(v - m); }
+    if (better(v, col, bv[K - 1], bi[K - 1])) {
+      float cv = v;
+      int ci = col;
+#pragma unroll
+      for (int i = 0; i < K; ++i) {                      // insertion into the sorted list, static indices only
+        if (better(cv, ci, bv[i], bi[i])) {
+          const float tv = bv[i]; const int ti = bi[i];
+          bv[i] = cv; bi[i] = ci; cv = tv; ci = ti;
+        }
+      }
+    }
+  }
+  const float gm = block_max(m, sh);
+  const float gs = block_sum(ssum * __expf(m - gm), sh);   // (a thread that saw nothing has ssum = 0)
+  const float lse = gm + logf(gs);
+  if (tid == 0 && lse_out) lse_out[row] = lse;
+  // K rounds: the best head among the threads' lists wins and its owner moves on to its next entry
+  const int lane = tid & 63, wave = tid >> 6;
+  for (int round = 0; round < k_out; ++round) {
+    float v = bv[0];
+    int id = bi[0], owner = tid;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(v, o);
+      const int oi = __shfl_xor(id, o), oo = __shfl_xor(owner, o);
+      if (better(ov, oi, v, id)) { v = ov; id = oi; owner = oo; }
+    }
+    if (lane == 0) { cand_v[wave] = v; cand_i[wave] = id; cand_owner[wave] = owner; }
+    __syncthreads();
+    float wv = cand_v[0];
+    int wi = cand_i[0], wo = cand_owner[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w)
+      if (better(cand_v[w], cand_i[w], wv, wi)) { wv = cand_v[w]; wi = cand_i[w]; wo = cand_owner[w]; }
+    if (tid == 0) {
+      top_logp[(size_t)row * k_out + round] = wv - lse;
+      top_id[(size_t)row * k_out + round] = wi;
+    }
+    if (tid == wo) {
+#pragma unroll
+      for (int i = 0; i + 1 < K; ++i) { bv[i] = bv[i + 1]; bi[i] = bi[i + 1]; }
+      bv[K - 1] = -INFINITY; bi[K - 1] = 0x7fffffff;
+    }
+    __syncthreads();
+  }
+}
+
+void launch_row_topk(hipStream_t s, int dt, const void* z, int ldz, int rows, int V, int k, float* top_logp, int* top_id,
+                     float* lse) {
+  if (rows <= 0) return;
+  dim3 grid(rows), block(256);
+#define TK(T, K) hipLaunchKernelGGL((row_topk_kernel<T, K>), grid, block, 0, s, (const T*)z, ldz, V, top_logp, top_id, lse, k)
+#define TKK(T) do { if (k <= 8) TK(T, 8); else TK(T, 16); } while (0)
+  if (dt == F32) TKK(float); else if (dt == F16) TKK(half_t); else TKK(bf16_t);
+#undef TKK
+#undef TK
+}
+
+// out[r][v] = z[r][v] - lse[r] in fp32 (test access to the full distribution)
+template <typename T>
+__global__ __launch_bounds__(256) void logprob_rows_kernel(const T* __restrict__ z, int ldz, const float* __restrict__ lse,
+                                                           float* __restrict__ out, int V) {
+  const int row = blockIdx.y;
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col < V) out[(size_t)row * V + col] = to_f<T>(z[(size_t)row * ldz + col]) - lse[row];
+}
+void launch_logprob_rows(hipStream_t s, int dt, const void* z, int ldz, const float* lse, float* out, int rows, int V) {
+  if (rows <= 0) return;
+  dim3 grid((V + 255) / 256, rows), block(256);
+  if (dt == F32) hipLaunchKernelGGL(logprob_rows_kernel<float>, grid, block, 0, s, (const float*)z, ldz, lse, out, V);
+  else if (dt == F16) hipLaunchKernelGGL(logprob_rows_kernel<half_t>, grid, block, 0, s, (const half_t*)z, ldz, lse, out, V);
+  else hipLaunchKernelGGL(logprob_rows_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)z, ldz, lse, out, V);
+}
+
+}  // namespace tfm

@@ -117,6 +117,26 @@ void launch_scaler_update(hipStream_t s, DevState* st, long long ntokens, float 
                           int scale_window, float min_scale, int dynamic);
 void launch_dropout_mask(hipStream_t s, uint64_t key, float p, uint8_t* out, int64_t n);
 
+// ---- incremental decoding ---------------------------------------------------------------------------------------------
+void launch_ancestry(hipStream_t s, const int* anc_old, int* anc_new, const int* parent, int rows, int max_steps, int t);
+void launch_cache_append(hipStream_t s, int dt, const void* qkv, void* Kc, void* Vc, int rows, int d, int max_steps, int t);
+struct DecodeAttnArgs {
+  int dt;
+  const void* q; int ldq;                // [rows, ldq], head h at column h * dh
+  const void *k, *v;                     // self: caches [rows][max_steps][row_stride]; cross: [src tokens][row_stride]
+  int row_stride;                        // elements between consecutive positions (d for the caches, 2d for fused K|V)
+  void* o; int ldo;
+  const int* anc;                        // self-attention: ancestry table [rows][max_steps]; null selects cross-attention
+  const int* src_off;                    // cross-attention: [sentences + 1] row offsets into k / v
+  int rows, H, dh, beam, t, max_steps;
+  int n_max;                             // upper bound on the positions any row attends to (sizes the LDS buffers)
+};
+void launch_decode_attention(hipStream_t s, const DecodeAttnArgs& a);
+// per row: log-sum-exp and the k (<= 16) largest logits as log-probabilities, best first, ties by ascending id
+void launch_row_topk(hipStream_t s, int dt, const void* z, int ldz, int rows, int V, int k, float* top_logp, int* top_id,
+                     float* lse);
+void launch_logprob_rows(hipStream_t s, int dt, const void* z, int ldz, const float* lse, float* out, int rows, int V);
+
 uint64_t dropout_site_key(uint64_t seed, uint64_t step, int stream, int layer, int sub);
 
 }  // namespace tfm

@@ -1094,6 +1094,274 @@ int tfm_apply_update(tfm_ctx* c, float lr, tfm_update_out* out) {
   return TFM_OK;
 }
 
+// ---- incremental decoding -----------------------------------------------------------------------------------------------------
+struct tfm_decoder {
+  tfm_ctx* c;
+  int max_rows, max_steps, max_src, topk;
+  // device buffers (caller's workspace)
+  void *resid[2], *norm[2], *y, *qkv, *att, *q, *inter, *logits;
+  float *mean, *rstd, *lse, *top_logp, *lp_stage;
+  int *top_id, *anc[2], *ibuf;
+  std::vector<void*> Kc, Vc, xkv;                  // per decoder layer
+  // pinned host staging
+  int* h_in;                                       // prev, parent, pos [3 * max_rows]; also source ids / pos / offsets
+  size_t h_in_ints;
+  float* h_out;                                    // top_logp [max_rows * topk] followed by top_id
+  // state of the batch being decoded
+  int B, beam, rows, t, cur, n_src_max;
+  bool begun;
+};
+
+namespace {
+
+size_t decoder_carve(tfm_decoder* D, char* base) {
+  tfm_ctx* c = D->c;
+  const tfm_config& cf = c->cfg;
+  const size_t R = (size_t)D->max_rows, d = cf.d_model, F = cf.d_ffn, esz = c->esz;
+  Arena a{base};
+  for (int i = 0; i < 2; ++i) { D->resid[i] = a.take(R * d * esz); D->norm[i] = a.take(R * d * esz); }
+  D->y = a.take(R * d * esz);
+  D->qkv = a.take(R * 3 * d * esz);
+  D->att = a.take(R * d * esz);
+  D->q = a.take(R * d * esz);
+  D->inter = a.take(R * F * esz);
+  D->logits = a.take(R * (size_t)cf.vocab * esz);
+  D->mean = (float*)a.take(R * 4);
+  D->rstd = (float*)a.take(R * 4);
+  D->lse = (float*)a.take(R * 4);
+  D->top_logp = (float*)a.take(R * D->topk * 8);   // values, then ids: one device-to-host copy per step
+  D->top_id = base ? (int*)(D->top_logp + R * D->topk) : nullptr;
+  D->lp_stage = (float*)a.take((size_t)16 * cf.vocab * 4);
+  D->anc[0] = (int*)a.take(R * D->max_steps * 4);
+  D->anc[1] = (int*)a.take(R * D->max_steps * 4);
+  D->ibuf = (int*)a.take(3 * R * 4);
+  D->Kc.assign(cf.dec_layers, nullptr); D->Vc.assign(cf.dec_layers, nullptr); D->xkv.assign(cf.dec_layers, nullptr);
+  for (int l = 0; l < cf.dec_layers; ++l) {
+    D->Kc[l] = a.take(R * D->max_steps * d * esz);
+    D->Vc[l] = a.take(R * D->max_steps * d * esz);
+    if (cf.enc_layers) D->xkv[l] = a.take((size_t)D->max_src * 2 * d * esz);
+  }
+  return (a.off + 255) & ~(size_t)255;
+}
+
+int decoder_check(const tfm_ctx* c, int max_rows, int max_steps, int max_src, int topk) {
+  if (!c) return TFM_EINVAL;
+  const tfm_config& cf = c->cfg;
+  if (max_rows < 1 || max_steps < 1 || max_steps > cf.max_len || topk < 1 || topk > 16 || topk > cf.vocab) return TFM_EINVAL;
+  if (cf.enc_layers && (max_src < 1 || max_src > cf.max_tokens)) return TFM_EINVAL;
+  // the attention kernel keeps element offsets into one cache in 32 bits
+  if ((double)max_rows * max_steps * cf.d_model >= 2147483648.0 || (double)std::max(max_src, 1) * 2 * cf.d_model >= 2147483648.0) return TFM_EINVAL;
+  return TFM_OK;
+}
+
+void decode_ln(tfm_decoder* D, const void* x, const void* y, int g, int b, void* s_out, void* n_out) {
+  tfm_ctx* c = D->c;
+  const int d = c->cfg.d_model;
+  run(c, TFM_PROF_NORM, 0.0, (double)c->esz * D->rows * d * (2.0 + (y ? 1.0 : 0.0) + (s_out ? 1.0 : 0.0)), [&] {
+    launch_residual_layernorm_fwd(c->stream, c->dt, x, y, wh(c, g), wh(c, b), s_out, n_out, D->mean, D->rstd, D->rows, d, 0, 0.f);
+  });
+}
+
+void decode_attention(tfm_decoder* D, const void* q, int ldq, const void* k, const void* v, int row_stride, const int* anc, int n_max,
+                      double positions) {
+  tfm_ctx* c = D->c;
+  const int d = c->cfg.d_model, H = c->cfg.n_heads;
+  DecodeAttnArgs a{};
+  a.dt = c->dt; a.q = q; a.ldq = ldq; a.k = k; a.v = v; a.row_stride = row_stride; a.o = D->att; a.ldo = d;
+  a.anc = anc; a.src_off = c->enc.off; a.rows = D->rows; a.H = H; a.dh = d / H; a.beam = D->beam; a.t = D->t;
+  a.max_steps = D->max_steps; a.n_max = n_max;
+  // positions = sum over rows of the positions attended to: K and V rows read once each, q read, output written
+  run(c, TFM_PROF_ATTENTION, 4.0 * d * positions, (double)c->esz * d * (2.0 * positions + 2.0 * D->rows),
+      [&] { launch_decode_attention(c->stream, a); });
+}
+
+// y = f_k(fin) for the single new position of every row
+void decode_sublayer(tfm_decoder* D, const Block& b, int layer, const void* fin, double src_positions) {
+  tfm_ctx* c = D->c;
+  const int d = c->cfg.d_model, F = c->cfg.d_ffn, R = D->rows;
+  if (b.kind == SELF) {
+    gemm(c, 0, R, 3 * d, d, fin, d, wh(c, b.w_a), d, D->qkv, 3 * d, wh(c, b.b_a));
+    run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * R * d * 4.0,
+        [&] { launch_cache_append(c->stream, c->dt, D->qkv, D->Kc[layer], D->Vc[layer], R, d, D->max_steps, D->t); });
+    decode_attention(D, D->qkv, 3 * d, D->Kc[layer], D->Vc[layer], d, D->anc[D->cur], D->t + 1, (double)R * (D->t + 1));
+    gemm(c, 0, R, d, d, D->att, d, wh(c, b.w_o), d, D->y, d, wh(c, b.b_o));
+  } else if (b.kind == CROSS) {
+    gemm(c, 0, R, d, d, fin, d, wh(c, b.w_a), d, D->q, d, wh(c, b.b_a));
+    const char* kv = (const char*)D->xkv[layer];
+    decode_attention(D, D->q, d, kv, kv + d * c->esz, 2 * d, nullptr, D->n_src_max, src_positions);
+    gemm(c, 0, R, d, d, D->att, d, wh(c, b.w_o), d, D->y, d, wh(c, b.b_o));
+  } else {
+    gemm(c, 0, R, F, d, fin, d, wh(c, b.w_a), d, D->inter, F, wh(c, b.b_a), 1);
+    gemm(c, 0, R, d, F, D->inter, F, wh(c, b.w_o), F, D->y, d, wh(c, b.b_o));
+  }
+}
+
+}  // namespace
+
+int tfm_decoder_workspace_bytes(const tfm_ctx* c, int32_t max_rows, int32_t max_steps, int32_t max_src_tokens, int32_t topk,
+                                size_t* bytes) {
+  if (!bytes || decoder_check(c, max_rows, max_steps, max_src_tokens, topk)) return TFM_EINVAL;
+  tfm_decoder D{};
+  D.c = const_cast<tfm_ctx*>(c); D.max_rows = max_rows; D.max_steps = max_steps; D.max_src = max_src_tokens; D.topk = topk;
+  *bytes = decoder_carve(&D, nullptr);
+  return TFM_OK;
+}
+
+int tfm_decoder_create(tfm_ctx* c, void* ws, size_t bytes, int32_t max_rows, int32_t max_steps, int32_t max_src_tokens,
+                       int32_t topk, tfm_decoder** out) {
+  if (!ws || !out || decoder_check(c, max_rows, max_steps, max_src_tokens, topk)) return c ? fail(c, TFM_EINVAL, "bad decoder sizes") : TFM_EINVAL;
+  if (((uintptr_t)ws & 255) != 0) return fail(c, TFM_EINVAL, "workspace must be 256-byte aligned");
+  tfm_decoder* D = new tfm_decoder{};
+  D->c = c; D->max_rows = max_rows; D->max_steps = max_steps; D->max_src = max_src_tokens; D->topk = topk;
+  const size_t need = decoder_carve(D, nullptr);
+  if (bytes < need) { delete D; return fail(c, TFM_ENOMEM, "decoder workspace has %zu bytes, %zu needed", bytes, need); }
+  decoder_carve(D, (char*)ws);
+  D->h_in_ints = std::max<size_t>(3 * (size_t)max_rows, 2 * (size_t)c->cfg.max_tokens + c->cfg.max_sentences + 1);
+  hipError_t e = hipHostMalloc((void**)&D->h_in, D->h_in_ints * 4, hipHostMallocDefault);
+  if (e == hipSuccess) e = hipHostMalloc((void**)&D->h_out, (size_t)max_rows * topk * 8, hipHostMallocDefault);
+  if (e != hipSuccess) {
+    if (D->h_in) hipHostFree(D->h_in);
+    delete D;
+    return fail(c, TFM_EHIP, "decoder staging buffers: %s", hipGetErrorString(e));
+  }
+  *out = D;
+  return TFM_OK;
+}
+
+void tfm_decoder_destroy(tfm_decoder* D) {
+  if (!D) return;
+  hipStreamSynchronize(D->c->stream);
+  if (D->h_in) hipHostFree(D->h_in);
+  if (D->h_out) hipHostFree(D->h_out);
+  delete D;
+}
+
+int tfm_decoder_begin(tfm_decoder* D, const int32_t* src, const int32_t* src_lens, int32_t B, int32_t Ls, int32_t beam) {
+  if (!D) return TFM_EINVAL;
+  tfm_ctx* c = D->c;
+  const tfm_config& cf = c->cfg;
+  const bool has_enc = cf.enc_layers > 0;
+  D->begun = false;
+  if (B < 1 || beam < 1 || (long long)B * beam > D->max_rows || B > cf.max_sentences)
+    return fail(c, TFM_EINVAL, "B = %d sentences x beam = %d exceeds the decoder's %d rows", B, beam, D->max_rows);
+  if (has_enc != (src != nullptr) || has_enc != (src_lens != nullptr)) return fail(c, TFM_EINVAL, "src is required exactly when the model has an encoder");
+  long long Ts = 0;
+  int maxs = 0;
+  if (has_enc) {
+    if (Ls < 1 || Ls > cf.max_len) return fail(c, TFM_EINVAL, "padded source length outside [1, %d]", cf.max_len);
+    for (int b = 0; b < B; ++b) {
+      if (src_lens[b] < 1 || src_lens[b] > Ls) return fail(c, TFM_EINVAL, "src_lens[%d] = %d outside [1, %d]", b, src_lens[b], Ls);
+      for (int t = 0; t < src_lens[b]; ++t)
+        if (src[(size_t)b * Ls + t] < 0 || src[(size_t)b * Ls + t] >= cf.vocab) return fail(c, TFM_EINVAL, "src[%d,%d] outside the vocabulary", b, t);
+      Ts += src_lens[b];
+      maxs = std::max(maxs, src_lens[b]);
+    }
+    if (Ts > D->max_src || Ts > cf.max_tokens) return fail(c, TFM_EINVAL, "%lld source tokens exceed the capacity", Ts);
+  }
+  adam_join(c);
+  D->B = B; D->beam = beam; D->rows = B * beam; D->t = 0; D->cur = 0; D->n_src_max = maxs;
+  if (has_enc) {
+    // the encoder runs once over the packed source sentences, without dropout, in the context's own buffers
+    HIP_TRY(c, hipStreamSynchronize(c->stream));             // the staging buffer may still feed an earlier copy
+    const size_t R = (size_t)cf.max_tokens;
+    int* ids = D->h_in; int* pos = ids + R; int* off = pos + R;
+    int r = 0;
+    StepCtx s{c};
+    s.B = B; s.Ts = (int)Ts; s.Tt = 0; s.step = 0;
+    s.slen.assign(src_lens, src_lens + B);
+    for (int b = 0; b < B; ++b) {
+      off[b] = r;
+      for (int t = 0; t < src_lens[b]; ++t, ++r) { ids[r] = src[(size_t)b * Ls + t]; pos[r] = t; }
+    }
+    off[B] = r;
+    HIP_TRY(c, hipMemcpyAsync(c->enc.ids, D->h_in, (2 * R + B + 1) * 4, hipMemcpyHostToDevice, c->stream));
+    c->enc.rows = (int)Ts; c->enc.max_len = maxs;
+    const float p_train = c->cfg.dropout;
+    c->cfg.dropout = 0.f;
+    stream_fwd(s, c->enc);
+    c->cfg.dropout = p_train;
+    const void* mem = c->enc.norm[c->enc.blocks.size()];
+    const int d = cf.d_model;
+    int layer = 0;
+    for (const Block& b : c->dec.blocks) {
+      if (b.kind != CROSS) continue;
+      gemm(c, 0, (int)Ts, 2 * d, d, mem, d, wh(c, b.w_kv), d, D->xkv[layer], 2 * d, wh(c, b.b_kv));
+      ++layer;
+    }
+  }
+  HIP_TRY(c, hipGetLastError());
+  D->begun = true;
+  return TFM_OK;
+}
+
+int tfm_decoder_step(tfm_decoder* D, const int32_t* prev, const int32_t* parent, float* top_logp, int32_t* top_id) {
+  if (!D || !prev || !top_logp || !top_id) return TFM_EINVAL;
+  tfm_ctx* c = D->c;
+  const tfm_config& cf = c->cfg;
+  if (!D->begun) return fail(c, TFM_ESTATE, "tfm_decoder_begin has not been called");
+  if (D->t >= D->max_steps) return fail(c, TFM_ESTATE, "the decoder was created for %d steps", D->max_steps);
+  const int R = D->rows, d = cf.d_model, V = cf.vocab;
+  for (int r = 0; r < R; ++r) {
+    if (prev[r] < 0 || prev[r] >= V) return fail(c, TFM_EINVAL, "prev[%d] = %d outside the vocabulary", r, prev[r]);
+    if (parent && (parent[r] < 0 || parent[r] >= R || parent[r] / D->beam != r / D->beam))
+      return fail(c, TFM_EINVAL, "parent[%d] = %d is not a row of the same sentence", r, parent[r]);
+  }
+  // the previous step's call synchronised, so the staging buffer is free
+  for (int r = 0; r < R; ++r) { D->h_in[r] = prev[r]; D->h_in[R + r] = parent ? parent[r] : r; D->h_in[2 * R + r] = D->t; }
+  HIP_TRY(c, hipMemcpyAsync(D->ibuf, D->h_in, (size_t)3 * R * 4, hipMemcpyHostToDevice, c->stream));
+  const int* d_prev = D->ibuf; const int* d_parent = D->ibuf + R; const int* d_pos = D->ibuf + 2 * R;
+  run(c, TFM_PROF_EMBED, 0.0, 4.0 * R * (D->t + 1) * 2.0,
+      [&] { launch_ancestry(c->stream, D->anc[D->cur], D->anc[D->cur ^ 1], d_parent, R, D->max_steps, D->t); });
+  D->cur ^= 1;
+  const bool pre = cf.pre_norm != 0;
+  const std::vector<Block>& blocks = c->dec.blocks;
+  const int K = (int)blocks.size();
+  void* emb = pre ? D->resid[0] : D->norm[0];
+  run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * R * d * 2.0,
+      [&] { launch_embed_fwd(c->stream, c->dt, c->Wh, d_prev, d_pos, c->pe, emb, R, d, 0, 0.f); });
+  if (pre) decode_ln(D, D->resid[0], nullptr, blocks[0].ln_g, blocks[0].ln_b, nullptr, D->norm[0]);
+  double src_positions = 0;
+  if (cf.enc_layers) src_positions = (double)c->enc.rows * D->beam;
+  for (int k = 0; k < K; ++k) {
+    const int i = k & 1, j = i ^ 1;
+    decode_sublayer(D, blocks[k], blocks[k].layer, D->norm[i], src_positions);
+    if (pre) {
+      const int g = k + 1 < K ? blocks[k + 1].ln_g : c->dec.lnf_g, b = k + 1 < K ? blocks[k + 1].ln_b : c->dec.lnf_b;
+      decode_ln(D, D->resid[i], D->y, g, b, D->resid[j], D->norm[j]);
+    } else {
+      decode_ln(D, D->norm[i], D->y, blocks[k].ln_g, blocks[k].ln_b, nullptr, D->norm[j]);
+    }
+  }
+  const void* top = D->norm[K & 1];
+  gemm(c, 0, R, V, d, top, d, c->Wh, d, D->logits, V);
+  run(c, TFM_PROF_LOSS, 0.0, (double)c->esz * R * V,
+      [&] { launch_row_topk(c->stream, c->dt, D->logits, V, R, V, D->topk, D->top_logp, D->top_id, D->lse); });
+  const size_t n = (size_t)R * D->topk;
+  HIP_TRY(c, hipMemcpyAsync(D->h_out, D->top_logp, n * 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(D->h_out + n, D->top_id, n * 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipGetLastError());
+  std::memcpy(top_logp, D->h_out, n * 4);
+  std::memcpy(top_id, D->h_out + n, n * 4);
+  D->t += 1;
+  return TFM_OK;
+}
+
+int tfm_decoder_get_logprobs(tfm_decoder* D, float* host, int64_t n) {
+  if (!D || !host) return TFM_EINVAL;
+  tfm_ctx* c = D->c;
+  const int V = c->cfg.vocab;
+  if (!D->begun || D->t == 0) return fail(c, TFM_ESTATE, "no step has been taken");
+  if (n != (int64_t)D->rows * V) return fail(c, TFM_EINVAL, "expected rows * vocab = %lld values", (long long)D->rows * V);
+  for (int r0 = 0; r0 < D->rows; r0 += 16) {
+    const int nr = std::min(16, D->rows - r0);
+    launch_logprob_rows(c->stream, c->dt, (const char*)D->logits + (size_t)r0 * V * c->esz, V, D->lse + r0, D->lp_stage, nr, V);
+    HIP_TRY(c, hipMemcpyAsync(host + (size_t)r0 * V, D->lp_stage, (size_t)nr * V * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+  }
+  return TFM_OK;
+}
+
 // ---- single operations ---------------------------------------------------------------------------------------------------------
 static int op_done() { return hipGetLastError() == hipSuccess ? TFM_OK : TFM_EHIP; }
 
