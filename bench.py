@@ -61,12 +61,112 @@ def cpu_baseline(workload, shape, batches, sample_tokens):
                       "numpy float64, %.1f s" % (n, r["ntokens"], workload, dt)}
 
 
+def run_decode(args):
+    """Beam-search translation with incremental decoding (Implementation, Inference; the paper's Table 1 setting: big
+    Transformer, beam 4, fp16).  A "step" is one token-capped batch of source sentences translated to the length cap."""
+    import numpy as np
+    import torch
+    import paper_1904_01038_amd as T
+    from paper_1904_01038_amd.search import beam_search
+    from synth import PRESETS, init_params, count_params
+    from synth.batches import zipf_ids
+
+    torch.cuda.set_device(0)
+    shape = PRESETS["big"]
+    beam, extra = 4, 10
+    rng = np.random.Generator(np.random.PCG64(6))
+    n_pool = 3003                                         # size of the test set the paper's table uses; lengths only
+    lens = rng.integers(10, 81, n_pool).astype(np.int32)
+    sents = [np.append(zipf_ids(rng, int(n) - 1, shape.vocab), shape.eos_id).astype(np.int32) for n in lens]
+    groups = T.batch_by_length(None, lens, args.decode_max_tokens, 1024, 8)
+    order = rng.permutation(len(groups))
+    max_b = max(len(g) for g in groups)
+    max_len = int(lens.max()) + extra
+    cfg = T.make_config(shape, precision=T.FP16, max_sentences=max_b, max_len=max_len,
+                        max_tokens=(args.decode_max_tokens + 63) // 64 * 64, dropout=0.1)
+    ctx = T.Tfm(cfg)
+    ctx.set_params(init_params(shape, 0))
+    dec = T.Decoder(ctx, max_b * beam, max_len, args.decode_max_tokens, 2 * beam)
+
+    def translate(g):
+        idx = groups[g]
+        sl = lens[idx]
+        src = np.full((len(idx), int(sl.max())), shape.pad_id, np.int32)
+        for i, j in enumerate(idx):
+            src[i, :sl[i]] = sents[j]
+        dec.begin(src, sl, beam)
+        out = beam_search(dec.step, len(idx), beam, int(sl.max()) + extra, shape.eos_id)
+        return len(idx), sum(len(h[0][1]) for h in out), int(sl.max()) + extra
+
+    for i in range(args.warmup):
+        translate(order[i % len(order)])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_sent = n_tok = n_steps = 0
+    for i in range(args.steps):
+        a, b, c_ = translate(order[(args.warmup + i) % len(order)])
+        n_sent, n_tok, n_steps = n_sent + a, n_tok + b, n_steps + c_
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ctx.profile_enable(True)
+    for i in range(min(args.profile_steps, 2)):
+        translate(order[i % len(order)])
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    total_ms = sum(p["ms"] for p in prof.values())
+    classes = {k: {"launches": p["launches"], "ms": p["ms"], "share": p["ms"] / total_ms,
+                   "gbs": p["bytes"] / (p["ms"] * 1e-3) / 1e9 if p["ms"] > 0 else 0.0}
+               for k, p in prof.items() if p["launches"]}
+    dom = max(("gemm", "attention"), key=lambda k: prof[k]["ms"])
+    g = prof[dom]
+    achieved = g["bytes"] / (g["ms"] * 1e-3) / 1e9
+    roofline = {"kernel": "%s class of the decoding step" % dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "algorithmic_bytes_per_launch": g["bytes"] / g["launches"], "avg_launch_ms": g["ms"] / g["launches"],
+                "classes": classes, "gpu_ms_share_of_wall": None}
+    out = {"metric": "sentences/sec, beam search with incremental decoding on 1 MI355X", "value": n_sent / dt,
+           "unit": "sentences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "fp16", "data": "synthetic",
+           "config": {"workload": "decode", "model": "big", "params": count_params(shape), "beam": beam,
+                      "batch_cap_padded_tokens": args.decode_max_tokens, "sentences": n_sent, "decode_steps": n_steps,
+                      "tokens_out_per_s": n_tok / dt,
+                      "length_cap": "source length + %d (random weights never prefer eos: every hypothesis runs to the cap)" % extra},
+           "roofline": roofline}
+    if not args.no_cpu_baseline:
+        from oracle.decoding import DecodingOracle, top_k
+        oracle = DecodingOracle(shape, init_params(shape, 0))
+        idx = groups[order[0]][:2]
+        t1 = time.time()
+        mems = [oracle.encode(sents[j]) for j in idx]
+        hist = [[shape.eos_id] for _ in idx]
+        n_cpu_steps = 4
+        for _ in range(n_cpu_steps):                      # greedy, one row per sentence
+            for r in range(len(idx)):
+                hist[r].append(top_k(oracle.next_logprobs(mems[r], hist[r]), 1)[0][1])
+        dtc = time.time() - t1
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p_.get("num_threads", 1) for p_ in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        full = float(np.mean(lens[idx])) + extra
+        out["cpu_baseline"] = {"value": len(idx) / (dtc * full / n_cpu_steps) , "unit": "sentences/s", "cores": int(cores),
+                               "kind": "oracle",
+                               "sample": "2 sentences, greedy (1 row each), encoder + %d decoding steps with the whole prefix "
+                                         "recomputed per step, numpy float64, %.1f s; scaled linearly to the %d-step cap "
+                                         "(an underestimate of the oracle's cost, which grows with the prefix)" % (n_cpu_steps, dtc, int(full))}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=12)
-    ap.add_argument("--workload", default="big", choices=list(WORKLOAD_RUN))
+    ap.add_argument("--workload", default="big", choices=list(WORKLOAD_RUN) + ["decode"])
+    ap.add_argument("--decode-max-tokens", type=int, default=3584, help="padded source tokens per decoding batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=384)
     ap.add_argument("--profile-steps", type=int, default=3)
@@ -81,6 +181,8 @@ def main():
     from synth import PRESETS, WORKLOADS, init_params, make_batches, count_params
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload == "decode":
+        return run_decode(args)
     torch.cuda.set_device(0)
     w = WORKLOADS[args.workload]
     shape = PRESETS[w["model"]]

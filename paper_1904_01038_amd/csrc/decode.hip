@@ -184,15 +184,87 @@ __global__ __launch_bounds__(256) void row_topk_kernel(const T* __restrict__ z, 
   }
 }
 
+// The same result with the row held in registers (NCH values per thread, V <= NT * NCH): every thread knows its own
+// best value; a round picks the best of those, and only the thread that owned it looks for its next best.
+template <typename T, int NCH, int NT>
+__global__ __launch_bounds__(NT) void row_topk_cached_kernel(const T* __restrict__ z, int ldz, int V, float* __restrict__ top_logp,
+                                                              int* __restrict__ top_id, float* __restrict__ lse_out, int k_out) {
+  __shared__ float sh[16];
+  __shared__ float cand_v[NT / 64];
+  __shared__ int cand_i[NT / 64];
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const T* zr = z + (size_t)row * ldz;
+  float c[NCH];
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int col = tid + i * NT;
+    c[i] = col < V ? to_f<T>(zr[col]) : -INFINITY;
+    m = fmaxf(m, c[i]);
+  }
+  const float gm = block_max(m, sh);
+  float se = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) se += __expf(c[i] - gm);                 // exp(-inf) = 0 for the padding
+  const float lse = gm + logf(block_sum(se, sh));
+  if (tid == 0 && lse_out) lse_out[row] = lse;
+  // this thread's best remaining (value, id): columns ascend with i, so the first maximum has the smallest id
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  auto rescan = [&]() {
+    bv = -INFINITY; bi = 0x7fffffff;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+      if (c[i] > bv) { bv = c[i]; bi = tid + i * NT; }
+  };
+  rescan();
+  for (int round = 0; round < k_out; ++round) {
+    float v = bv;
+    int id = bi;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(v, o);
+      const int oi = __shfl_xor(id, o);
+      if (better(ov, oi, v, id)) { v = ov; id = oi; }
+    }
+    if (lane == 0) { cand_v[wave] = v; cand_i[wave] = id; }
+    __syncthreads();
+    float wv = cand_v[0];
+    int wi = cand_i[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w)
+      if (better(cand_v[w], cand_i[w], wv, wi)) { wv = cand_v[w]; wi = cand_i[w]; }
+    if (tid == 0) {
+      top_logp[(size_t)row * k_out + round] = wv - lse;
+      top_id[(size_t)row * k_out + round] = wi;
+    }
+    if (wi % NT == tid) {                                              // the owner drops it and looks again
+#pragma unroll
+      for (int i = 0; i < NCH; ++i)
+        if (tid + i * NT == wi) c[i] = -INFINITY;
+      rescan();
+    }
+    __syncthreads();
+  }
+}
+
 void launch_row_topk(hipStream_t s, int dt, const void* z, int ldz, int rows, int V, int k, float* top_logp, int* top_id,
                      float* lse) {
   if (rows <= 0) return;
   dim3 grid(rows), block(256);
+#define TKC(T, NCH, NT) hipLaunchKernelGGL((row_topk_cached_kernel<T, NCH, NT>), grid, dim3(NT), 0, s, (const T*)z, ldz, V, top_logp, top_id, lse, k)
 #define TK(T, K) hipLaunchKernelGGL((row_topk_kernel<T, K>), grid, block, 0, s, (const T*)z, ldz, V, top_logp, top_id, lse, k)
-#define TKK(T) do { if (k <= 8) TK(T, 8); else TK(T, 16); } while (0)
+#define TKK(T)                                                         \
+  do {                                                                 \
+    if (V <= 256 * 16) TKC(T, 16, 256);                                \
+    else if (V <= 1024 * 32) TKC(T, 32, 1024);                         \
+    else if (k <= 8) TK(T, 8);                                         \
+    else TK(T, 16);                                                    \
+  } while (0)
   if (dt == F32) TKK(float); else if (dt == F16) TKK(half_t); else TKK(bf16_t);
 #undef TKK
 #undef TK
+#undef TKC
 }
 
 // out[r][v] = z[r][v] - lse[r] in fp32 (test access to the full distribution)

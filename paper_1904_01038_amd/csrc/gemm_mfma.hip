@@ -393,8 +393,10 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   p.partial = splits > 1 ? (float*)a.splitk_ws : nullptr;
   dim3 grid(p.tiles_total, splits), block(64 * WM * WN);
   if (a.form == 0) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, false, false>), grid, block, 0, s, p);
-  else if (a.form == 1) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, false, true>), grid, block, 0, s, p);
-  else hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, true, true>), grid, block, 0, s, p);
+  else if constexpr (BM >= 128 && BN >= 128) {           // the [k][row] swizzle spans 16 vectors = 128 rows
+    if (a.form == 1) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, false, true>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, true, true>), grid, block, 0, s, p);
+  }
   if (splits > 1) {
     const size_t quads = ((size_t)a.M * a.N + 3) / 4;
     hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, (const float*)a.splitk_ws, splits,
@@ -413,8 +415,11 @@ static int forced_tile() {                               // tuning aid: TFM_GEMM
 //    1  128x128    32     3      3      small K: more blocks in flight hide the short K loop's ramp
 //   12  128x128    64     3      1      K >= 3072: whole 128-byte lines per row and two K-steps in flight
 //   13  256x256    64     2      1      >= 150 tiles of 256x256: half the bytes fetched per flop
+//   20   64x64     64     3      3      fewer than 128 tiles of 128x128 (a decoding step's few rows)
 static int choose_tile(const GemmArgs& a) {
   if (forced_tile() > 0) return forced_tile();
+  const long t1 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
+  if (t1 < 128 && a.form == 0) return 20;               // few rows (a decoding step, X W^T): smaller tiles reach more CUs
   const long t3 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
   if (t3 >= 150) return 13;
   if (a.K >= 3072) return 12;
@@ -426,6 +431,10 @@ static void gemm_mfma_dispatch(hipStream_t s, const GemmArgs& a) {
   switch (choose_tile(a)) {
     case 13: gemm_mfma_launch<T, 256, 256, 2, 4, 64, 2>(s, a); break;
     case 12: gemm_mfma_launch<T, 128, 128, 2, 2, 64, 3>(s, a); break;
+    case 20:                                            // (the [k][row] swizzle spans 16 vectors: NT form only)
+      if (a.form == 0) gemm_mfma_launch<T, 64, 64, 2, 2, 64, 3>(s, a);
+      else gemm_mfma_launch<T, 128, 128, 2, 2, 32, 3>(s, a);
+      break;
     default: gemm_mfma_launch<T, 128, 128, 2, 2, 32, 3>(s, a); break;
   }
 }
