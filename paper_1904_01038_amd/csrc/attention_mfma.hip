@@ -16,6 +16,15 @@
 #include "common.h"
 #include "kernels.h"
 
+// Minimum wavefronts per SIMD the register allocation must leave room for.  Left to itself the compiler gives the
+// backward kernel more than 256 registers (one wavefront per SIMD, two blocks per CU), and the kernel is bound by the
+// latency of its dependent load -> product -> softmax chains, which only more resident wavefronts hide.
+#ifndef ATT_FWD_MIN_WAVES
+#define ATT_FWD_MIN_WAVES 4
+#endif
+#ifndef ATT_BWD_MIN_WAVES
+#define ATT_BWD_MIN_WAVES 2
+#endif
 namespace tfm {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -124,7 +133,7 @@ __device__ __forceinline__ void store4(uint16_t* p, float a, float b, float c, f
 
 // ---- forward ------------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(ATT_THREADS) void attn_fwd_mfma_kernel(AttnP p) {
+__global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_kernel(AttnP p) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[CH * PT];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[CH * PT];
   const int b = blockIdx.z, h = blockIdx.y;
@@ -382,7 +391,7 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnP& p, int chunk, uin
 // One launch for the whole backward: the first nq_chunks blocks along x compute dQ, the rest dK/dV; the two halves are
 // independent, so they run side by side instead of one after the other.
 template <typename T>
-__global__ __launch_bounds__(ATT_THREADS) void attn_bwd_mfma_kernel(AttnP p, int nq_chunks) {
+__global__ __launch_bounds__(ATT_THREADS, ATT_BWD_MIN_WAVES) void attn_bwd_mfma_kernel(AttnP p, int nq_chunks) {
   __shared__ __attribute__((aligned(16))) uint16_t S0[CH * PT];
   __shared__ __attribute__((aligned(16))) uint16_t S1[CH * PT];
   __shared__ __attribute__((aligned(16))) float Ls[CH];
