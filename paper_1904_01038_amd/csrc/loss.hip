@@ -1,6 +1,6 @@
 // Fused log-softmax + label-smoothed cross-entropy, forward and backward in place over the vocabulary.
 // HBM-bound: one block per target token; the row of logits is read once into registers when it fits
-// (V <= 256 threads * 16 chunks * 8), reduced (max, sum exp, sum z) in fp32, and overwritten with
+// (V <= 1024 threads * 16 chunks * 8), reduced (max, sum exp, sum z) in fp32, and overwritten with
 // scale * (softmax(z) - q).  Algorithmic traffic: one read + one write of the logits.
 #include "common.h"
 #include "kernels.h"
@@ -9,7 +9,7 @@ namespace tfm {
 
 constexpr int LV = 8;
 constexpr int LOSS_THREADS = 256;
-constexpr int LOSS_MAX_CHUNKS = 16;      // register-resident row: up to 256 * 16 * 8 = 32768 logits
+constexpr int LOSS_MAX_CHUNKS = 16;      // register-resident row: up to 1024 threads * 16 chunks * 8 = 131072 logits
 
 struct OnlineLse { float m, s; };
 __device__ __forceinline__ void lse_add(OnlineLse& a, float z) {
@@ -17,8 +17,8 @@ __device__ __forceinline__ void lse_add(OnlineLse& a, float z) {
 }
 
 // CACHED: the row lives in registers (NCH chunks per thread); otherwise it is read twice.
-template <typename T, int VEC, bool CACHED, int NCH>
-__global__ __launch_bounds__(LOSS_THREADS) void loss_kernel(T* __restrict__ z, const int* __restrict__ labels,
+template <typename T, int VEC, bool CACHED, int NCH, int NT>
+__global__ __launch_bounds__(NT) void loss_kernel(T* __restrict__ z, const int* __restrict__ labels,
                                                             float* __restrict__ loss_rows, float* __restrict__ nll_rows, int V,
                                                             float eps, const float* __restrict__ scale_ptr, float mult,
                                                             float* __restrict__ step_scale_out) {
@@ -34,7 +34,7 @@ __global__ __launch_bounds__(LOSS_THREADS) void loss_kernel(T* __restrict__ z, c
   if (CACHED) {
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const int col = (threadIdx.x + c * LOSS_THREADS) * VEC;
+      const int col = (threadIdx.x + c * NT) * VEC;
       if (col < V) {
         load_f<T, VEC>(zr + col, cache[c]);
 #pragma unroll
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(LOSS_THREADS) void loss_kernel(T* __restrict__ z, c
       }
     }
   } else {
-    for (int col = threadIdx.x * VEC; col < V; col += LOSS_THREADS * VEC) {
+    for (int col = threadIdx.x * VEC; col < V; col += NT * VEC) {
       float t[VEC];
       load_f<T, VEC>(zr + col, t);
 #pragma unroll
@@ -54,14 +54,14 @@ __global__ __launch_bounds__(LOSS_THREADS) void loss_kernel(T* __restrict__ z, c
   if (CACHED) {
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const int col = (threadIdx.x + c * LOSS_THREADS) * VEC;
+      const int col = (threadIdx.x + c * NT) * VEC;
       if (col < V) {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) se += __expf(cache[c][i] - m);
       }
     }
   } else {
-    for (int col = threadIdx.x * VEC; col < V; col += LOSS_THREADS * VEC) {
+    for (int col = threadIdx.x * VEC; col < V; col += NT * VEC) {
       float t[VEC];
       load_f<T, VEC>(zr + col, t);
 #pragma unroll
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(LOSS_THREADS) void loss_kernel(T* __restrict__ z, c
   if (CACHED) {
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const int col = (threadIdx.x + c * LOSS_THREADS) * VEC;
+      const int col = (threadIdx.x + c * NT) * VEC;
       if (col < V) {
         float o[VEC];
 #pragma unroll
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(LOSS_THREADS) void loss_kernel(T* __restrict__ z, c
       }
     }
   } else {
-    for (int col = threadIdx.x * VEC; col < V; col += LOSS_THREADS * VEC) {
+    for (int col = threadIdx.x * VEC; col < V; col += NT * VEC) {
       float t[VEC], o[VEC];
       load_f<T, VEC>(zr + col, t);
 #pragma unroll
@@ -111,15 +111,18 @@ __global__ __launch_bounds__(LOSS_THREADS) void loss_kernel(T* __restrict__ z, c
 template <typename T>
 static void loss_dispatch(hipStream_t s, void* z, const int* labels, float* loss_rows, float* nll_rows, int rows, int V,
                           float eps, const float* scale_ptr, float mult, float* sso) {
-  dim3 grid(rows), block(LOSS_THREADS);
-#define LOSS(VEC, CACHED, NCH)                                                                                       \
-  hipLaunchKernelGGL((loss_kernel<T, VEC, CACHED, NCH>), grid, block, 0, s, (T*)z, labels, loss_rows, nll_rows, V, eps, \
+  dim3 grid(rows);
+#define LOSS(VEC, CACHED, NCH, NT)                                                                                       \
+  hipLaunchKernelGGL((loss_kernel<T, VEC, CACHED, NCH, NT>), grid, dim3(NT), 0, s, (T*)z, labels, loss_rows, nll_rows, V, eps, \
                      scale_ptr, mult, sso)
-  if (V % LV != 0) { LOSS(1, false, 1); return; }
-  const int chunks = (V / LV + LOSS_THREADS - 1) / LOSS_THREADS;
-  if (sizeof(T) == 2 && chunks <= 4) LOSS(LV, true, 4);
-  else if (sizeof(T) == 2 && chunks <= LOSS_MAX_CHUNKS) LOSS(LV, true, LOSS_MAX_CHUNKS);
-  else LOSS(LV, false, 1);
+  if (V % LV != 0) { LOSS(1, false, 1, 256); return; }
+  const int vecs = V / LV;                               // 8-element vectors in a row
+  // the row stays in registers when it fits; long rows get 1024 threads so that few registers hold it and many
+  // wavefronts per CU keep loads in flight
+  if (sizeof(T) == 2 && vecs <= 4 * 256) LOSS(LV, true, 4, 256);
+  else if (sizeof(T) == 2 && vecs <= 4 * 1024) LOSS(LV, true, 4, 1024);
+  else if (sizeof(T) == 2 && vecs <= LOSS_MAX_CHUNKS * 1024) LOSS(LV, true, LOSS_MAX_CHUNKS, 1024);
+  else LOSS(LV, false, 1, 1024);
 #undef LOSS
 }
 
