@@ -200,11 +200,103 @@ __global__ __launch_bounds__(64 * LNB_WAVES) void layernorm_bwd_kernel(
   }
 }
 
+// Column held by slot p of the row kernel's LDS / partial layout: lane l keeps elements i = 0..7 of 8-vector
+// l + 64 c in slot c * 512 + i * 64 + l, so that a wavefront's stores of one element hit 64 different banks
+// (storing a lane's 8 values side by side would be an 8-way conflict, 16 wavefronts deep).  d must be a multiple of 512.
+__host__ __device__ __forceinline__ int ln_slot_column(int p) { return ((p & 63) + 64 * (p >> 9)) * 8 + ((p >> 6) & 7); }
+
+// The same computation when every row can have a wavefront of its own (rows <= LNB_MAX_BLOCKS * LNR_WAVES): 16
+// wavefronts per block, one row each, no loop.  Nothing is accumulated across rows, so the three per-column
+// quantities go from the row's registers straight into the block's LDS reduction, the register footprint stays below
+// 128 and a row's two dependent passes are the whole critical path.
+constexpr int LNR_WAVES = 16;
+
+template <typename T, int NCH>
+__global__ __launch_bounds__(64 * LNR_WAVES) void layernorm_bwd_row_kernel(
+    const T* __restrict__ dn, const T* __restrict__ add, const T* __restrict__ sres, const float* __restrict__ mean,
+    const float* __restrict__ rstd, const T* __restrict__ gamma, T* __restrict__ ds, T* __restrict__ ds_drop,
+    float* __restrict__ partial, int rows, int d, uint64_t key, uint32_t thr, float inv_keep) {
+  extern __shared__ float lds[];     // [LNR_WAVES][d]
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int row = blockIdx.x * LNR_WAVES + w;
+  const bool live = row < rows;
+  const size_t base = (size_t)(live ? row : 0) * d;
+  float a[NCH][LN_VEC], xh[NCH][LN_VEC], o[NCH][LN_VEC];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c)
+#pragma unroll
+    for (int i = 0; i < LN_VEC; ++i) a[c][i] = xh[c][i] = o[c][i] = 0.f;
+  if (live) {
+    const float mu = mean[row], rs = rstd[row];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int col = (lane + 64 * c) * LN_VEC;
+      if (col < d) {
+        float b[LN_VEC], g[LN_VEC];
+        load_f<T, LN_VEC>(dn + base + col, a[c]);
+        load_f<T, LN_VEC>(sres + base + col, b);
+        load_f<T, LN_VEC>(gamma + col, g);
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i) {
+          xh[c][i] = (b[i] - mu) * rs;
+          o[c][i] = a[c][i] * g[i];                      // dxhat, turned into ds below
+          s1 += o[c][i];
+          s2 += o[c][i] * xh[c][i];
+        }
+      }
+    }
+    const float c1 = wave_sum(s1) / (float)d, c2 = wave_sum(s2) / (float)d;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int col = (lane + 64 * c) * LN_VEC;
+      if (col < d) {
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i) o[c][i] = rs * (o[c][i] - c1 - xh[c][i] * c2);
+        if (add) {
+          float t[LN_VEC];
+          load_f<T, LN_VEC>(add + base + col, t);
+#pragma unroll
+          for (int i = 0; i < LN_VEC; ++i) o[c][i] += t[i];
+        }
+        store_f<T, LN_VEC>(ds + base + col, o[c]);
+        if (thr) {
+          drop_apply<LN_VEC>(o[c], key, base + col, thr, inv_keep);
+          store_f<T, LN_VEC>(ds_drop + base + col, o[c]);
+        }
+        // the consumers read the rounded value; sum exactly what they will see
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i) o[c][i] = to_f<T>(from_f<T>(o[c][i]));
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int col = (lane + 64 * c) * LN_VEC;
+      if (col < d) {
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i)                  // slot (c, i, lane): consecutive lanes, consecutive banks
+          lds[w * d + c * 512 + i * 64 + lane] = k == 0 ? a[c][i] * xh[c][i] : (k == 1 ? a[c][i] : o[c][i]);
+      }
+    }
+    __syncthreads();
+    for (int slot = threadIdx.x; slot < d; slot += 64 * LNR_WAVES) {    // partials stay in slot order (see ln_slot_column)
+      float t = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < LNR_WAVES; ++ww) t += lds[ww * d + slot];
+      partial[((size_t)blockIdx.x * 3 + k) * d + slot] = t;
+    }
+  }
+}
+
 // out_k[j] = sum_p partial[p][k][j], p in a fixed order; k < nk <= 3.  One block owns 32 columns of one k: 8 row
 // lanes stride over the partials (coalesced 128-byte reads), then LDS combines the 8 lanes in a fixed order.
 template <typename T>
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int np, int nk, int n, T* o0, T* o1,
-                                                              T* o2) {
+                                                              T* o2, int slots) {
   __shared__ float sh[8][32];
   const int cx = threadIdx.x & 31, py = threadIdx.x >> 5;
   const int k = blockIdx.y;
@@ -229,7 +321,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
       float t = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) t += sh[i][cx];
-      o[j] = from_f<T>(t);
+      o[slots ? ln_slot_column(j) : j] = from_f<T>(t);    // slots: index j is a slot of the row kernel's layout
     }
   }
 }
@@ -246,9 +338,22 @@ static void ln_bwd_dispatch(hipStream_t s, const void* dn, const void* add, cons
                             void* dbias, int rows, int d, uint64_t key, float p, void* scratch) {
   const uint32_t thr = (p > 0.f && ds_drop) ? drop_threshold(p) : 0u;
   const float inv_keep = 1.f / (1.f - p);
+  const int nch = (d + 511) / 512;
+  if (rows <= LNB_MAX_BLOCKS * LNR_WAVES && d % 512 == 0 && nch <= 2) {   // a wavefront per row
+    const int nbr = (rows + LNR_WAVES - 1) / LNR_WAVES;
+    const size_t shr = (size_t)LNR_WAVES * d * sizeof(float);
+#define LN_BWD_ROW(N)                                                                                                   \
+  hipLaunchKernelGGL((layernorm_bwd_row_kernel<T, N>), dim3(nbr), dim3(64 * LNR_WAVES), shr, s, (const T*)dn, (const T*)add,        \
+                     (const T*)sres, mean, rstd, (const T*)gamma, (T*)ds, (T*)ds_drop, (float*)scratch, rows, d, key, thr, \
+                     inv_keep)
+    if (nch <= 1) LN_BWD_ROW(1); else LN_BWD_ROW(2);
+#undef LN_BWD_ROW
+    hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((d + 31) / 32, 3), dim3(256), 0, s, (const float*)scratch, nbr, 3, d,
+                       (T*)dgamma, (T*)dbeta, (T*)dbias, 1);
+    return;
+  }
   const int nb = lnb_blocks(rows);
   const size_t shm = (size_t)LNB_WAVES * d * sizeof(float);
-  const int nch = (d + 511) / 512;
 #define LN_BWD(N)                                                                                                       \
   hipLaunchKernelGGL((layernorm_bwd_kernel<T, N>), dim3(nb), dim3(64 * LNB_WAVES), shm, s, (const T*)dn, (const T*)add,             \
                      (const T*)sres, mean, rstd, (const T*)gamma, (T*)ds, (T*)ds_drop, (float*)scratch, rows, d, key, thr, \
@@ -256,7 +361,7 @@ static void ln_bwd_dispatch(hipStream_t s, const void* dn, const void* add, cons
   if (nch <= 1) LN_BWD(1); else if (nch == 2) LN_BWD(2); else if (nch == 3) LN_BWD(3); else LN_BWD(4);
 #undef LN_BWD
   hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((d + 31) / 32, 3), dim3(256), 0, s, (const float*)scratch, nb, 3, d,
-                     (T*)dgamma, (T*)dbeta, (T*)dbias);
+                     (T*)dgamma, (T*)dbeta, (T*)dbias, 0);
 }
 
 void launch_layernorm_bwd(hipStream_t s, int dt, const void* dn, const void* add, const void* sres, const float* mean,
@@ -308,7 +413,7 @@ static void colsum_dispatch(hipStream_t s, const void* x, int ld, int rows, int 
   dim3 grid((n + 64 * LN_VEC - 1) / (64 * LN_VEC), ny);
   hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, s, (const T*)x, ld, rows, n, (float*)scratch);
   hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((n + 31) / 32, 1), dim3(256), 0, s, (const float*)scratch, ny, 1, n,
-                     (T*)out, (T*)nullptr, (T*)nullptr);
+                     (T*)out, (T*)nullptr, (T*)nullptr, 0);
 }
 
 void launch_colsum(hipStream_t s, int dt, const void* x, int ld, int rows, int n, void* out, void* scratch) {
