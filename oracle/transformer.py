@@ -320,12 +320,76 @@ class OracleTransformer:
     # -- one sentence ------------------------------------------------------------------------------------------
     def _embed_fwd(self, ids, stream, row0):
         d = self.shape.d_model
-        x = np.sqrt(d) * self.p["embed"][ids] + positional_encoding(len(ids), d)
+        x = np.sqrt(d) * self._lookup(ids) + positional_encoding(len(ids), d)
         return self._drop(x, stream, -1, 0, row0)
 
     def _embed_bwd(self, ids, dx, keep, g):
-        dx = self._drop_bwd(dx, keep)
-        g.add_rows("embed", ids, np.sqrt(self.shape.d_model) * dx, self.shape.vocab)
+        dx = np.sqrt(self.shape.d_model) * self._drop_bwd(dx, keep)
+        if not self.shape.cutoffs:
+            g.add_rows("embed", ids, dx, self.shape.vocab)
+            return
+        P = self.p
+        for c, (lo, hi) in enumerate(self.shape.cluster_bounds()):
+            sel = (ids >= lo) & (ids < hi)
+            if not sel.any():
+                continue
+            if c == 0:
+                g.add_rows("embed", ids[sel], dx[sel], P["embed"].shape[0])
+            else:
+                rows = P[f"embed.{c}"][ids[sel] - lo]
+                g.add(f"embed.{c}.proj", dx[sel].T @ rows)
+                g.add_rows(f"embed.{c}", ids[sel] - lo, dx[sel] @ P[f"embed.{c}.proj"], hi - lo)
+
+    # -- adaptive input embeddings / adaptive softmax (Applications, language modeling) ------------------------
+    def _lookup(self, ids):
+        """Token vectors before scaling: the head's rows as they are, a tail cluster's narrow rows through
+        the cluster's projection up to the model width."""
+        P = self.p
+        if not self.shape.cutoffs:
+            return P["embed"][ids]
+        out = np.zeros((len(ids), self.shape.d_model))
+        for c, (lo, hi) in enumerate(self.shape.cluster_bounds()):
+            sel = (ids >= lo) & (ids < hi)
+            if c == 0:
+                out[sel] = P["embed"][ids[sel]]
+            else:
+                out[sel] = P[f"embed.{c}"][ids[sel] - lo] @ P[f"embed.{c}.proj"].T
+        return out
+
+    def _adaptive_nll(self, y, tgt, scale, g):
+        """log p(w) = log p_head(w) for a head token, log p_head(cluster of w) + log p_cluster(w) otherwise; the
+        head is a softmax over its tokens plus one entry per tail cluster, a tail cluster projects the state down
+        to its width (transposed input projection) and scores its own tokens (its input table).  Returns
+        (nll per token, d nll * scale / d y, max |d logits|) and adds the parameter gradients to g."""
+        P = self.p
+        bounds = self.shape.cluster_bounds()
+        c0 = bounds[0][1]
+        cluster = np.zeros(len(tgt), dtype=np.int64)
+        for c, (lo, hi) in enumerate(bounds):
+            cluster[(tgt >= lo) & (tgt < hi)] = c
+        z = y @ P["embed"].T
+        head_label = np.where(cluster == 0, tgt, c0 + cluster - 1)
+        _, nll, dz = label_smoothed_nll(z, head_label, 0.0)
+        dz *= scale
+        dz_max = float(np.max(np.abs(dz))) if dz.size else 0.0
+        g.add("embed", dz.T @ y)
+        dy = dz @ P["embed"]
+        for c in range(1, len(bounds)):
+            sel = np.nonzero(cluster == c)[0]
+            if len(sel) == 0:
+                continue
+            lo = bounds[c][0]
+            E, Pc = P[f"embed.{c}"], P[f"embed.{c}.proj"]
+            u = y[sel] @ Pc
+            _, nll_c, dzc = label_smoothed_nll(u @ E.T, tgt[sel] - lo, 0.0)
+            dzc *= scale
+            dz_max = max(dz_max, float(np.max(np.abs(dzc))))
+            nll[sel] += nll_c
+            du = dzc @ E
+            g.add(f"embed.{c}", dzc.T @ u)
+            g.add(f"embed.{c}.proj", y[sel].T @ du)
+            dy[sel] += du @ Pc.T
+        return nll, dy, dz_max
 
     def _sentence(self, src, tgt, srow0, trow0, scale, g):
         """Forward + backward of scale * sum_t loss_t for one sentence.  Returns (loss_sum, nll_sum, max|dz|)."""
@@ -363,14 +427,18 @@ class OracleTransformer:
             dcaches.append((c1, c2, c3))
         if sh.pre_norm:
             y, dec_lnf = layer_norm_fwd(y, P["dec.ln_final.g"], P["dec.ln_final.b"])
-        z = y @ P["embed"].T                                    # tied output projection, no bias
-        loss, nll, dz = label_smoothed_nll(z, tgt, self.cfg.label_smoothing)
-        dz *= scale                                             # the loss is scaled right after the forward pass
-        dz_max = float(np.max(np.abs(dz))) if dz.size else 0.0
-
-        # ---- backward
-        g.add("embed", dz.T @ y)
-        dy = dz @ P["embed"]
+        if sh.cutoffs:
+            assert self.cfg.label_smoothing == 0.0, "the adaptive softmax is trained on the plain likelihood"
+            nll, dy, dz_max = self._adaptive_nll(y, np.asarray(tgt, dtype=np.int64), scale, g)
+            loss = nll
+        else:
+            z = y @ P["embed"].T                                # tied output projection, no bias
+            loss, nll, dz = label_smoothed_nll(z, tgt, self.cfg.label_smoothing)
+            dz *= scale                                         # the loss is scaled right after the forward pass
+            dz_max = float(np.max(np.abs(dz))) if dz.size else 0.0
+            # ---- backward
+            g.add("embed", dz.T @ y)
+            dy = dz @ P["embed"]
         if sh.pre_norm:
             dy, dg, db = layer_norm_bwd(dy, dec_lnf)
             g.add("dec.ln_final.g", dg)

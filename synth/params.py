@@ -15,8 +15,8 @@ def init_params(shape: ModelShape, seed: int, *, generic: bool = False):
     d = shape.d_model
     out = {}
     for name, shp in param_specs(shape):
-        if name == "embed":
-            a = rng.normal(0.0, d ** -0.5, size=shp)
+        if name == "embed" or (name.startswith("embed.") and not name.endswith(".proj")):
+            a = rng.normal(0.0, shp[1] ** -0.5, size=shp)
         elif len(shp) == 2:
             lim = (6.0 / (shp[0] + shp[1])) ** 0.5
             a = rng.uniform(-lim, lim, size=shp)

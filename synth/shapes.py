@@ -9,6 +9,12 @@ Every linear layer is stored as W[out, in] and computes y = x W^T + b.  The quer
 of self-attention are one fused matrix `wqkv` whose row blocks are (Wq; Wk; Wv); cross-attention keeps
 `wq` for the decoder side and a fused `wkv` = (Wk; Wv) for the encoder side.  There is one shared
 embedding table `embed` [V, d]; the output projection is tied to it and has no bias.
+
+With `cutoffs` (language model only) the vocabulary, sorted by frequency, is cut into a head [0, c_0) and tail
+clusters [c_{i-1}, c_i), the last one ending at V (adaptive input embeddings and adaptive softmax, Applications:
+language modeling).  Tail cluster i = 1, 2, ... has its own table `embed.i` [V_i, d / factor^i] and a projection
+`embed.i.proj` [d, d / factor^i]; both are shared between the input and the output side.  `embed` then has
+c_0 + (number of tail clusters) rows: the head's tokens followed by one output row per tail cluster.
 """
 from dataclasses import dataclass, asdict
 
@@ -24,6 +30,16 @@ class ModelShape:
     pad_id: int = 1
     eos_id: int = 2
     pre_norm: int = 0      # 0: LayerNorm after each residual sum; 1: before each sub-layer plus a final one
+    cutoffs: tuple = ()    # adaptive input/softmax: ascending ends of the head and of every tail cluster but the last
+    factor: int = 4        # width of tail cluster i is d_model / factor^i
+
+    def cluster_bounds(self):
+        """[(lo, hi)] of the head and the tail clusters; a single (0, vocab) without cutoffs."""
+        edges = [0, *self.cutoffs, self.vocab]
+        return [(edges[i], edges[i + 1]) for i in range(len(edges) - 1)]
+
+    def cluster_width(self, i):
+        return self.d_model // self.factor ** i
 
     def asdict(self):
         return asdict(self)
@@ -34,6 +50,8 @@ PRESETS = {
     "base": ModelShape(6, 6, 512, 8, 2048, 32768),
     "big": ModelShape(6, 6, 1024, 16, 4096, 32768),
     "lm16": ModelShape(0, 16, 1024, 16, 4096, 32768, pre_norm=1),
+    # the same network with adaptive inputs / adaptive softmax over a WikiText-103-sized vocabulary
+    "lm16a": ModelShape(0, 16, 1024, 16, 4096, 267744, pre_norm=1, cutoffs=(20000, 60000)),
 }
 
 
@@ -60,7 +78,14 @@ def _ffn(prefix, d, f):
 def param_specs(shape: ModelShape):
     """Canonical ordered list of (name, shape) for every learnable tensor."""
     d, f = shape.d_model, shape.d_ffn
-    out = [("embed", (shape.vocab, d))]
+    if shape.cutoffs:
+        bounds = shape.cluster_bounds()
+        out = [("embed", (bounds[0][1] + len(bounds) - 1, d))]
+        for i in range(1, len(bounds)):
+            di = shape.cluster_width(i)
+            out += [(f"embed.{i}", (bounds[i][1] - bounds[i][0], di)), (f"embed.{i}.proj", (d, di))]
+    else:
+        out = [("embed", (shape.vocab, d))]
     for i in range(shape.enc_layers):
         p = f"enc.{i}"
         out += _attn_self(p + ".self", d) + _ln(p + ".ln_self", d)
