@@ -68,6 +68,17 @@ typedef struct {
   int32_t scale_window;     /* clean updates after which the scale doubles                                   */
   float   min_loss_scale;   /* tfm_apply_update reports TFM_ESCALE below this                                */
   uint64_t seed;            /* dropout seed; parameters are set by the caller                                */
+  /* Adaptive input embeddings and adaptive softmax (Applications, language modeling); decoder-only models with
+   * label_smoothing = 0.  n_cutoffs = 0: one flat tied table.  Otherwise the vocabulary (sorted by frequency) is
+   * the head [0, cutoffs[0]) plus n_cutoffs tail clusters [cutoffs[i-1], cutoffs[i]), the last ending at vocab; tail
+   * cluster i has a table "embed.i" [V_i, d_model / adaptive_factor^i] and a projection "embed.i.proj"
+   * [d_model, d_model / adaptive_factor^i], both shared by the input and the output side, and "embed" holds the
+   * head's cutoffs[0] tokens followed by one output row per tail cluster.  The matrix-core kernels serve tables
+   * whose row counts (cutoffs[0] + n_cutoffs, every V_i) and widths are multiples of 8; other sizes run on the
+   * generic kernels. */
+  int32_t n_cutoffs;        /* 0 .. 3 */
+  int32_t cutoffs[3];
+  int32_t adaptive_factor;  /* >= 1 when n_cutoffs > 0 */
 } tfm_config;
 
 typedef struct {

@@ -11,11 +11,13 @@ template <typename T>
 __global__ __launch_bounds__(256) void embed_fwd_kernel(const T* __restrict__ E, const int* __restrict__ ids,
                                                         const int* __restrict__ pos, const float* __restrict__ pe,
                                                         T* __restrict__ out, int rows, int d, float scale, uint64_t key,
-                                                        uint32_t thr, float inv_keep) {
+                                                        uint32_t thr, float inv_keep, const T* __restrict__ alt) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
-  const T* e = E + (size_t)ids[row] * d;
+  // a negative id -1-k selects row k of `alt` (adaptive inputs: the projected vectors of tail-cluster tokens)
+  const int id = ids[row];
+  const T* e = id >= 0 ? E + (size_t)id * d : alt + (size_t)(-1 - id) * d;
   const float* p = pe + (size_t)pos[row] * d;
   for (int col = lane * EV; col < d; col += 64 * EV) {
     float v[EV];
@@ -28,14 +30,14 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(const T* __restrict__ E,
 }
 
 void launch_embed_fwd(hipStream_t s, int dt, const void* E, const int* ids, const int* pos, const float* pe, void* out,
-                      int rows, int d, uint64_t key, float p) {
+                      int rows, int d, uint64_t key, float p, const void* alt) {
   if (rows <= 0) return;
   const uint32_t thr = p > 0.f ? drop_threshold(p) : 0u;
   const float inv_keep = 1.f / (1.f - p), scale = sqrtf((float)d);
   dim3 grid((rows + 3) / 4), block(256);
-  if (dt == F32) hipLaunchKernelGGL((embed_fwd_kernel<float>), grid, block, 0, s, (const float*)E, ids, pos, pe, (float*)out, rows, d, scale, key, thr, inv_keep);
-  else if (dt == F16) hipLaunchKernelGGL((embed_fwd_kernel<half_t>), grid, block, 0, s, (const half_t*)E, ids, pos, pe, (half_t*)out, rows, d, scale, key, thr, inv_keep);
-  else hipLaunchKernelGGL((embed_fwd_kernel<bf16_t>), grid, block, 0, s, (const bf16_t*)E, ids, pos, pe, (bf16_t*)out, rows, d, scale, key, thr, inv_keep);
+  if (dt == F32) hipLaunchKernelGGL((embed_fwd_kernel<float>), grid, block, 0, s, (const float*)E, ids, pos, pe, (float*)out, rows, d, scale, key, thr, inv_keep, (const float*)alt);
+  else if (dt == F16) hipLaunchKernelGGL((embed_fwd_kernel<half_t>), grid, block, 0, s, (const half_t*)E, ids, pos, pe, (half_t*)out, rows, d, scale, key, thr, inv_keep, (const half_t*)alt);
+  else hipLaunchKernelGGL((embed_fwd_kernel<bf16_t>), grid, block, 0, s, (const bf16_t*)E, ids, pos, pe, (bf16_t*)out, rows, d, scale, key, thr, inv_keep, (const bf16_t*)alt);
 }
 
 // Embedding gradient.  The host groups the occurrences of every distinct token (fixed order) and cuts each group into

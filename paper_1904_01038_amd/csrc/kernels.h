@@ -84,8 +84,16 @@ void launch_loss(hipStream_t s, int dt, void* z, const int* labels, float* loss_
 // sums[0] = sum loss_rows, sums[1] = sum nll_rows (double, single block, fixed order)
 void launch_sum_rows(hipStream_t s, const float* loss_rows, const float* nll_rows, int rows, double* sums);
 
+// ids[r] >= 0: row ids[r] of E; ids[r] = -1-k: row k of alt (both d wide)
 void launch_embed_fwd(hipStream_t s, int dt, const void* E, const int* ids, const int* pos, const float* pe, void* out,
-                      int rows, int d, uint64_t key, float p);
+                      int rows, int d, uint64_t key, float p, const void* alt = nullptr);
+// ---- adaptive inputs / adaptive softmax: row movers (index lists from the host) ----------------------------------------
+void launch_gather_rows(hipStream_t s, int dt, const void* src, int ld_src, const int* idx, void* dst, int width, int n);
+void launch_gather_dx(hipStream_t s, int dt, const void* dx, const int* idx, void* dst, int d, int n, float scale, uint64_t key, float p);
+void launch_scatter_add_rows(hipStream_t s, int dt, void* dst, int ld_dst, const int* idx, const void* src, int width, int n);
+void launch_scatter_add_f32(hipStream_t s, float* a, float* b, const int* idx, const float* sa, const float* sb, int n);
+void launch_segsum_add_rows(hipStream_t s, int dt, void* dst, const void* src, int width, const int* tok, const int* beg, const int* end,
+                            const int* entries, int n_seg);
 // Adds sqrt(d) * dropout-backward(dx) of every occurrence of a token to its row of the embedding gradient.
 // The host supplies occurrence lists cut into segments (see embed.hip); an entry is (stream << 30) | row.
 constexpr int EMB_SEG = 32;

@@ -66,6 +66,28 @@ struct Arena {
 
 constexpr int STAGE_SLOTS = 4;
 
+// Adaptive input embeddings / adaptive softmax (language model).  Cluster 0 is the head, clusters 1..n the tails.
+struct Adaptive {
+  int n = 0;                               // tail clusters (0: flat vocabulary)
+  int lo[4], hi[4], width[4];              // token range and embedding width per cluster
+  int E[4], P[4];                          // parameter indices of a tail cluster's table and projection
+  int v0;                                  // rows of "embed": the head's tokens plus one row per tail cluster
+  int vmax;                                // largest tail cluster
+  // device buffers
+  void *Xc[4], *dXc[4], *U[4], *dU[4];     // [R, width]: gathered narrow rows (input side), their gradient; projected states
+  void *Y, *dY, *Hc, *dHc;                 // [R, d]: projected inputs, their gradient; gathered states, their gradient
+  void* tmpP[4];                           // [d, width]: the output side's projection gradient until the input side adds its own
+  float *tail_loss, *tail_nll;             // [R]
+  int *in_idx, *in_tok, *out_idx, *out_lab, *sg_tok, *sg_beg, *sg_end, *sg_ent;   // [R] each, filled per step
+  // this step's counts (host)
+  int in_cnt[4], in_off[4], out_cnt[4], out_off[4], sg_cnt[4], sg_off[4];
+  int cluster_of(int id) const {
+    int c = 0;
+    while (c < n && id >= hi[c]) ++c;
+    return c;
+  }
+};
+
 struct ProfRec { int cls; hipEvent_t a, b; double flops, bytes; };
 
 }  // namespace
@@ -110,6 +132,8 @@ struct tfm_ctx {
   int *seg_tok, *seg_beg, *seg_end, *seg_dst, *mt_tok, *mt_row0, *mt_n;
   float* emb_partial;
   size_t int_block_ints;
+  Adaptive ad;
+  std::vector<std::pair<int, int>> ad_pairs;
   // host staging
   int* stage[STAGE_SLOTS];
   hipEvent_t stage_ev[STAGE_SLOTS];
@@ -156,7 +180,16 @@ int add_param(std::vector<Param>& ps, int64_t& off, const std::string& name, int
 void build_params(const tfm_config& c, std::vector<Param>& ps, int64_t& P, Stream& enc, Stream& dec) {
   const int d = c.d_model, F = c.d_ffn;
   int64_t off = 0;
-  add_param(ps, off, "embed", c.vocab, d);
+  add_param(ps, off, "embed", c.n_cutoffs ? c.cutoffs[0] + c.n_cutoffs : c.vocab, d);
+  {
+    int width = d;
+    for (int i = 1; i <= c.n_cutoffs; ++i) {
+      width /= c.adaptive_factor;
+      const int lo = c.cutoffs[i - 1], hi = i < c.n_cutoffs ? c.cutoffs[i] : c.vocab;
+      add_param(ps, off, "embed." + std::to_string(i), hi - lo, width);
+      add_param(ps, off, "embed." + std::to_string(i) + ".proj", d, width);
+    }
+  }
   auto ln = [&](const std::string& pre, int& g, int& b) {
     g = add_param(ps, off, pre + ".g", d, 0);
     b = add_param(ps, off, pre + ".b", d, 0);
@@ -232,6 +265,21 @@ int validate(const tfm_config& c, char* msg) {
   if (!(c.init_loss_scale > 0.f) || !std::isfinite(c.init_loss_scale)) BAD("init_loss_scale must be positive");
   if (c.scale_window < 1) BAD("scale_window must be >= 1");
   if (!(c.min_loss_scale >= 0.f)) BAD("min_loss_scale must be >= 0");
+  if (c.n_cutoffs < 0 || c.n_cutoffs > 3) BAD("n_cutoffs must be 0 .. 3");
+  if (c.n_cutoffs > 0) {
+    if (c.enc_layers != 0) BAD("adaptive inputs / adaptive softmax are for the decoder-only language model");
+    if (c.label_smoothing != 0.f) BAD("the adaptive softmax is trained on the plain likelihood: label_smoothing must be 0");
+    if (c.adaptive_factor < 1) BAD("adaptive_factor must be >= 1");
+    int prev = 0, width = c.d_model;
+    for (int i = 0; i < c.n_cutoffs; ++i) {
+      if (c.cutoffs[i] <= prev || c.cutoffs[i] >= c.vocab) BAD("cutoffs must ascend inside (0, vocab)");
+      prev = c.cutoffs[i];
+      if (width % c.adaptive_factor) BAD("d_model must be divisible by adaptive_factor^i for every tail cluster");
+      width /= c.adaptive_factor;
+      if (width < 4 || width % 4) BAD("a tail cluster's width must be a multiple of 4");
+    }
+    if (c.pad_id >= c.cutoffs[0] || c.eos_id >= c.cutoffs[0]) BAD("pad and eos must lie in the head");
+  }
 #undef BAD
   return TFM_OK;
 }
@@ -279,7 +327,33 @@ size_t carve(tfm_ctx* c, char* base) {
   c->dkv = a.take(R * 2 * d * esz);
   c->dmemA = a.take(R * d * esz);
   c->dmemB = a.take(R * d * esz);
-  c->logits = a.take(R * (size_t)cf.vocab * esz);
+  {
+    Adaptive& ad = c->ad;
+    ad.n = cf.n_cutoffs;
+    ad.v0 = cf.vocab;
+    ad.vmax = 0;
+    int width = (int)d;
+    for (int k = 0; k <= ad.n; ++k) {
+      ad.lo[k] = k ? cf.cutoffs[k - 1] : 0;
+      ad.hi[k] = k < ad.n ? cf.cutoffs[k] : cf.vocab;
+      ad.width[k] = width;
+      if (k) { ad.E[k] = 2 * k - 1; ad.P[k] = 2 * k; ad.vmax = std::max(ad.vmax, ad.hi[k] - ad.lo[k]); }   // parameters 1, 2, 3, 4, ...
+      width = cf.adaptive_factor > 0 ? width / cf.adaptive_factor : width;
+    }
+    if (ad.n) ad.v0 = cf.cutoffs[0] + ad.n;
+  }
+  // logits: [R, vocab], or for the adaptive softmax the head's [R, v0] followed by room for one tail cluster at a time
+  c->logits = a.take(R * (size_t)(c->ad.n ? c->ad.v0 + c->ad.vmax : cf.vocab) * esz + 256);   // (+ the tail region's alignment)
+  if (c->ad.n) {
+    Adaptive& ad = c->ad;
+    for (int k = 1; k <= ad.n; ++k) {
+      const size_t w = ad.width[k];
+      ad.Xc[k] = a.take(R * w * esz); ad.dXc[k] = a.take(R * w * esz); ad.U[k] = a.take(R * w * esz); ad.dU[k] = a.take(R * w * esz);
+      ad.tmpP[k] = a.take(d * w * esz);
+    }
+    ad.Y = a.take(R * d * esz); ad.dY = a.take(R * d * esz); ad.Hc = a.take(R * d * esz); ad.dHc = a.take(R * d * esz);
+    ad.tail_loss = (float*)a.take(R * 4); ad.tail_nll = (float*)a.take(R * 4);
+  }
   c->loss_rows = (float*)a.take(R * 4);
   c->nll_rows = (float*)a.take(R * 4);
   c->pe = (float*)a.take((size_t)cf.max_len * d * 4);
@@ -296,7 +370,7 @@ size_t carve(tfm_ctx* c, char* base) {
   const size_t Bc = (size_t)cf.max_sentences + 1;
   const size_t NS = 2 * R + 2 * R / EMB_SEG + 2, NM = 2 * R / EMB_SEG + 2;
   c->emb_partial = (float*)a.take((2 * NM) * d * sizeof(float));
-  c->int_block_ints = 2 * (2 * R + Bc) + R + 2 * R + 4 * NS + 3 * NM;
+  c->int_block_ints = 2 * (2 * R + Bc) + R + 2 * R + 4 * NS + 3 * NM + (c->ad.n ? 8 * R : 0);
   c->ibase = (int*)a.take(c->int_block_ints * 4);
   int* p = c->ibase;
   auto nxt = [&](size_t n) { int* r = base ? p : nullptr; p += n; return r; };
@@ -306,6 +380,11 @@ size_t carve(tfm_ctx* c, char* base) {
   c->uentries = nxt(2 * R);
   c->seg_tok = nxt(NS); c->seg_beg = nxt(NS); c->seg_end = nxt(NS); c->seg_dst = nxt(NS);
   c->mt_tok = nxt(NM); c->mt_row0 = nxt(NM); c->mt_n = nxt(NM);
+  if (c->ad.n) {
+    Adaptive& ad = c->ad;
+    ad.in_idx = nxt(R); ad.in_tok = nxt(R); ad.out_idx = nxt(R); ad.out_lab = nxt(R);
+    ad.sg_tok = nxt(R); ad.sg_beg = nxt(R); ad.sg_end = nxt(R); ad.sg_ent = nxt(R);
+  }
   return (a.off + 255) & ~(size_t)255;
 }
 
@@ -731,8 +810,18 @@ void stream_fwd(const StepCtx& s, Stream& st) {
   const bool pre = c->cfg.pre_norm != 0;
   void* emb = pre ? st.resid[0] : st.norm[0];
   need(c, 0);
+  const Adaptive& ad = c->ad;
+  for (int k = 1; k <= ad.n; ++k) {                  // adaptive inputs: narrow rows of tail tokens, projected up to d
+    const int n = ad.in_cnt[k], w = ad.width[k];
+    if (n == 0) continue;
+    need(c, ad.P[k]);
+    run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * n * w * 2.0,
+        [&] { launch_gather_rows(c->stream, c->dt, wh(c, ad.E[k]), w, ad.in_tok + ad.in_off[k], ad.Xc[k], w, n); });
+    gemm(c, 0, n, d, w, ad.Xc[k], w, wh(c, ad.P[k]), w, (char*)ad.Y + (size_t)ad.in_off[k] * d * c->esz, d);
+  }
   run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * T * d * 2.0, [&] {
-    launch_embed_fwd(c->stream, c->dt, c->Wh, st.ids, st.pos, c->pe, emb, T, d, site_key(s, st.id, -1, 0), c->cfg.dropout);
+    launch_embed_fwd(c->stream, c->dt, c->Wh, st.ids, st.pos, c->pe, emb, T, d, site_key(s, st.id, -1, 0), c->cfg.dropout,
+                     ad.n ? ad.Y : nullptr);
   });
   if (pre) ln_fwd(c, st.resid[0], nullptr, st.blocks[0].ln_g, st.blocks[0].ln_b, nullptr, st.norm[0], st.mean[0], st.rstd[0], T, 0);
   for (int k = 0; k < K; ++k) {
@@ -865,6 +954,69 @@ void* stream_bwd(const StepCtx& s, Stream& st, void** dmem_cur, void** dmem_othe
   return nullptr;
 }
 
+// Adaptive softmax, tail clusters (the head went through the ordinary vocabulary path with the cluster entries as
+// extra classes): for the positions whose target lies in cluster k, project the state down with the cluster's input
+// projection transposed, score the cluster's tokens with its input table, take the loss in place, and send the
+// gradients back: into the table, the projection, and (scattered) into dcur.
+void adaptive_tails(const StepCtx& s, const void* top, float mult) {
+  tfm_ctx* c = s.c;
+  const Adaptive& ad = c->ad;
+  const int d = c->cfg.d_model;
+  const size_t esz = c->esz;
+  char* Zt = (char*)c->logits + (((size_t)c->cfg.max_tokens * ad.v0 * esz + 255) & ~(size_t)255);
+  for (int k = 1; k <= ad.n; ++k) {
+    const int n = ad.out_cnt[k], w = ad.width[k], Vk = ad.hi[k] - ad.lo[k], off = ad.out_off[k];
+    void* gE = gr(c, ad.E[k]);
+    if (n == 0) {                                   // no target in this cluster: its table gets no output-side gradient
+      hipMemsetAsync(gE, 0, (size_t)Vk * w * esz, c->stream);
+      continue;
+    }
+    const void* Pk = wh(c, ad.P[k]);
+    const void* Ek = wh(c, ad.E[k]);
+    run(c, TFM_PROF_EMBED, 0.0, (double)esz * n * d * 2.0, [&] { launch_gather_rows(c->stream, c->dt, top, d, ad.out_idx + off, ad.Hc, d, n); });
+    gemm(c, 1, n, w, d, ad.Hc, d, Pk, w, ad.U[k], w);                       // u = P^T h
+    gemm(c, 0, n, Vk, w, ad.U[k], w, Ek, w, Zt, Vk);                         // z = E u
+    run(c, TFM_PROF_LOSS, 0.0, 2.0 * esz * (double)n * Vk, [&] {
+      launch_loss(c->stream, c->dt, Zt, ad.out_lab + off, ad.tail_loss + off, ad.tail_nll + off, n, Vk, 0.f, &c->st->loss_scale, mult, nullptr);
+    });
+    gemm(c, 1, n, w, Vk, Zt, Vk, Ek, w, ad.dU[k], w);                        // du = E^T dz
+    gemm(c, 2, Vk, w, n, Zt, Vk, ad.U[k], w, gE, w);                         // dE = dz^T u
+    gemm(c, 0, n, d, w, ad.dU[k], w, Pk, w, ad.dHc, d);                      // dh = P du
+    // dP (output side) = h^T du; the input side adds its own share if the cluster also occurs among the inputs
+    gemm(c, 2, d, w, n, ad.Hc, d, ad.dU[k], w, ad.in_cnt[k] ? ad.tmpP[k] : gr(c, ad.P[k]), w);
+    run(c, TFM_PROF_EMBED, 0.0, (double)esz * n * d * 3.0, [&] {
+      launch_scatter_add_rows(c->stream, c->dt, c->dcur, d, ad.out_idx + off, ad.dHc, d, n);
+      launch_scatter_add_f32(c->stream, c->loss_rows, c->nll_rows, ad.out_idx + off, ad.tail_loss + off, ad.tail_nll + off, n);
+    });
+  }
+}
+
+// Adaptive inputs, backward: ddec is the gradient w.r.t. the embedding output.  For the positions fed with a token of
+// tail cluster k: gather sqrt(d) * dropout-backward(ddec), pull it through the projection, add the rows of equal
+// tokens into the table's gradient (segments in a fixed order) and form the projection's gradient.
+void adaptive_embed_bwd(const StepCtx& s, const void* ddec) {
+  tfm_ctx* c = s.c;
+  const Adaptive& ad = c->ad;
+  const int d = c->cfg.d_model;
+  const size_t esz = c->esz;
+  for (int k = 1; k <= ad.n; ++k) {
+    const int n = ad.in_cnt[k], w = ad.width[k], off = ad.in_off[k];
+    if (n == 0) {
+      if (ad.out_cnt[k] == 0) hipMemsetAsync(gr(c, ad.P[k]), 0, (size_t)d * w * esz, c->stream);
+      continue;
+    }
+    run(c, TFM_PROF_EMBED, 0.0, (double)esz * n * d * 2.0, [&] {
+      launch_gather_dx(c->stream, c->dt, ddec, ad.in_idx + off, ad.dY, d, n, sqrtf((float)d), site_key(s, 1, -1, 0), c->cfg.dropout);
+    });
+    gemm(c, 1, n, w, d, ad.dY, d, wh(c, ad.P[k]), w, ad.dXc[k], w);           // dx_narrow = P^T dy
+    gemm(c, 2, d, w, n, ad.dY, d, ad.Xc[k], w, gr(c, ad.P[k]), w, nullptr, 0, nullptr, ad.out_cnt[k] ? ad.tmpP[k] : nullptr);
+    run(c, TFM_PROF_EMBED, 0.0, (double)esz * n * w * 3.0, [&] {
+      launch_segsum_add_rows(c->stream, c->dt, gr(c, ad.E[k]), ad.dXc[k], w, ad.sg_tok + ad.sg_off[k], ad.sg_beg + ad.sg_off[k],
+                             ad.sg_end + ad.sg_off[k], ad.sg_ent, ad.sg_cnt[k]);
+    });
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -914,6 +1066,9 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   int* uent = labels + R;
   int* seg_tok = uent + 2 * R; int* seg_beg = seg_tok + NS; int* seg_end = seg_beg + NS; int* seg_dst = seg_end + NS;
   int* mt_tok = seg_dst + NS; int* mt_row0 = mt_tok + NM; int* mt_n = mt_row0 + NM;
+  Adaptive& ad = c->ad;
+  int* a_in_idx = mt_n + NM; int* a_in_tok = a_in_idx + R; int* a_out_idx = a_in_tok + R; int* a_out_lab = a_out_idx + R;
+  int* a_sg_tok = a_out_lab + R; int* a_sg_beg = a_sg_tok + R; int* a_sg_end = a_sg_beg + R; int* a_sg_ent = a_sg_end + R;
   StepCtx s{c};
   s.B = B; s.Ts = (int)Ts; s.Tt = (int)Tt; s.step = c->train_steps;
   s.tlen.assign(tgt_lens, tgt_lens + B);
@@ -946,14 +1101,16 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
     c->ustart.resize(2 * R + 2);
     int* uniq = c->uniq.data();
     int* ustart = c->ustart.data();
+    // (adaptive inputs: only head tokens live in "embed"; tail tokens are grouped per cluster below)
+    const int head_end = ad.n ? ad.hi[0] : cf.vocab;
     for (int i = 0; i < (int)Ts; ++i) if (cnt[e_ids[i]]++ == 0) uniq[nu++] = e_ids[i];
-    for (int i = 0; i < (int)Tt; ++i) if (cnt[d_ids[i]]++ == 0) uniq[nu++] = d_ids[i];
+    for (int i = 0; i < (int)Tt; ++i) if (d_ids[i] < head_end && cnt[d_ids[i]]++ == 0) uniq[nu++] = d_ids[i];
     std::sort(uniq, uniq + nu);
     int acc = 0;
     for (int u = 0; u < nu; ++u) { ustart[u] = acc; const int n = cnt[uniq[u]]; cnt[uniq[u]] = acc; acc += n; }
     ustart[nu] = acc;
     for (int i = 0; i < (int)Ts; ++i) uent[cnt[e_ids[i]]++] = i;
-    for (int i = 0; i < (int)Tt; ++i) uent[cnt[d_ids[i]]++] = (1 << 30) | i;
+    for (int i = 0; i < (int)Tt; ++i) if (d_ids[i] < head_end) uent[cnt[d_ids[i]]++] = (1 << 30) | i;
     for (int u = 0; u < nu; ++u) cnt[uniq[u]] = 0;
     // cut every token's occurrence list into segments of at most EMB_SEG entries
     int prow = 0;
@@ -967,6 +1124,50 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
         seg_dst[n_seg] = ns > 1 ? prow++ : -1;
         ++n_seg;
       }
+    }
+  }
+  if (ad.n) {
+    // Input side: the positions whose token lies in tail cluster k, in order; their ids become -1 - (compact row) so
+    // that the embedding kernel reads the projected vector.  Rows of equal token form a segment of the table's gradient.
+    for (int k = 0; k <= ad.n; ++k) ad.in_cnt[k] = ad.out_cnt[k] = ad.sg_cnt[k] = 0;
+    for (int i = 0; i < (int)Tt; ++i) { ad.in_cnt[ad.cluster_of(d_ids[i])]++; ad.out_cnt[ad.cluster_of(labels[i])]++; }
+    int acc_in = 0, acc_out = 0;
+    for (int k = 1; k <= ad.n; ++k) { ad.in_off[k] = acc_in; acc_in += ad.in_cnt[k]; ad.out_off[k] = acc_out; acc_out += ad.out_cnt[k]; }
+    int fill_in[4] = {0, 0, 0, 0}, fill_out[4] = {0, 0, 0, 0};
+    for (int i = 0; i < (int)Tt; ++i) {
+      const int ki = ad.cluster_of(d_ids[i]);
+      if (ki) {
+        const int row = ad.in_off[ki] + fill_in[ki]++;
+        a_in_idx[row] = i;
+        a_in_tok[row] = d_ids[i] - ad.lo[ki];
+        d_ids[i] = -1 - row;
+      }
+      const int ko = ad.cluster_of(labels[i]);
+      if (ko) {
+        const int row = ad.out_off[ko] + fill_out[ko]++;
+        a_out_idx[row] = i;
+        a_out_lab[row] = labels[i] - ad.lo[ko];
+        labels[i] = ad.hi[0] + ko - 1;                     // the head predicts the cluster
+      }
+    }
+    int nseg = 0;
+    std::vector<std::pair<int, int>>& pairs = c->ad_pairs;
+    for (int k = 1; k <= ad.n; ++k) {
+      pairs.clear();
+      for (int j = 0; j < ad.in_cnt[k]; ++j) pairs.emplace_back(a_in_tok[ad.in_off[k] + j], j);
+      std::sort(pairs.begin(), pairs.end());
+      ad.sg_off[k] = nseg;
+      for (size_t j = 0; j < pairs.size(); ++j) {
+        a_sg_ent[ad.in_off[k] + j] = pairs[j].second;      // row of this cluster's compact matrices
+        if (j == 0 || pairs[j].first != pairs[j - 1].first) {
+          a_sg_tok[nseg] = pairs[j].first;
+          a_sg_beg[nseg] = ad.in_off[k] + (int)j;
+          if (j) a_sg_end[nseg - 1] = ad.in_off[k] + (int)j;
+          ++nseg;
+        }
+      }
+      if (!pairs.empty()) a_sg_end[nseg - 1] = ad.in_off[k] + (int)pairs.size();
+      ad.sg_cnt[k] = nseg - ad.sg_off[k];
     }
   }
   HIP_TRY(c, hipMemcpyAsync(c->ibase, hb, c->int_block_ints * 4, hipMemcpyHostToDevice, c->stream));
@@ -987,21 +1188,24 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   const int Kd = (int)de.blocks.size();
   const void* top = de.norm[Kd];
   adam_join(c);                                    // every parameter has been touched by now; nothing is left pending
-  gemm(c, 0, (int)Tt, V, d, top, d, c->Wh, d, c->logits, V);
+  // flat vocabulary: all V logits; adaptive softmax: the head's tokens plus one entry per tail cluster
+  const int V0 = ad.n ? ad.v0 : V;
+  gemm(c, 0, (int)Tt, V0, d, top, d, c->Wh, d, c->logits, V0);
   const float mult = c->next_mult;
   c->next_mult = 1.f;
-  run(c, TFM_PROF_LOSS, 0.0, 2.0 * c->esz * (double)Tt * V, [&] {
-    launch_loss(c->stream, c->dt, c->logits, c->labels, c->loss_rows, c->nll_rows, (int)Tt, V, cf.label_smoothing, &c->st->loss_scale,
+  run(c, TFM_PROF_LOSS, 0.0, 2.0 * c->esz * (double)Tt * V0, [&] {
+    launch_loss(c->stream, c->dt, c->logits, c->labels, c->loss_rows, c->nll_rows, (int)Tt, V0, cf.label_smoothing, &c->st->loss_scale,
                 mult, &c->st->step_scale);
-    launch_sum_rows(c->stream, c->loss_rows, c->nll_rows, (int)Tt, &c->st->loss_sum);
   });
 
   // ---- backward
   c->sync_used = 0;
   c->side_s1 = c->side_blk = nullptr;
   side_begin(c);
-  wgrad(c, V, d, (int)Tt, c->logits, V, top, d, c->g, d);                  // embedding gradient, output side
-  gemm(c, 1, (int)Tt, d, V, c->logits, V, c->Wh, d, c->dcur, d);
+  wgrad(c, V0, d, (int)Tt, c->logits, V0, top, d, c->g, d);                // embedding gradient, output side
+  gemm(c, 1, (int)Tt, d, V0, c->logits, V0, c->Wh, d, c->dcur, d);
+  if (ad.n) adaptive_tails(s, top, mult);          // tail clusters: their losses, gradients, and their share of dcur
+  run(c, TFM_PROF_LOSS, 0.0, 8.0 * (double)Tt, [&] { launch_sum_rows(c->stream, c->loss_rows, c->nll_rows, (int)Tt, &c->st->loss_sum); });
   void* dmem_cur = c->dmemA;
   void* dmem_other = c->dmemB;
   bool dmem_valid = false;
@@ -1010,6 +1214,7 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   if (has_enc) denc = stream_bwd(s, c->enc, &dmem_cur, &dmem_other, &dmem_valid, dmem_cur);
   if (c->overlap) order(c, c->side, c->stream);                            // join: every weight gradient is in g
   c->side_s1 = c->side_blk = nullptr;
+  if (ad.n) adaptive_embed_bwd(s, ddec);
   run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * d * ((double)Ts + Tt + 2.0 * nu), [&] {
     EmbedBwdArgs ea{};
     ea.dt = c->dt; ea.gE = c->g; ea.partial = c->emb_partial;
@@ -1147,6 +1352,7 @@ size_t decoder_carve(tfm_decoder* D, char* base) {
 int decoder_check(const tfm_ctx* c, int max_rows, int max_steps, int max_src, int topk) {
   if (!c) return TFM_EINVAL;
   const tfm_config& cf = c->cfg;
+  if (cf.n_cutoffs) return TFM_EINVAL;             // decoding with an adaptive softmax is not built
   if (max_rows < 1 || max_steps < 1 || max_steps > cf.max_len || topk < 1 || topk > 16 || topk > cf.vocab) return TFM_EINVAL;
   if (cf.enc_layers && (max_src < 1 || max_src > cf.max_tokens)) return TFM_EINVAL;
   // the attention kernel keeps element offsets into one cache in 32 bits
