@@ -28,6 +28,7 @@ WORKLOAD_RUN = {
     "big": ("fp16", 0.1, 1, 128.0),
     "big_accum": ("fp16", 0.1, 16, 128.0),
     "lm16": ("fp16", 0.1, 4, 128.0),
+    "lm16a": ("fp16", 0.1, 4, 128.0),
 }
 
 
@@ -51,7 +52,7 @@ def cpu_baseline(workload, shape, batches, sample_tokens):
         tgt, tl, src, sl = b.tgt[:1, :cut], np.array([cut], np.int32), None, None
     else:
         tgt, tl, src, sl = b.tgt[:n], b.tgt_lens[:n], b.src[:n], b.src_lens[:n]
-    oracle = OracleTransformer(shape, init_params(shape, 0), TrainConfig(init_loss_scale=1.0))
+    oracle = OracleTransformer(shape, init_params(shape, 0), TrainConfig(init_loss_scale=1.0, label_smoothing=0.0 if shape.cutoffs else 0.1))
     t0 = time.time()
     r = oracle.train_step(src, tgt, sl, tl)
     oracle.apply_update(1e-4)
@@ -194,7 +195,7 @@ def main():
     max_tok = max(max(b.ntokens, 0 if b.src is None else int(b.src_lens.sum())) for b in batches)
     max_sent = max(len(b.tgt_lens) for b in batches)
     cfg = T.make_config(shape, precision=prec, max_sentences=max_sent, max_len=max_len, max_tokens=(max_tok + 63) // 64 * 64,
-                        dropout=dropout, init_loss_scale=scale, seed=0)
+                        dropout=dropout, init_loss_scale=scale, seed=0, label_smoothing=0.0 if shape.cutoffs else 0.1)
     ctx = T.Tfm(cfg)
     ctx.set_params(init_params(shape, 0))
     ctx.set_overlap(not args.no_overlap)

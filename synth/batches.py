@@ -85,6 +85,7 @@ WORKLOADS = {
     "big": dict(model="big", kind="translation", lo=10, hi=80, max_tokens=3584, seed=2),
     "big_accum": dict(model="big", kind="translation", lo=10, hi=120, max_tokens=3584, seed=3),
     "lm16": dict(model="lm16", kind="lm", blocks=8, block_len=512, seed=4),
+    "lm16a": dict(model="lm16a", kind="lm", blocks=8, block_len=512, seed=5),
 }
 
 

@@ -50,8 +50,10 @@ PRESETS = {
     "base": ModelShape(6, 6, 512, 8, 2048, 32768),
     "big": ModelShape(6, 6, 1024, 16, 4096, 32768),
     "lm16": ModelShape(0, 16, 1024, 16, 4096, 32768, pre_norm=1),
-    # the same network with adaptive inputs / adaptive softmax over a WikiText-103-sized vocabulary
-    "lm16a": ModelShape(0, 16, 1024, 16, 4096, 267744, pre_norm=1, cutoffs=(20000, 60000)),
+    # The same network with adaptive inputs / adaptive softmax over a WikiText-103-sized vocabulary (267.7 K types, cut
+    # near 20 K and 60 K).  The cuts are placed so that every table has a multiple of 8 rows (19998 head tokens + 2
+    # cluster entries, 40000, 207744): the matrix-core GEMMs then serve all of them.
+    "lm16a": ModelShape(0, 16, 1024, 16, 4096, 267742, pre_norm=1, cutoffs=(19998, 59998)),
 }
 
 

@@ -23,13 +23,14 @@ def run_workload(workload, precision_name, n_sentences=None):
     max_tok = max(batch.ntokens, 0 if batch.src is None else int(batch.src_lens.sum()))
     cfg = T.make_config(shape, precision=prec, max_sentences=len(batch.tgt_lens), max_tokens=(max_tok + 63) // 64 * 64,
                         max_len=max(batch.tgt.shape[1], 0 if batch.src is None else batch.src.shape[1]),
-                        dropout=0.0, init_loss_scale=scale)
+                        dropout=0.0, init_loss_scale=scale, label_smoothing=0.0 if shape.cutoffs else 0.1)
     gpu = T.Tfm(cfg)
     gpu.set_params(params)
     rg = gpu.train_step(batch.src, batch.tgt, batch.src_lens, batch.tgt_lens)
     gg = gpu.get_grads()
     gpu.close()
-    oracle = OracleTransformer(shape, params, TrainConfig(init_loss_scale=scale, fp16_overflow=False))
+    oracle = OracleTransformer(shape, params, TrainConfig(init_loss_scale=scale, fp16_overflow=False,
+                                                          label_smoothing=0.0 if shape.cutoffs else 0.1))
     del params
     ro = oracle.train_step(batch.src, batch.tgt, batch.src_lens, batch.tgt_lens)
     return rg, ro, gg, oracle.G
@@ -54,3 +55,8 @@ def test_base_bf16_full_size_subbatch():
 
 def test_lm16_fp16_full_size_subbatch():
     check(*run_workload("lm16", "fp16"))
+
+
+def test_lm16_adaptive_fp16_full_size_subbatch():
+    """267.7 K types in three clusters: every tail GEMM at its real shape."""
+    check(*run_workload("lm16a", "fp16"))
