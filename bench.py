@@ -169,7 +169,7 @@ def main():
     ap.add_argument("--workload", default="big", choices=list(WORKLOAD_RUN) + ["decode"])
     ap.add_argument("--decode-max-tokens", type=int, default=3584, help="padded source tokens per decoding batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=384)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1100)
     ap.add_argument("--profile-steps", type=int, default=3)
     ap.add_argument("--no-overlap", action="store_true", help="enqueue weight-gradient work on the main stream too")
     args = ap.parse_args()
