@@ -102,6 +102,8 @@ struct tfm_ctx {
   std::vector<hipEvent_t> sync_ev;                  // ordering events, handed out in sequence within a step
   size_t sync_used;
   hipEvent_t side_s1, side_blk;                     // side-stream marks of the block just enqueued (null: none)
+  hipEvent_t kv_ready;                              // side-stream mark after the cross-attention K/V projections (null: none)
+  bool kv_done;                                     // they were projected ahead and the main stream already waited
   // The Adam step also runs on the side stream, cut into chunks in the order the forward pass first touches the
   // parameters (the flat order), so the next sub-batch's forward pass starts while later layers are still being
   // updated: it waits chunk by chunk.  Every other entry point first waits for the whole update.
@@ -784,7 +786,8 @@ void sublayer_fwd(const StepCtx& s, Stream& st, int k, const void* fin, void* y)
     Stream& en = c->enc;
     const void* mem = en.norm[en.blocks.size()];
     gemm(c, 0, T, d, d, fin, d, wh(c, b.w_a), d, b.inter, d, wh(c, b.b_a));
-    gemm(c, 0, en.rows, 2 * d, d, mem, d, wh(c, b.w_kv), d, b.kv, 2 * d, wh(c, b.b_kv));
+    if (c->kv_ready) { main_wait(c, c->kv_ready); c->kv_done = true; }   // projected ahead on the side stream (see tfm_train_step) ...
+    else if (!c->kv_done) gemm(c, 0, en.rows, 2 * d, d, mem, d, wh(c, b.w_kv), d, b.kv, 2 * d, wh(c, b.b_kv));   // ... or here
     const char* kv = (const char*)b.kv;
     attention(s, false, st, en, s.tlen, s.slen, b.inter, d, kv, 2 * d, kv + d * c->esz, 2 * d, b.ctx, b.lse, false);
     gemm(c, 0, T, d, d, b.ctx, d, wh(c, b.w_o), d, y, d, wh(c, b.b_o));
@@ -1182,7 +1185,23 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
     run(c, TFM_PROF_OPTIM, 0.0, (double)c->P * (c->esz + 4.0), [&] { launch_convert(c->stream, c->dt, c->g, F32, c->G, c->P); });
 
   // ---- forward
-  if (has_enc) stream_fwd(s, c->enc);
+  c->sync_used = 0;
+  c->side_s1 = c->side_blk = nullptr;
+  c->kv_ready = nullptr;
+  c->kv_done = false;
+  if (has_enc) {
+    stream_fwd(s, c->enc);
+    if (c->overlap) {
+      // Every decoder layer's cross-attention keys and values depend on the encoder output alone: project them on the
+      // side stream while the decoder's first blocks run; the first cross-attention block waits for all of them.
+      side_begin(c);
+      const void* mem = c->enc.norm[c->enc.blocks.size()];
+      for (Block& b : c->dec.blocks)
+        if (b.kind == CROSS)
+          gemm(c, 0, c->enc.rows, 2 * d, d, mem, d, wh(c, b.w_kv), d, b.kv, 2 * d, wh(c, b.b_kv), 0, nullptr, nullptr, true);
+      c->kv_ready = mark(c, c->side);
+    }
+  }
   stream_fwd(s, c->dec);
   Stream& de = c->dec;
   const int Kd = (int)de.blocks.size();
@@ -1199,8 +1218,6 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   });
 
   // ---- backward
-  c->sync_used = 0;
-  c->side_s1 = c->side_blk = nullptr;
   side_begin(c);
   wgrad(c, V0, d, (int)Tt, c->logits, V0, top, d, c->g, d);                // embedding gradient, output side
   gemm(c, 1, (int)Tt, d, V0, c->logits, V0, c->Wh, d, c->dcur, d);
