@@ -208,11 +208,14 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
   };
 
   constexpr int WAIT = (OA::LOADS + OB::LOADS) * (D - 1);   // loads that may still be in flight when a K-step must have landed
-  static_assert(WAIT <= 15, "vmcnt immediate");
+  static_assert(WAIT <= 63, "vmcnt is a 6-bit count");
+  // s_waitcnt immediate: vmcnt[3:0] in bits 3:0 and vmcnt[5:4] in bits 15:14; expcnt (6:4) and lgkmcnt (11:8) left at
+  // their maxima, i.e. not waited for
+  constexpr int WAITCNT = 0x0F70 | (WAIT & 15) | ((WAIT >> 4) << 14);
 #pragma unroll
   for (int t = 0; t < D; ++t) issue(t, t);
   u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  __builtin_amdgcn_s_waitcnt(0x0F70 | WAIT);             // K-step 0 has landed
+  __builtin_amdgcn_s_waitcnt(WAITCNT);                   // K-step 0 has landed
   __syncthreads();
   issue(D, D % STAGES);
   read_frags(0, 0, fa0, fb0);
@@ -233,7 +236,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
         if (j + 2 < KK) {
           if (j % 2 == 0) read_frags(u, j + 2, fa0, fb0); else read_frags(u, j + 2, fa1, fb1);
         } else if (j == KK - 2) {
-          __builtin_amdgcn_s_waitcnt(0x0F70 | WAIT);     // K-step kt+1 has landed for this wavefront ...
+          __builtin_amdgcn_s_waitcnt(WAITCNT);           // K-step kt+1 has landed for this wavefront ...
           __syncthreads();                               // ... and for all of them; stage u is no longer read
           read_frags((u + 1) % STAGES, 0, fa0, fb0);
           issue(kt + 1 + D, u);
@@ -415,7 +418,7 @@ static int forced_tile() {                               // tuning aid: TFM_GEMM
 //    1  128x128    32     3      3      small K: more blocks in flight hide the short K loop's ramp
 //   12  128x128    64     3      1      K >= 3072: whole 128-byte lines per row and two K-steps in flight
 //   13  256x256    64     2      1      >= 150 tiles of 256x256: half the bytes fetched per flop
-//   20   64x64     64     3      3      fewer than 128 tiles of 128x128 (a decoding step's few rows)
+//   20   64x64     64     4      2      fewer than 128 tiles of 128x128 (a decoding step's few rows)
 static int choose_tile(const GemmArgs& a) {
   if (forced_tile() > 0) return forced_tile();
   const long t1 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
@@ -432,7 +435,7 @@ static void gemm_mfma_dispatch(hipStream_t s, const GemmArgs& a) {
     case 13: gemm_mfma_launch<T, 256, 256, 2, 4, 64, 2>(s, a); break;
     case 12: gemm_mfma_launch<T, 128, 128, 2, 2, 64, 3>(s, a); break;
     case 20:                                            // (the [k][row] swizzle spans 16 vectors: NT form only)
-      if (a.form == 0) gemm_mfma_launch<T, 64, 64, 2, 2, 64, 3>(s, a);
+      if (a.form == 0) gemm_mfma_launch<T, 64, 64, 2, 2, 64, 4>(s, a);
       else gemm_mfma_launch<T, 128, 128, 2, 2, 32, 3>(s, a);
       break;
     default: gemm_mfma_launch<T, 128, 128, 2, 2, 32, 3>(s, a); break;
