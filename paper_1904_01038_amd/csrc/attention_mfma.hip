@@ -20,7 +20,7 @@
 // backward kernel more than 256 registers (one wavefront per SIMD, two blocks per CU), and the kernel is bound by the
 // latency of its dependent load -> product -> softmax chains, which only more resident wavefronts hide.
 #ifndef ATT_FWD_MIN_WAVES
-#define ATT_FWD_MIN_WAVES 4
+#define ATT_FWD_MIN_WAVES 3
 #endif
 #ifndef ATT_BWD_MIN_WAVES
 #define ATT_BWD_MIN_WAVES 2
@@ -97,6 +97,23 @@ __device__ __forceinline__ void stage_tile(uint16_t* S, const uint16_t* __restri
     *reinterpret_cast<u32x4*>(S + r * PT + c) = x;
   }
 }
+// The same in two halves, so that the next chunk's rows travel from memory while the current chunk is being used.
+__device__ __forceinline__ void fetch_tile(u32x4 (&x)[4], const uint16_t* __restrict__ G, int ld, int row0, int nvalid) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v = threadIdx.x + ATT_THREADS * i;
+    const int r = v >> 3, c = (v & 7) * 8;
+    x[i] = u32x4{0u, 0u, 0u, 0u};
+    if (row0 + r < nvalid) x[i] = *reinterpret_cast<const u32x4*>(G + (size_t)(row0 + r) * ld + c);
+  }
+}
+__device__ __forceinline__ void put_tile(uint16_t* S, const u32x4 (&x)[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v = threadIdx.x + ATT_THREADS * i;
+    *reinterpret_cast<u32x4*>(S + (v >> 3) * PT + (v & 7) * 8) = x[i];
+  }
+}
 // operand fragments of 32 rows straight from global memory (rows beyond nvalid are zero)
 __device__ __forceinline__ void load_frags(u32x4 (&f)[4], const uint16_t* __restrict__ G, int ld, int row, int nvalid, int lane) {
   const int r = row + (lane & 31);
@@ -154,11 +171,18 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_
 #pragma unroll
   for (int e = 0; e < 16; ++e) { acc[0][e] = 0.f; acc[1][e] = 0.f; }
   const int kend = p.causal ? min(lk, qstart + 64) : lk;
+  u32x4 kx[4], vx[4];                               // the next chunk's K and V rows, in flight
+  fetch_tile(kx, K, p.ldk, 0, lk);
+  fetch_tile(vx, V, p.ldv, 0, lk);
   for (int kc = 0; kc < kend; kc += CH) {
     __syncthreads();
-    stage_tile(Ks, K, p.ldk, kc, lk);
-    stage_tile(Vs, V, p.ldv, kc, lk);
+    put_tile(Ks, kx);
+    put_tile(Vs, vx);
     __syncthreads();
+    if (kc + CH < kend) {
+      fetch_tile(kx, K, p.ldk, kc + CH, lk);
+      fetch_tile(vx, V, p.ldv, kc + CH, lk);
+    }
     if (!active) continue;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
@@ -240,11 +264,18 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnP& p, int chunk, uint
 #pragma unroll
   for (int e = 0; e < 16; ++e) { acc[0][e] = 0.f; acc[1][e] = 0.f; }
   const int kend = p.causal ? min(lk, qstart + 64) : lk;
+  u32x4 kx[4], vx[4];
+  fetch_tile(kx, K, p.ldk, 0, lk);
+  fetch_tile(vx, V, p.ldv, 0, lk);
   for (int kc = 0; kc < kend; kc += CH) {
     __syncthreads();
-    stage_tile(Ks, K, p.ldk, kc, lk);
-    stage_tile(Vs, V, p.ldv, kc, lk);
+    put_tile(Ks, kx);
+    put_tile(Vs, vx);
     __syncthreads();
+    if (kc + CH < kend) {
+      fetch_tile(kx, K, p.ldk, kc + CH, lk);
+      fetch_tile(vx, V, p.ldv, kc + CH, lk);
+    }
     if (!active) continue;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
