@@ -29,6 +29,7 @@ WORKLOAD_RUN = {
     "big_accum": ("fp16", 0.1, 16, 128.0),
     "lm16": ("fp16", 0.1, 4, 128.0),
     "lm16a": ("fp16", 0.1, 4, 128.0),
+    "lm24": ("fp16", 0.1, 4, 128.0),
 }
 
 

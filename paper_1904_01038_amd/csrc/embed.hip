@@ -132,12 +132,11 @@ static void embed_bwd_dispatch(hipStream_t s, const EmbedBwdArgs& a) {
   const uint32_t thr = a.p > 0.f ? drop_threshold(a.p) : 0u;
   const float inv_keep = 1.f / (1.f - a.p), scale = sqrtf((float)a.d);
   const size_t shm = (size_t)4 * a.d * sizeof(float);
-  if (a.d <= 512)
-    hipLaunchKernelGGL((embed_bwd_kernel<T, 1>), dim3(a.n_seg), dim3(256), shm, s, (T*)a.gE, a.partial, a.seg_tok, a.seg_beg, a.seg_end,
-                       a.seg_dst, a.entries, (const T*)a.dx0, (const T*)a.dx1, a.d, scale, a.key0, a.key1, thr, inv_keep);
-  else
-    hipLaunchKernelGGL((embed_bwd_kernel<T, 2>), dim3(a.n_seg), dim3(256), shm, s, (T*)a.gE, a.partial, a.seg_tok, a.seg_beg, a.seg_end,
-                       a.seg_dst, a.entries, (const T*)a.dx0, (const T*)a.dx1, a.d, scale, a.key0, a.key1, thr, inv_keep);
+#define EMB_BWD(N)                                                                                                             \
+  hipLaunchKernelGGL((embed_bwd_kernel<T, N>), dim3(a.n_seg), dim3(256), shm, s, (T*)a.gE, a.partial, a.seg_tok, a.seg_beg, a.seg_end, \
+                     a.seg_dst, a.entries, (const T*)a.dx0, (const T*)a.dx1, a.d, scale, a.key0, a.key1, thr, inv_keep)
+  if (a.d <= 512) EMB_BWD(1); else if (a.d <= 1024) EMB_BWD(2); else if (a.d <= 1536) EMB_BWD(3); else EMB_BWD(4);   // d <= 2048
+#undef EMB_BWD
   if (a.n_multi > 0)
     hipLaunchKernelGGL((embed_bwd_merge_kernel<T>), dim3(a.n_multi), dim3(256), 0, s, (T*)a.gE, (const float*)a.partial, a.mt_tok,
                        a.mt_row0, a.mt_n, a.d, scale);

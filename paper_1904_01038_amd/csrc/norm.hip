@@ -339,7 +339,7 @@ static void ln_bwd_dispatch(hipStream_t s, const void* dn, const void* add, cons
   const uint32_t thr = (p > 0.f && ds_drop) ? drop_threshold(p) : 0u;
   const float inv_keep = 1.f / (1.f - p);
   const int nch = (d + 511) / 512;
-  if (rows <= LNB_MAX_BLOCKS * LNR_WAVES && d % 512 == 0 && nch <= 2) {   // a wavefront per row
+  if (rows <= LNB_MAX_BLOCKS * LNR_WAVES && d % 512 == 0 && nch <= 2) {   // a wavefront per row (its LDS stage stays within 64 KB)
     const int nbr = (rows + LNR_WAVES - 1) / LNR_WAVES;
     const size_t shr = (size_t)LNR_WAVES * d * sizeof(float);
 #define LN_BWD_ROW(N)                                                                                                   \

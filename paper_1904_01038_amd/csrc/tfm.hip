@@ -248,7 +248,7 @@ void build_params(const tfm_config& c, std::vector<Param>& ps, int64_t& P, Strea
 int validate(const tfm_config& c, char* msg) {
 #define BAD(...) do { snprintf(msg, 256, __VA_ARGS__); return TFM_EINVAL; } while (0)
   if (c.enc_layers < 0 || c.enc_layers > 64 || c.dec_layers < 1 || c.dec_layers > 64) BAD("layer counts out of range");
-  if (c.d_model < 8 || c.d_model > 1024 || c.d_model % 8) BAD("d_model must be a multiple of 8 in [8, 1024]");
+  if (c.d_model < 8 || c.d_model > 2048 || c.d_model % 8) BAD("d_model must be a multiple of 8 in [8, 2048]");
   if (c.n_heads < 1 || c.d_model % c.n_heads) BAD("d_model must be divisible by n_heads");
   if (c.d_model / c.n_heads > 128) BAD("head width above 128");
   if (c.d_ffn < 8 || c.d_ffn % 8) BAD("d_ffn must be a multiple of 8");
@@ -1653,7 +1653,7 @@ int tfm_op_layernorm_bwd(int32_t dtype, const void* dn, const void* add, const v
                          const void* gamma, void* ds, void* ds_drop, void* dgamma, void* dbeta, void* dbias, int32_t rows,
                          int32_t d, uint64_t drop_key, float p, void* scratch, void* stream) {
   if (dtype < 0 || dtype > 2 || !dn || !s || !mean || !rstd || !gamma || !ds || !dgamma || !dbeta || !scratch) return TFM_EINVAL;
-  if (rows < 1 || d < 8 || d % 8 || d > 1024) return TFM_EINVAL;
+  if (rows < 1 || d < 8 || d % 8 || d > 2048) return TFM_EINVAL;
   launch_layernorm_bwd((hipStream_t)stream, dtype, dn, add, s, mean, rstd, gamma, ds, ds_drop, dgamma, dbeta, dbias, rows, d,
                        drop_key, p, scratch);
   return op_done();

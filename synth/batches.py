@@ -86,6 +86,7 @@ WORKLOADS = {
     "big_accum": dict(model="big", kind="translation", lo=10, hi=120, max_tokens=3584, seed=3),
     "lm16": dict(model="lm16", kind="lm", blocks=8, block_len=512, seed=4),
     "lm16a": dict(model="lm16a", kind="lm", blocks=8, block_len=512, seed=5),
+    "lm24": dict(model="lm24", kind="lm", blocks=8, block_len=512, seed=6),
 }
 
 

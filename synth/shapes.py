@@ -50,6 +50,8 @@ PRESETS = {
     "base": ModelShape(6, 6, 512, 8, 2048, 32768),
     "big": ModelShape(6, 6, 1024, 16, 4096, 32768),
     "lm16": ModelShape(0, 16, 1024, 16, 4096, 32768, pre_norm=1),
+    # the larger language model: 24 blocks, inner dimension 8K, embedding dimension 1.5K (24 heads of width 64)
+    "lm24": ModelShape(0, 24, 1536, 24, 8192, 32768, pre_norm=1),
     # The same network with adaptive inputs / adaptive softmax over a WikiText-103-sized vocabulary (267.7 K types, cut
     # near 20 K and 60 K).  The cuts are placed so that every table has a multiple of 8 rows (19998 head tokens + 2
     # cluster entries, 40000, 207744): the matrix-core GEMMs then serve all of them.

@@ -129,3 +129,29 @@ def test_side_stream_gives_bit_identical_gradients():
     for k in runs[0][0]:
         assert np.array_equal(runs[0][0][k], runs[1][0][k]), k
         assert np.array_equal(runs[0][1][k], runs[1][1][k]), k
+
+
+@pytest.mark.parametrize("prec", ["fp32", "fp16"])
+def test_model_width_1536(prec):
+    """The larger language model's width: three 512-column chunks per row in the normalisation and embedding kernels,
+    24 heads of width 64."""
+    import paper_1904_01038_amd as T
+    shape = ModelShape(0, 1, 1536, 24, 256, 96, pre_norm=1)
+    p = T.FP32 if prec == "fp32" else T.FP16
+    gpu, oracle = make_pair(shape, p, dropout=0.1, init_loss_scale=4.0 if prec == "fp16" else 1.0, max_sentences=4, max_len=80,
+                            max_tokens=256)
+    rng = np.random.default_rng(0)
+    lens = np.array([70, 9, 33], np.int32)
+    tgt = np.full((3, 70), shape.pad_id, np.int32)
+    for i, n in enumerate(lens):
+        tgt[i, :n] = rng.integers(4, shape.vocab, n)
+    rg, ro = step_both(gpu, oracle, Batch(None, tgt, None, lens))
+    assert rg["overflow"] == 0
+    assert abs(rg["loss_sum"] - ro["loss_sum"]) <= (1e-4 if prec == "fp32" else 1e-2) * abs(ro["loss_sum"])
+    gg = gpu.get_grads()
+    for k, v in oracle.G.items():
+        if prec == "fp32":
+            assert max_rel(gg[k], v) <= 1e-3, (k, max_rel(gg[k], v))
+        else:
+            assert cosine(gg[k], v) >= 0.999, (k, cosine(gg[k], v))
+    gpu.close()
