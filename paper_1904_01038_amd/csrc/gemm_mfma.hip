@@ -28,6 +28,8 @@
 //    order by a second kernel (no atomics, reproducible).
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -328,9 +330,10 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
   }
 }
 
-// C[m, n] = sum over splits (fixed order) of partial[s][m][n]
+// C[m, n] = epilogue(sum over splits (fixed order) of partial[s][m][n]); epilogue = optional bias[n], optional ReLU
 template <typename T>
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits, int M, int N, T* __restrict__ C, int ldc) {
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits, int M, int N, T* __restrict__ C, int ldc,
+                                                            const T* __restrict__ bias, int relu) {
   const size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
   const size_t total = (size_t)M * N;
   if (idx >= total) return;
@@ -340,7 +343,17 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
   }
   const int m = (int)(idx / N), n = (int)(idx % N);
-  const float v[4] = {a.x, a.y, a.z, a.w};
+  float v[4] = {a.x, a.y, a.z, a.w};
+  if (bias) {
+    float bb[4];
+    load_f<T, 4>(bias + n, bb);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += bb[e];
+  }
+  if (relu) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+  }
   store_f<T, 4>(C + (size_t)m * ldc + n, v);
 }
 
@@ -390,8 +403,12 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   if (a.form == 2 && a.splitk_ws && !a.bias && !a.relu && !a.mask && !a.residual && p.tiles_total <= 128 && nk >= 32) {
     splits = 256 / p.tiles_total;
     if (splits > 8) splits = 8;
-    while (splits > 1 && (size_t)splits * a.M * a.N * sizeof(float) > a.splitk_ws_bytes) --splits;
+  } else if (a.form == 0 && BM == 64 && a.splitk_ws && !a.mask && !a.residual && p.tiles_total <= 128 && nk >= 8) {
+    // X W^T with few rows (a decoding step): the weights stream through more CUs; every slice keeps >= 4 K-steps and
+    // bias / ReLU move into the reduction
+    splits = std::min(std::min(256 / p.tiles_total, nk / 4), 8);
   }
+  while (splits > 1 && (size_t)splits * a.M * a.N * sizeof(float) > a.splitk_ws_bytes) --splits;
   p.ksteps_per_split = (nk + splits - 1) / splits;
   p.partial = splits > 1 ? (float*)a.splitk_ws : nullptr;
   dim3 grid(p.tiles_total, splits), block(64 * WM * WN);
@@ -403,7 +420,7 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   if (splits > 1) {
     const size_t quads = ((size_t)a.M * a.N + 3) / 4;
     hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, (const float*)a.splitk_ws, splits,
-                       a.M, a.N, (T*)a.C, a.ldc);
+                       a.M, a.N, (T*)a.C, a.ldc, (const T*)a.bias, a.relu);
   }
 }
 

@@ -93,6 +93,36 @@ def test_gemm_split_k_weight_gradient_is_exact_and_reproducible(prec, shape):
 
 
 @pytest.mark.parametrize("prec", ["fp16", "bf16"])
+@pytest.mark.parametrize("shape,bias,relu", [((280, 1024, 1024), True, False), ((192, 1024, 4096), True, True), ((72, 512, 640), False, False),
+                                             ((320, 3072, 1024), True, False)])
+def test_gemm_few_rows_split_k_with_bias_and_relu_is_exact(prec, shape, bias, relu):
+    """X W^T with few rows (a decoding step): 64x64 tiles, K split over blocks, bias and ReLU applied by the reduction."""
+    import torch
+    import paper_1904_01038_amd as T
+    M, N, K = shape
+    dt = _dtypes()[prec]
+    rng = np.random.default_rng(M + K)
+    A = rng.integers(-2, 3, (M, K)).astype(np.float64)
+    B = rng.integers(-2, 3, (N, K)).astype(np.float64)
+    bv = rng.integers(-3, 4, N).astype(np.float64)
+    ref = A @ B.T + (bv if bias else 0.0)
+    if relu:
+        ref = np.maximum(ref, 0.0)
+    assert np.abs(ref).max() < 2048 or prec == "bf16"
+    want = _t(ref, dt).float().cpu().numpy().astype(np.float64)
+    tA, tB, tb = _t(A, dt), _t(B, dt), _t(bv, dt)
+    ws = torch.empty(8 * 320 * 3072, dtype=torch.float32, device="cuda")
+    outs = []
+    for w in (ws, None, ws):
+        out = torch.zeros(M, N, dtype=dt, device="cuda")
+        T.ops.gemm(0, tA, tB, out, M, N, K, bias=tb if bias else None, relu=relu, workspace=w)
+        outs.append(out.float().cpu().numpy().astype(np.float64))
+    if prec == "fp16":
+        assert np.array_equal(outs[0], want)
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])    # split or not, run to run: the same bits
+
+
+@pytest.mark.parametrize("prec", ["fp16", "bf16"])
 def test_gemm_random_values_close_to_float64(prec):
     import torch
     import paper_1904_01038_amd as T
