@@ -411,7 +411,9 @@ void run(tfm_ctx* c, int cls, double flops, double bytes, F&& launch) { run(c, c
 hipEvent_t mark(tfm_ctx* c, hipStream_t on) {
   if (c->sync_used == c->sync_ev.size()) {
     hipEvent_t e = nullptr;
-    hipEventCreateWithFlags(&e, hipEventDisableTiming);
+    // (ordering between two streams of one device: a device-scope release is enough and far cheaper than the default,
+    // which makes the work visible to the host as well)
+    hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventReleaseToDevice);
     c->sync_ev.push_back(e);
   }
   hipEvent_t e = c->sync_ev[c->sync_used++];
@@ -542,7 +544,7 @@ int tfm_create(const tfm_config* cfg, void* ws, size_t bytes, void* hip_stream, 
       c->chunks.push_back({o0, o1 - o0, p1 - 1});
       for (int i = p0; i < p1; ++i) c->chunk_of[i] = (int)k;
       hipEvent_t e = nullptr;
-      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { fail(nullptr, TFM_EHIP, "cannot create events"); return cleanup(TFM_EHIP); }
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventReleaseToDevice) != hipSuccess) { fail(nullptr, TFM_EHIP, "cannot create events"); return cleanup(TFM_EHIP); }
       c->adam_ev.push_back(e);
     }
   }
