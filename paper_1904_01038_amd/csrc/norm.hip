@@ -292,26 +292,28 @@ __global__ __launch_bounds__(64 * LNR_WAVES) void layernorm_bwd_row_kernel(
   }
 }
 
-// out_k[j] = sum_p partial[p][k][j], p in a fixed order; k < nk <= 3.  One block owns 32 columns of one k: 8 row
-// lanes stride over the partials (coalesced 128-byte reads), then LDS combines the 8 lanes in a fixed order.
+// out_k[j] = sum_p partial[p][k][j], p in a fixed order; k < nk <= 3.  One block owns 32 columns of one k: 32 row
+// lanes stride over the partials (coalesced 128-byte reads, all of a lane's loads in flight at once for up to 256
+// partials), then LDS combines the 32 lanes in a fixed order.
+constexpr int RP_LANES = 32;
 template <typename T>
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int np, int nk, int n, T* o0, T* o1,
-                                                              T* o2, int slots) {
-  __shared__ float sh[8][32];
+__global__ __launch_bounds__(32 * RP_LANES) void reduce_partials_kernel(const float* __restrict__ partial, int np, int nk, int n, T* o0,
+                                                                        T* o1, T* o2, int slots) {
+  __shared__ float sh[RP_LANES][33];
   const int cx = threadIdx.x & 31, py = threadIdx.x >> 5;
   const int k = blockIdx.y;
   const int j = blockIdx.x * 32 + cx;
   float acc = 0.f;
   if (j < n) {
     int p = py;
-    for (; p + 56 < np; p += 64) {                      // 8 loads in flight per thread; the order of the adds is fixed
+    for (; p + 7 * RP_LANES < np; p += 8 * RP_LANES) {  // 8 loads in flight per thread; the order of the adds is fixed
       float v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = partial[((size_t)(p + 8 * u) * nk + k) * n + j];
+      for (int u = 0; u < 8; ++u) v[u] = partial[((size_t)(p + RP_LANES * u) * nk + k) * n + j];
 #pragma unroll
       for (int u = 0; u < 8; ++u) acc += v[u];
     }
-    for (; p < np; p += 8) acc += partial[((size_t)p * nk + k) * n + j];
+    for (; p < np; p += RP_LANES) acc += partial[((size_t)p * nk + k) * n + j];
   }
   sh[py][cx] = acc;
   __syncthreads();
@@ -320,7 +322,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
     if (o) {
       float t = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) t += sh[i][cx];
+      for (int i = 0; i < RP_LANES; ++i) t += sh[i][cx];
       o[slots ? ln_slot_column(j) : j] = from_f<T>(t);    // slots: index j is a slot of the row kernel's layout
     }
   }
@@ -348,7 +350,7 @@ static void ln_bwd_dispatch(hipStream_t s, const void* dn, const void* add, cons
                      inv_keep)
     if (nch <= 1) LN_BWD_ROW(1); else LN_BWD_ROW(2);
 #undef LN_BWD_ROW
-    hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((d + 31) / 32, 3), dim3(256), 0, s, (const float*)scratch, nbr, 3, d,
+    hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((d + 31) / 32, 3), dim3(32 * RP_LANES), 0, s, (const float*)scratch, nbr, 3, d,
                        (T*)dgamma, (T*)dbeta, (T*)dbias, 1);
     return;
   }
@@ -360,7 +362,7 @@ static void ln_bwd_dispatch(hipStream_t s, const void* dn, const void* add, cons
                      inv_keep)
   if (nch <= 1) LN_BWD(1); else if (nch == 2) LN_BWD(2); else if (nch == 3) LN_BWD(3); else LN_BWD(4);
 #undef LN_BWD
-  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((d + 31) / 32, 3), dim3(256), 0, s, (const float*)scratch, nb, 3, d,
+  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((d + 31) / 32, 3), dim3(32 * RP_LANES), 0, s, (const float*)scratch, nb, 3, d,
                      (T*)dgamma, (T*)dbeta, (T*)dbias, 0);
 }
 
@@ -412,7 +414,7 @@ static void colsum_dispatch(hipStream_t s, const void* x, int ld, int rows, int 
   const int ny = (rows + CS_ROWS_PER_BLOCK - 1) / CS_ROWS_PER_BLOCK;
   dim3 grid((n + 64 * LN_VEC - 1) / (64 * LN_VEC), ny);
   hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, s, (const T*)x, ld, rows, n, (float*)scratch);
-  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((n + 31) / 32, 1), dim3(256), 0, s, (const float*)scratch, ny, 1, n,
+  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((n + 31) / 32, 1), dim3(32 * RP_LANES), 0, s, (const float*)scratch, ny, 1, n,
                      (T*)out, (T*)nullptr, (T*)nullptr, 0);
 }
 
