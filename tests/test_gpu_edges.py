@@ -155,3 +155,20 @@ def test_model_width_1536(prec):
         else:
             assert cosine(gg[k], v) >= 0.999, (k, cosine(gg[k], v))
     gpu.close()
+
+
+@pytest.mark.parametrize("prec", ["fp16", "bf16"])
+def test_half_precision_with_head_widths_other_than_64(prec):
+    """Head widths 16 and 128 take the generic attention kernels; odd sizes take the generic GEMM."""
+    import paper_1904_01038_amd as T
+    p = T.FP16 if prec == "fp16" else T.BF16
+    for shape in (ModelShape(1, 1, 64, 4, 136, 88), ModelShape(1, 1, 256, 2, 64, 72, pre_norm=1)):
+        gpu, oracle = make_pair(shape, p, dropout=0.1, init_loss_scale=4.0, max_sentences=8, max_len=40, max_tokens=256)
+        batch = make_batches("base", 1, shape=shape, max_tokens=200, lo=5, hi=38)[0]
+        rg, ro = step_both(gpu, oracle, batch)
+        assert rg["overflow"] == 0
+        assert abs(rg["loss_sum"] - ro["loss_sum"]) <= 1e-2 * abs(ro["loss_sum"])
+        gg = gpu.get_grads()
+        for k, v in oracle.G.items():
+            assert cosine(gg[k], v) >= 0.999, (shape, k, cosine(gg[k], v))
+        gpu.close()
