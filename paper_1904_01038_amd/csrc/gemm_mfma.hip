@@ -151,8 +151,17 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
   constexpr int D = STAGES - 1;                          // K-steps in flight ahead of the one being consumed
   typedef Operand<BM, BK, NW, ATR> OA;
   typedef Operand<BN, BK, NW, BTR> OB;
-  __shared__ __attribute__((aligned(1024))) unsigned char As[STAGES][OA::TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) unsigned char Bs[STAGES][OB::TILE_BYTES];
+  // One LDS block: the A ring, the B ring, and (re-using both once the K loop is over) the epilogue's staging strips,
+  // which for 16 wavefronts can be a little larger than the rings.
+  constexpr int SW = TN * 32;                             // epilogue strip width in columns
+  constexpr int SP = SW + 4;                              // its padded pitch in floats: conflict-free for both passes
+  constexpr int RING_BYTES = STAGES * (OA::TILE_BYTES + OB::TILE_BYTES);
+  constexpr int STRIP_BYTES = NW * 32 * SP * 4;
+  constexpr int LDS_BYTES = RING_BYTES > STRIP_BYTES ? RING_BYTES : STRIP_BYTES;
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS per CU");
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_BYTES];
+  unsigned char(*As)[OA::TILE_BYTES] = reinterpret_cast<unsigned char(*)[OA::TILE_BYTES]>(smem);
+  unsigned char(*Bs)[OB::TILE_BYTES] = reinterpret_cast<unsigned char(*)[OB::TILE_BYTES]>(smem + STAGES * OA::TILE_BYTES);
   // XCD-aware tile order: hardware deals block b to XCD b % 8; give each XCD a contiguous run of tile ids
   int tile;
   {
@@ -256,11 +265,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
   // its own slice of LDS (free now: every wavefront is past its last fragment read) and re-reads it so that a lane owns
   // 16 consecutive columns of a row and 4 lanes cover a whole 128-byte line of the output.
   __syncthreads();
-  constexpr int SW = TN * 32;                             // strip width in columns
-  constexpr int SP = SW + 4;                              // padded pitch in floats: conflict-free for both passes
-  static_assert(NW * 32 * SP * 4 <= STAGES * (OA::TILE_BYTES + OB::TILE_BYTES), "epilogue staging must fit in the ring");
-  float* strip = reinterpret_cast<float*>(&As[0][0]) + wave * (32 * SP);
-  static_assert(sizeof(As) % 16 == 0, "Bs follows As contiguously");
+  float* strip = reinterpret_cast<float*>(smem) + wave * (32 * SP);
   constexpr int LPR = SW / 16;                            // lanes per row when re-reading (4 for a 64-column strip)
   constexpr int RPP = 64 / LPR;                           // rows per pass
   const T* bias = reinterpret_cast<const T*>(p.bias);
@@ -430,19 +435,21 @@ static int forced_tile() {                               // tuning aid: TFM_GEMM
   return v;
 }
 
-// Configuration choice, from measurements on the projection shapes of the big Transformer (M ~ 3264 tokens):
-//   id  tile     K-step  ring   resident blocks per CU
-//    1  128x128    32     3      3      small K: more blocks in flight hide the short K loop's ramp
-//   12  128x128    64     3      1      K >= 3072: whole 128-byte lines per row and two K-steps in flight
-//   13  256x256    64     2      1      >= 150 tiles of 256x256: half the bytes fetched per flop
-//   20   64x64     64     4      2      fewer than 128 tiles of 128x128 (a decoding step's few rows)
+// Configuration choice, from measurements on the projection shapes of the big and base Transformers (M ~ 3264-3700 tokens):
+//   id  tile     wavefronts  K-step  ring   resident blocks per CU
+//    1  128x128      4         32     3      3      more than 256 tiles and K < 3072: several blocks per CU keep it fed
+//   12  128x128     16         64     3      1      K >= 3072, or at most 256 tiles (one block per CU anyway): 16 wavefronts
+//                                                   of 32x32 hide the fetch latency that 4 of 64x64 exposed (10-15 % faster)
+//   13  256x256      8         64     2      1      >= 150 tiles of 256x256: half the bytes fetched per flop (16 wavefronts
+//                                                   are slower here: more LDS traffic per flop)
+//   20   64x64       4         64     4      2      fewer than 128 tiles of 128x128 (a decoding step's few rows)
 static int choose_tile(const GemmArgs& a) {
   if (forced_tile() > 0) return forced_tile();
   const long t1 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
   if (t1 < 128 && a.form == 0) return 20;               // few rows (a decoding step, X W^T): smaller tiles reach more CUs
   const long t3 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
   if (t3 >= 150) return 13;
-  if (a.K >= 3072) return 12;
+  if (a.K >= 3072 || t1 <= 256) return 12;
   return 1;
 }
 
@@ -450,7 +457,7 @@ template <typename T>
 static void gemm_mfma_dispatch(hipStream_t s, const GemmArgs& a) {
   switch (choose_tile(a)) {
     case 13: gemm_mfma_launch<T, 256, 256, 2, 4, 64, 2>(s, a); break;
-    case 12: gemm_mfma_launch<T, 128, 128, 2, 2, 64, 3>(s, a); break;
+    case 12: gemm_mfma_launch<T, 128, 128, 4, 4, 64, 3>(s, a); break;
     case 20:                                            // (the [k][row] swizzle spans 16 vectors: NT form only)
       if (a.form == 0) gemm_mfma_launch<T, 64, 64, 2, 2, 64, 4>(s, a);
       else gemm_mfma_launch<T, 128, 128, 2, 2, 32, 3>(s, a);
