@@ -179,6 +179,15 @@ int tfm_op_gemm_ws(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K,
                    const void* B, int32_t ldb, void* C, int32_t ldc, const void* bias, int32_t relu,
                    const void* mask, const void* residual, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Grouped weight gradients, the form every linear layer's backward pass ends in (accumulated gradients of Implementation,
+ * Multi-GPU training, are sums of exactly these): for i < n (n <= 48), C_i[M_i, N_i] = A_i^T B_i with A_i[K_i, M_i],
+ * B_i[K_i, N_i], and, where colsum[i] != NULL, colsum[i][m] = sum over k of A_i[k, m] (the bias gradient), all in ONE
+ * launch.  dims: host int32 [n][6] = M, N, K, lda, ldb, ldc (row strides in elements); A, B, C, colsum: host arrays of
+ * n device pointers (colsum itself may be NULL).  dtype TFM_FP16 or TFM_BF16 only; M, N and the strides multiples of 8,
+ * pointers 16-byte aligned, else TFM_EINVAL and nothing is launched.  Outputs must not overlap inputs or each other. */
+int tfm_op_wgrad_grouped(int32_t dtype, int32_t n, const int32_t* dims, const void* const* A, const void* const* B,
+                         void* const* C, void* const* colsum, void* stream);
+
 /* Multi-head attention over packed sentences.  q rows of sentence b are q_off[b]..q_off[b+1], keys/values
  * k_off[b]..k_off[b+1] (device int32 [B+1]).  Head h uses columns h*dh..(h+1)*dh.  o = softmax(q k^T/sqrt(dh)
  * [+ causal mask]) v; lse (device fp32 [H, q_off[B]]) receives the row log-sum-exp of the scaled scores. */

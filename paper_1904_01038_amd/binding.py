@@ -97,6 +97,7 @@ def lib():
         L.tfm_profile_read.argtypes = [vp, C.POINTER(ProfEntry), i32]
         L.tfm_op_gemm.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, vp]
         L.tfm_op_gemm_ws.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, vp, C.c_size_t, vp]
+        L.tfm_op_wgrad_grouped.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp]
         L.tfm_op_attention_fwd.argtypes = [i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, i32, i32, i32,
                                            i32, i32, vp]
         L.tfm_op_attention_bwd.argtypes = [i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, i32, vp, i32, vp,

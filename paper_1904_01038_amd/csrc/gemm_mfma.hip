@@ -70,6 +70,33 @@ struct MfmaGemmParams {
   int ksteps_per_split;                                  // split-K: K-steps per blockIdx.y slice
   float* partial;                                        // split-K: fp32 partial tiles [split][M][N], else null
   uint32_t a_bytes, b_bytes;                             // extents for the range-checked loads
+  uint16_t* colsum;                                      // grouped weight gradients: [M] sums of A's rows over K (a bias gradient), or null
+};
+
+// Sum of the 8 values of a fragment register quadruple, added to c in fp32 (fixed order).
+template <typename T> struct FragSum;
+template <> struct FragSum<half_t> {
+  typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+  static __device__ __forceinline__ float run(u32x4 a, float c) {
+    const f16x2 one = {(_Float16)1.f, (_Float16)1.f};
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t word = a[w];                          // (a copy: bit-casting the vector element in place read element 0 every time)
+      c = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, word), one, c, false);
+    }
+    return c;
+  }
+};
+template <> struct FragSum<bf16_t> {
+  static __device__ __forceinline__ float run(u32x4 a, float c) {
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t word = a[w];
+      c += __uint_as_float(word << 16);
+      c += __uint_as_float(word & 0xffff0000u);
+    }
+    return c;
+  }
 };
 
 // One operand's path from global memory through the LDS ring into MFMA fragments.
@@ -143,8 +170,10 @@ struct Operand {
   }
 };
 
-template <typename T, int BM, int BN, int WM, int WN, int BK, int STAGES, bool ATR, bool BTR>
-__global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfma_kernel(MfmaGemmParams p) {
+// One output tile (or one K-slice of it).  `tile` is the tile id inside this problem after the XCD re-mapping, `slice`
+// the split-K slice.  CS: the block column tn == 0 also sums A's rows over K (see MfmaGemmParams::colsum).
+template <typename T, int BM, int BN, int WM, int WN, int BK, int STAGES, bool ATR, bool BTR, bool CS>
+__device__ __forceinline__ void gemm_mfma_tile(const MfmaGemmParams& p, int tile, int slice) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;    // MFMA tiles per wavefront
   constexpr int KK = BK / 16;                            // MFMA sub-steps per K-step (2 or 4)
@@ -162,12 +191,6 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
   __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_BYTES];
   unsigned char(*As)[OA::TILE_BYTES] = reinterpret_cast<unsigned char(*)[OA::TILE_BYTES]>(smem);
   unsigned char(*Bs)[OB::TILE_BYTES] = reinterpret_cast<unsigned char(*)[OB::TILE_BYTES]>(smem + STAGES * OA::TILE_BYTES);
-  // XCD-aware tile order: hardware deals block b to XCD b % 8; give each XCD a contiguous run of tile ids
-  int tile;
-  {
-    const int b = blockIdx.x, nb = p.tiles_total, q = nb >> 3, r = nb & 7, x = b & 7;
-    tile = x * q + (x < r ? x : r) + (b >> 3);
-  }
   // Tile ids run column-major inside bands of group_m tile rows, so the run of ids an XCD works on at one time
   // covers a compact patch of the output and shares its A and B panels in that XCD's L2.
   int tm, tn;
@@ -184,7 +207,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
   const u32x4 ra = {(uint32_t)(uintptr_t)p.A, (uint32_t)((uintptr_t)p.A >> 32) & 0xffffu, p.a_bytes, 0x00020000u};
   const u32x4 rb = {(uint32_t)(uintptr_t)p.B, (uint32_t)((uintptr_t)p.B >> 32) & 0xffffu, p.b_bytes, 0x00020000u};
   // split-K: this block covers K-steps kt0 .. ; everything at or beyond kend reads as zero
-  const int kt0 = blockIdx.y * p.ksteps_per_split;
+  const int kt0 = slice * p.ksteps_per_split;
   const int kend = min(p.K, (kt0 + p.ksteps_per_split) * BK);
   const int nk = max(0, (kend - kt0 * BK + BK - 1) / BK);
   OA oa;
@@ -211,11 +234,21 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
 #pragma unroll
     for (int j = 0; j < TN; ++j) fb[j] = OB::frag(Bs[stage], wn * (BN / WN) + j * 32, kk, lane);
   };
+  // Row sums of A: the wavefronts of the first tile column that hold the first column strip see every A fragment of
+  // their rows exactly once (K-steps beyond the slice read zeros), so they add them up on the vector ALU beside the MFMAs.
+  const bool do_cs = CS && p.colsum != nullptr && tn == 0 && wn == 0;
+  float cs[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) cs[i] = 0.f;
   auto mfmas = [&](const u32x4 (&fa)[TM], const u32x4 (&fb)[TN]) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::run(fb[j], fa[i], acc[i][j]);   // transposed product: D'[n][m]
+    if (CS && do_cs) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) cs[i] = FragSum<T>::run(fa[i], cs[i]);
+    }
   };
 
   constexpr int WAIT = (OA::LOADS + OB::LOADS) * (D - 1);   // loads that may still be in flight when a K-step must have landed
@@ -272,7 +305,15 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
   const T* mask = reinterpret_cast<const T*>(p.mask);
   const T* res = reinterpret_cast<const T*>(p.residual);
   T* C = reinterpret_cast<T*>(p.C);
-  float* P = p.partial ? p.partial + (size_t)blockIdx.y * p.M * p.N : nullptr;
+  float* P = p.partial ? p.partial + (size_t)slice * p.M * p.N : nullptr;
+  if (CS && do_cs) {                                      // lanes l and l + 32 hold the two k-groups of row l
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const float t = cs[i] + __shfl_xor(cs[i], 32);
+      const int m = m0 + wm * (BM / WM) + i * 32 + (lane & 31);
+      if (lane < 32 && m < p.M) reinterpret_cast<T*>(p.colsum)[m] = from_f<T>(t);
+    }
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -335,6 +376,52 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
   }
 }
 
+// XCD-aware block order: hardware deals block b to XCD b % 8; give each XCD a contiguous run of tile ids
+__device__ __forceinline__ int xcd_tile(int b, int nb) {
+  const int q = nb >> 3, r = nb & 7, x = b & 7;
+  return x * q + (x < r ? x : r) + (b >> 3);
+}
+
+template <typename T, int BM, int BN, int WM, int WN, int BK, int STAGES, bool ATR, bool BTR>
+__global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfma_kernel(MfmaGemmParams p) {
+  gemm_mfma_tile<T, BM, BN, WM, WN, BK, STAGES, ATR, BTR, false>(p, xcd_tile(blockIdx.x, p.tiles_total), blockIdx.y);
+}
+
+// Grouped weight gradients: one launch covers the tiles of up to GROUP_MAX independent products C_i = A_i^T B_i (each
+// with its own shapes and, optionally, the row sums of A_i^T as a bias gradient).  A single projection's weight gradient
+// has 16-256 tiles, too few to fill 256 compute units for more than a fraction of a round; the tiles of many of them
+// laid end to end do.  The table travels in the kernel arguments.
+constexpr int GROUP_MAX = 48;
+struct GroupedProblem {
+  const uint16_t* A; const uint16_t* B; uint16_t* C; uint16_t* colsum;
+  int M, N, K, lda, ldb, ldc, tile_begin, tiles_m, tiles_n;
+  uint32_t a_bytes, b_bytes;
+  int pad_;
+};
+struct GroupedTable {
+  int n, tiles_total;
+  GroupedProblem pr[GROUP_MAX];
+};
+static_assert(sizeof(GroupedTable) <= 4096, "kernel argument space");
+
+template <typename T, int BM, int BN, int WM, int WN, int BK, int STAGES>
+__global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfma_grouped_kernel(GroupedTable tab) {
+  const int tile = xcd_tile(blockIdx.x, tab.tiles_total);
+  int pi = 0;
+  for (int i = 1; i < tab.n; ++i) pi = tile >= tab.pr[i].tile_begin ? i : pi;
+  const GroupedProblem& g = tab.pr[pi];
+  MfmaGemmParams p;
+  p.M = g.M; p.N = g.N; p.K = g.K;
+  p.A = g.A; p.lda = g.lda; p.B = g.B; p.ldb = g.ldb; p.C = g.C; p.ldc = g.ldc;
+  p.bias = nullptr; p.relu = 0; p.mask = nullptr; p.residual = nullptr;
+  p.tiles_n = g.tiles_n; p.tiles_m = g.tiles_m; p.tiles_total = g.tiles_m * g.tiles_n; p.group_m = 8;
+  p.ksteps_per_split = (g.K + BK - 1) / BK;
+  p.partial = nullptr;
+  p.a_bytes = g.a_bytes; p.b_bytes = g.b_bytes;
+  p.colsum = g.colsum;
+  gemm_mfma_tile<T, BM, BN, WM, WN, BK, STAGES, true, true, true>(p, tile - g.tile_begin, 0);
+}
+
 // C[m, n] = epilogue(sum over splits (fixed order) of partial[s][m][n]); epilogue = optional bias[n], optional ReLU
 template <typename T>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits, int M, int N, T* __restrict__ C, int ldc,
@@ -392,6 +479,7 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   p.M = a.M; p.N = a.N; p.K = a.K;
   p.A = (const uint16_t*)a.A; p.lda = a.lda; p.B = (const uint16_t*)a.B; p.ldb = a.ldb; p.C = (uint16_t*)a.C; p.ldc = a.ldc;
   p.bias = (const uint16_t*)a.bias; p.relu = a.relu; p.mask = (const uint16_t*)a.mask; p.residual = (const uint16_t*)a.residual;
+  p.colsum = nullptr;
   p.tiles_n = (a.N + BN - 1) / BN;
   p.tiles_m = (a.M + BM - 1) / BM;
   p.tiles_total = p.tiles_n * p.tiles_m;
@@ -426,6 +514,54 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
     const size_t quads = ((size_t)a.M * a.N + 3) / 4;
     hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, (const float*)a.splitk_ws, splits,
                        a.M, a.N, (T*)a.C, a.ldc, (const T*)a.bias, a.relu);
+  }
+}
+
+// ---- grouped weight gradients ---------------------------------------------------------------------------------------------
+bool wgrad_group_supported(int dt, const WgradJob& j) {
+  GemmArgs a{dt, 2, j.M, j.N, j.K, j.A, j.lda, j.B, j.ldb, j.C, j.ldc, nullptr, 0, nullptr, nullptr};
+  if (!gemm_mfma_supported(a)) return false;
+  return j.colsum == nullptr || ((uintptr_t)j.colsum & 1) == 0;
+}
+
+template <typename T, int BM, int BN, int WM, int WN, int BK, int STAGES>
+static void wgrad_grouped_launch(hipStream_t s, const WgradJob* jobs, int n) {
+  GroupedTable tab;
+  int tiles = 0;
+  for (int i = 0; i < n; ++i) {
+    const WgradJob& j = jobs[i];
+    GroupedProblem& g = tab.pr[i];
+    g.A = (const uint16_t*)j.A; g.B = (const uint16_t*)j.B; g.C = (uint16_t*)j.C; g.colsum = (uint16_t*)j.colsum;
+    g.M = j.M; g.N = j.N; g.K = j.K; g.lda = j.lda; g.ldb = j.ldb; g.ldc = j.ldc;
+    g.tiles_m = (j.M + BM - 1) / BM; g.tiles_n = (j.N + BN - 1) / BN;
+    g.tile_begin = tiles;
+    tiles += g.tiles_m * g.tiles_n;
+    g.a_bytes = (uint32_t)extent_bytes(j.K, j.M, j.lda);
+    g.b_bytes = (uint32_t)extent_bytes(j.K, j.N, j.ldb);
+    g.pad_ = 0;
+  }
+  tab.n = n; tab.tiles_total = tiles;
+  hipLaunchKernelGGL((gemm_mfma_grouped_kernel<T, BM, BN, WM, WN, BK, STAGES>), dim3(tiles), dim3(64 * WM * WN), 0, s, tab);
+}
+
+// 256x256 tiles fetch half as many bytes per flop as 128x128 ones but come in coarser rounds over the 256 compute units:
+// compare the rounds each tiling needs, weighted by what a tile of each kind was measured to cost (103 vs 31 us at K = 3264).
+void launch_wgrad_grouped(hipStream_t s, int dt, const WgradJob* jobs, int n) {
+  if (n <= 0) return;
+  long t256 = 0, t128 = 0;
+  for (int i = 0; i < n; ++i) {
+    t256 += (long)((jobs[i].M + 255) / 256) * ((jobs[i].N + 255) / 256);
+    t128 += (long)((jobs[i].M + 127) / 128) * ((jobs[i].N + 127) / 128);
+  }
+  static const int forced = [] { const char* e = getenv("TFM_WGRAD_TILE"); return e ? atoi(e) : 0; }();
+  const double c256 = (double)((t256 + 255) / 256) * 103.0, c128 = (double)((t128 + 255) / 256) * 31.0;
+  const bool big = forced ? forced == 256 : c256 <= c128;
+  if (dt == F16) {
+    if (big) wgrad_grouped_launch<half_t, 256, 256, 2, 4, 64, 2>(s, jobs, n);
+    else wgrad_grouped_launch<half_t, 128, 128, 4, 4, 64, 3>(s, jobs, n);
+  } else {
+    if (big) wgrad_grouped_launch<bf16_t, 256, 256, 2, 4, 64, 2>(s, jobs, n);
+    else wgrad_grouped_launch<bf16_t, 128, 128, 4, 4, 64, 3>(s, jobs, n);
   }
 }
 

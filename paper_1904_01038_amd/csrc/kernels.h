@@ -48,6 +48,19 @@ bool gemm_mfma_supported(const GemmArgs& a);
 void launch_gemm_naive(hipStream_t s, const GemmArgs& a);
 void launch_gemm_mfma(hipStream_t s, const GemmArgs& a);      // requires gemm_mfma_supported(a)
 
+// Grouped weight gradients (half precision): one launch computes C_i[M_i, N_i] = A_i^T B_i over K_i rows for every job and,
+// where colsum is set, colsum_i[M_i] = the column sums of A_i (the bias gradient that goes with the weight gradient).
+struct WgradJob {
+  int M, N, K;
+  const void* A; int lda;                // [K, M]
+  const void* B; int ldb;                // [K, N]
+  void* C; int ldc;                      // [M, N]
+  void* colsum;                          // [M] or null
+};
+constexpr int WGRAD_GROUP_MAX = 48;      // jobs per launch
+bool wgrad_group_supported(int dt, const WgradJob& j);
+void launch_wgrad_grouped(hipStream_t s, int dt, const WgradJob* jobs, int n);   // n <= WGRAD_GROUP_MAX, every job supported
+
 struct AttnArgs {
   int dt;
   const void *q, *k, *v; int ldq, ldk, ldv;

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -41,6 +42,11 @@ struct Block {
   void* kv;                // cross: [R,2d] over source rows
   void* ctx;               // attention output [R,d]
   float* lse;              // [H,R]
+  // Backward: the gradients the block's weight gradients are formed from.  Each block keeps its own, so the weight
+  // gradients of many blocks can be deferred and computed together (see flush_wgrads).
+  void* dy;                // [R,d]: gradient w.r.t. the sub-layer output (after dropout-backward)
+  void* dint;              // gradient w.r.t. inter: [R,3d] | [R,d] | [R,F]
+  void* dkv;               // cross: [R,2d] over source rows
 };
 
 struct Stream {
@@ -101,7 +107,12 @@ struct tfm_ctx {
   bool overlap;
   std::vector<hipEvent_t> sync_ev;                  // ordering events, handed out in sequence within a step
   size_t sync_used;
-  hipEvent_t side_s1, side_blk;                     // side-stream marks of the block just enqueued (null: none)
+  // Deferred weight gradients: queued while the chain of input gradients runs, launched as grouped GEMMs (one launch
+  // for the tiles of many projections) on the side stream.
+  std::vector<WgradJob> wq;
+  std::vector<double> wq_flops;
+  long wq_tiles;
+  long wq_flush_tiles;                              // flush once this many 128x128 tiles are queued
   hipEvent_t kv_ready;                              // side-stream mark after the cross-attention K/V projections (null: none)
   bool kv_done;                                     // they were projected ahead and the main stream already waited
   // The Adam step also runs on the side stream, cut into chunks in the order the forward pass first touches the
@@ -125,7 +136,7 @@ struct tfm_ctx {
   int R;                   // row capacity
   // scratch
   void *demb[2];           // gradient w.r.t. the embedding output of the encoder / decoder stream
-  void *y, *dcur, *dsA, *dsB, *dy, *dctx, *dinter, *dq, *dkv, *dmemA, *dmemB, *logits;
+  void *y, *dcur, *dsA, *dsB, *dctx, *dmemA, *dmemB, *logits;
   float *loss_rows, *nll_rows, *pe;
   void *red_scratch, *scan_scratch, *splitk_ws;
   void *red_scratch_side, *splitk_ws_side;          // the side stream's own reduction scratch
@@ -310,9 +321,12 @@ size_t carve(tfm_ctx* c, char* base) {
       s->rstd[k] = (float*)a.take(R * 4);
     }
     for (Block& b : s->blocks) {
-      if (b.kind == SELF) { b.inter = a.take(R * 3 * d * esz); b.ctx = a.take(R * d * esz); b.lse = (float*)a.take(H * R * 4); }
-      else if (b.kind == CROSS) { b.inter = a.take(R * d * esz); b.kv = a.take(R * 2 * d * esz); b.ctx = a.take(R * d * esz); b.lse = (float*)a.take(H * R * 4); }
-      else { b.inter = a.take(R * F * esz); }
+      if (b.kind == SELF) { b.inter = a.take(R * 3 * d * esz); b.ctx = a.take(R * d * esz); b.lse = (float*)a.take(H * R * 4); b.dint = a.take(R * 3 * d * esz); }
+      else if (b.kind == CROSS) {
+        b.inter = a.take(R * d * esz); b.kv = a.take(R * 2 * d * esz); b.ctx = a.take(R * d * esz); b.lse = (float*)a.take(H * R * 4);
+        b.dint = a.take(R * d * esz); b.dkv = a.take(R * 2 * d * esz);
+      } else { b.inter = a.take(R * F * esz); b.dint = a.take(R * F * esz); }
+      b.dy = a.take(R * d * esz);
     }
   }
   const size_t wide = std::max(3 * d, F);
@@ -322,11 +336,7 @@ size_t carve(tfm_ctx* c, char* base) {
   c->demb[1] = a.take(R * d * esz);
   c->dsA = a.take(R * d * esz);
   c->dsB = a.take(R * d * esz);
-  c->dy = a.take(R * d * esz);
   c->dctx = a.take(R * d * esz);
-  c->dinter = a.take(R * wide * esz);
-  c->dq = a.take(R * d * esz);
-  c->dkv = a.take(R * 2 * d * esz);
   c->dmemA = a.take(R * d * esz);
   c->dmemB = a.take(R * d * esz);
   {
@@ -425,7 +435,7 @@ inline void order(tfm_ctx* c, hipStream_t from, hipStream_t to) { hipStreamWaitE
 inline hipStream_t wstream(tfm_ctx* c) { return c->overlap ? c->side : c->stream; }
 // main -> side: the operands of the weight-gradient work enqueued next are ready
 inline void side_begin(tfm_ctx* c) { if (c->overlap) order(c, c->stream, c->side); }
-// main waits for a side mark (before it overwrites what that side work reads)
+// main waits for a side mark
 inline void main_wait(tfm_ctx* c, hipEvent_t& e) {
   if (c->overlap && e) hipStreamWaitEvent(c->stream, e, 0);
   e = nullptr;
@@ -472,9 +482,42 @@ void gemm(tfm_ctx* c, int form, int M, int N, int K, const void* A, int lda, con
   const double bytes = (double)c->esz * ((double)M * K + (double)K * N + (double)M * N * (1.0 + (mask ? 1.0 : 0.0) + (residual ? 1.0 : 0.0)));
   run(c, TFM_PROF_GEMM, 2.0 * M * N * K, bytes, [&] { launch_gemm(stream, a); }, stream);
 }
-// weight gradient dW[M,N] = A^T B over K rows, on the side stream
-inline void wgrad(tfm_ctx* c, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C, int ldc) {
+// Launches the queued weight gradients as one grouped GEMM on the side stream (after everything enqueued on the main
+// stream so far, which produced their operands).
+void flush_wgrads(tfm_ctx* c) {
+  if (c->wq.empty()) return;
+  hipStream_t stream = wstream(c);
+  side_begin(c);
+  double flops = 0, bytes = 0;
+  for (size_t i = 0; i < c->wq.size(); ++i) {
+    const WgradJob& j = c->wq[i];
+    flops += 2.0 * j.M * j.N * j.K;
+    bytes += (double)c->esz * ((double)j.M * j.K + (double)j.K * j.N + (double)j.M * j.N);
+  }
+  run(c, TFM_PROF_GEMM, flops, bytes, [&] { launch_wgrad_grouped(stream, c->dt, c->wq.data(), (int)c->wq.size()); }, stream);
+  c->wq.clear();
+  c->wq_tiles = 0;
+}
+
+// Weight gradient dW[M,N] = A^T B over K rows and, if bias_grad is given, the bias gradient [M] = column sums of A.
+// A and B must stay untouched until the end of the backward pass: the product is queued, not launched.  Shapes the
+// grouped matrix-core kernel does not take (fp32 mode, widths that are not multiples of 8) run at once on the side stream.
+void wgrad(tfm_ctx* c, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C, int ldc, void* bias_grad = nullptr) {
+  if (M <= 0 || N <= 0) return;
+  WgradJob j{M, N, K, A, lda, B, ldb, C, ldc, bias_grad};
+  if (c->dt != F32 && K > 0 && wgrad_group_supported(c->dt, j)) {
+    c->wq.push_back(j);
+    c->wq_tiles += (long)((M + 127) / 128) * ((N + 127) / 128);
+    if ((int)c->wq.size() == WGRAD_GROUP_MAX || c->wq_tiles >= c->wq_flush_tiles) flush_wgrads(c);
+    return;
+  }
+  side_begin(c);
   gemm(c, 2, M, N, K, A, lda, B, ldb, C, ldc, nullptr, 0, nullptr, nullptr, true);
+  if (bias_grad) {
+    hipStream_t stream = wstream(c);
+    void* scratch = c->overlap ? c->red_scratch_side : c->red_scratch;
+    run(c, TFM_PROF_NORM, 0.0, (double)c->esz * K * M, [&] { launch_colsum(stream, c->dt, A, lda, K, M, bias_grad, scratch); }, stream);
+  }
 }
 
 double attn_flops(const std::vector<int>& lq, const std::vector<int>& lk, int d, bool causal) {
@@ -529,6 +572,12 @@ int tfm_create(const tfm_config* cfg, void* ws, size_t bytes, void* hip_stream, 
     return cleanup(TFM_EHIP);
   }
   c->overlap = true;
+  c->wq_tiles = 0;
+  {
+    // (tuning aid: TFM_WGRAD_FLUSH=<128x128 tiles> flushes the weight-gradient queue whenever that many tiles wait)
+    const char* e = getenv("TFM_WGRAD_FLUSH");
+    c->wq_flush_tiles = e && atol(e) > 0 ? atol(e) : 4096;
+  }
   {
     // chunk boundaries: the embedding, then one chunk per block (its parameters are contiguous), final norms with
     // the block before them
@@ -839,69 +888,44 @@ void stream_fwd(const StepCtx& s, Stream& st) {
   }
 }
 
-// bias gradient, on the side stream
-void colsum(tfm_ctx* c, const void* x, int ld, int rows, int n, void* out) {
-  hipStream_t stream = wstream(c);
-  void* scratch = c->overlap ? c->red_scratch_side : c->red_scratch;
-  run(c, TFM_PROF_NORM, 0.0, (double)c->esz * rows * n, [&] { launch_colsum(stream, c->dt, x, ld, rows, n, out, scratch); }, stream);
-}
-
-// backward of sub-layer k given dy; writes the gradient w.r.t. its input (plus `residual` if given) to dout
+// backward of sub-layer k given dy (which lives in the block's own b.dy); writes the gradient w.r.t. its input (plus
+// `residual` if given) to dout.  Weight and bias gradients are queued (see wgrad).
 void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const void* fin, const void* residual, void* dout,
                   void** dmem_cur, void** dmem_other, bool* dmem_valid) {
   tfm_ctx* c = s.c;
   Block& b = st.blocks[k];
   const int d = c->cfg.d_model, F = c->cfg.d_ffn, T = st.rows;
   const std::vector<int>& len = st.id ? s.tlen : s.slen;
-  // Side stream, part 1: the output projection's weight gradient needs only dy.  Part 2: the input projection's
-  // weight and bias gradients need the gradient this block writes into dinter / dq / dkv.  The main stream waits for
-  // part 2 of the PREVIOUS block right before it overwrites those buffers, and for part 1 of this block before the
-  // next LayerNorm backward overwrites dy (see stream_bwd).
-  side_begin(c);
   if (b.kind == SELF) {
     wgrad(c, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d);
-    if (c->overlap) c->side_s1 = mark(c, c->side);
     gemm(c, 1, T, d, d, dy, d, wh(c, b.w_o), d, c->dctx, d);
     const char* qkv = (const char*)b.inter;
-    char* dqkv = (char*)c->dinter;
-    main_wait(c, c->side_blk);
+    char* dqkv = (char*)b.dint;
     attention(s, true, st, st, len, len, qkv, 3 * d, qkv + d * c->esz, 3 * d, qkv + 2 * d * c->esz, 3 * d, b.ctx, b.lse, st.id == 1,
               c->dctx, dqkv, 3 * d, dqkv + d * c->esz, 3 * d, dqkv + 2 * d * c->esz, 3 * d);
-    side_begin(c);
-    wgrad(c, 3 * d, d, T, dqkv, 3 * d, fin, d, gr(c, b.w_a), d);
-    colsum(c, dqkv, 3 * d, T, 3 * d, gr(c, b.b_a));
     gemm(c, 1, T, d, 3 * d, dqkv, 3 * d, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
+    wgrad(c, 3 * d, d, T, dqkv, 3 * d, fin, d, gr(c, b.w_a), d, gr(c, b.b_a));
   } else if (b.kind == CROSS) {
     Stream& en = c->enc;
     const void* mem = en.norm[en.blocks.size()];
     wgrad(c, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d);
-    if (c->overlap) c->side_s1 = mark(c, c->side);
     gemm(c, 1, T, d, d, dy, d, wh(c, b.w_o), d, c->dctx, d);
     const char* kv = (const char*)b.kv;
-    char* dkv = (char*)c->dkv;
-    main_wait(c, c->side_blk);
+    char* dkv = (char*)b.dkv;
     attention(s, true, st, en, s.tlen, s.slen, b.inter, d, kv, 2 * d, kv + d * c->esz, 2 * d, b.ctx, b.lse, false, c->dctx,
-              c->dq, d, dkv, 2 * d, dkv + d * c->esz, 2 * d);
-    side_begin(c);
-    wgrad(c, d, d, T, c->dq, d, fin, d, gr(c, b.w_a), d);
-    colsum(c, c->dq, d, T, d, gr(c, b.b_a));
-    wgrad(c, 2 * d, d, en.rows, dkv, 2 * d, mem, d, gr(c, b.w_kv), d);
-    colsum(c, dkv, 2 * d, en.rows, 2 * d, gr(c, b.b_kv));
-    gemm(c, 1, T, d, d, c->dq, d, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
+              b.dint, d, dkv, 2 * d, dkv + d * c->esz, 2 * d);
+    gemm(c, 1, T, d, d, b.dint, d, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
     gemm(c, 1, en.rows, d, 2 * d, dkv, 2 * d, wh(c, b.w_kv), d, *dmem_other, d, nullptr, 0, nullptr, *dmem_valid ? *dmem_cur : nullptr);
     std::swap(*dmem_cur, *dmem_other);
     *dmem_valid = true;
+    wgrad(c, d, d, T, b.dint, d, fin, d, gr(c, b.w_a), d, gr(c, b.b_a));
+    wgrad(c, 2 * d, d, en.rows, dkv, 2 * d, mem, d, gr(c, b.w_kv), d, gr(c, b.b_kv));
   } else {
     wgrad(c, d, F, T, dy, d, b.inter, F, gr(c, b.w_o), F);
-    if (c->overlap) c->side_s1 = mark(c, c->side);
-    main_wait(c, c->side_blk);
-    gemm(c, 1, T, F, d, dy, d, wh(c, b.w_o), F, c->dinter, F, nullptr, 0, b.inter, nullptr);
-    side_begin(c);
-    wgrad(c, F, d, T, c->dinter, F, fin, d, gr(c, b.w_a), d);
-    colsum(c, c->dinter, F, T, F, gr(c, b.b_a));
-    gemm(c, 1, T, d, F, c->dinter, F, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
+    gemm(c, 1, T, F, d, dy, d, wh(c, b.w_o), F, b.dint, F, nullptr, 0, b.inter, nullptr);
+    gemm(c, 1, T, d, F, b.dint, F, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
+    wgrad(c, F, d, T, b.dint, F, fin, d, gr(c, b.w_a), d, gr(c, b.b_a));
   }
-  if (c->overlap) c->side_blk = mark(c, c->side);
 }
 
 void ln_bwd(tfm_ctx* c, const void* dn, const void* add, const void* sres, const float* mean, const float* rstd, int g, int b,
@@ -928,33 +952,33 @@ void* stream_bwd(const StepCtx& s, Stream& st, void** dmem_cur, void** dmem_othe
   if (!pre) {
     for (int k = K - 1; k >= 0; --k) {
       Block& b = st.blocks[k];
-      main_wait(c, c->side_s1);                // the previous block's first weight gradient still reads dy / dsA
-      ln_bwd(c, dn, nullptr, st.resid[k + 1], st.mean[k + 1], st.rstd[k + 1], b.ln_g, b.ln_b, c->dsA, c->dy, b.b_o, T, block_key(s, st, k));
-      const void* dy = drop ? c->dy : c->dsA;
+      // with dropout the kernel writes both the residual branch's gradient (dsA) and the sub-layer's (b.dy); without, they
+      // are the same tensor
+      void* ds = drop ? c->dsA : b.dy;
+      ln_bwd(c, dn, nullptr, st.resid[k + 1], st.mean[k + 1], st.rstd[k + 1], b.ln_g, b.ln_b, ds, b.dy, b.b_o, T, block_key(s, st, k));
       void* out = k == 0 ? c->demb[st.id] : c->dcur;
-      sublayer_bwd(s, st, k, dy, st.norm[k], c->dsA, out, dmem_cur, dmem_other, dmem_valid);
+      sublayer_bwd(s, st, k, b.dy, st.norm[k], ds, out, dmem_cur, dmem_other, dmem_valid);
       dn = out;
     }
     return dn;
   }
-  // pre-norm: the residual stream's gradient ping-pongs between dsA and dsB
+  // pre-norm: the residual stream's gradient ping-pongs between dsA and dsB; without dropout it IS the gradient of the
+  // sub-layer below and is written straight into that block's own buffer
   void* dR = nullptr;
-  void* ds = c->dsA;
-  void* ds_alt = c->dsB;
+  void* pp = c->dsA;
+  void* pp_alt = c->dsB;
   for (int idx = K; idx >= 0; --idx) {
     const int g = idx < K ? st.blocks[idx].ln_g : st.lnf_g;
     const int b = idx < K ? st.blocks[idx].ln_b : st.lnf_b;
     const int bias = idx >= 1 ? st.blocks[idx - 1].b_o : -1;
-    if (idx == 0) ds = c->demb[st.id];
-    main_wait(c, c->side_s1);
-    ln_bwd(c, dn, dR, st.resid[idx], st.mean[idx], st.rstd[idx], g, b, ds, idx >= 1 ? c->dy : nullptr, bias, T,
-           idx >= 1 ? block_key(s, st, idx - 1) : 0);
+    void* bdy = idx >= 1 ? st.blocks[idx - 1].dy : nullptr;
+    void* ds = idx == 0 ? c->demb[st.id] : (drop ? pp : bdy);
+    ln_bwd(c, dn, dR, st.resid[idx], st.mean[idx], st.rstd[idx], g, b, ds, bdy, bias, T, idx >= 1 ? block_key(s, st, idx - 1) : 0);
     if (idx == 0) return ds;
-    const void* dy = drop ? c->dy : ds;
-    sublayer_bwd(s, st, idx - 1, dy, st.norm[idx - 1], nullptr, c->dcur, dmem_cur, dmem_other, dmem_valid);
+    sublayer_bwd(s, st, idx - 1, bdy, st.norm[idx - 1], nullptr, c->dcur, dmem_cur, dmem_other, dmem_valid);
     dn = c->dcur;
     dR = ds;
-    std::swap(ds, ds_alt);
+    std::swap(pp, pp_alt);
   }
   return nullptr;
 }
@@ -1188,7 +1212,8 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
 
   // ---- forward
   c->sync_used = 0;
-  c->side_s1 = c->side_blk = nullptr;
+  c->wq.clear();
+  c->wq_tiles = 0;
   c->kv_ready = nullptr;
   c->kv_done = false;
   if (has_enc) {
@@ -1220,7 +1245,6 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   });
 
   // ---- backward
-  side_begin(c);
   wgrad(c, V0, d, (int)Tt, c->logits, V0, top, d, c->g, d);                // embedding gradient, output side
   gemm(c, 1, (int)Tt, d, V0, c->logits, V0, c->Wh, d, c->dcur, d);
   if (ad.n) adaptive_tails(s, top, mult);          // tail clusters: their losses, gradients, and their share of dcur
@@ -1229,10 +1253,11 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   void* dmem_other = c->dmemB;
   bool dmem_valid = false;
   void* ddec = stream_bwd(s, de, &dmem_cur, &dmem_other, &dmem_valid, c->dcur);
+  flush_wgrads(c);                                 // the decoder's weight gradients run beside the encoder's backward pass
   void* denc = nullptr;
   if (has_enc) denc = stream_bwd(s, c->enc, &dmem_cur, &dmem_other, &dmem_valid, dmem_cur);
+  flush_wgrads(c);
   if (c->overlap) order(c, c->side, c->stream);                            // join: every weight gradient is in g
-  c->side_s1 = c->side_blk = nullptr;
   if (ad.n) adaptive_embed_bwd(s, ddec);
   run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * d * ((double)Ts + Tt + 2.0 * nu), [&] {
     EmbedBwdArgs ea{};
@@ -1609,6 +1634,22 @@ int tfm_op_gemm_ws(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K,
   a.splitk_ws = workspace;
   a.splitk_ws_bytes = workspace ? workspace_bytes : 0;
   launch_gemm((hipStream_t)stream, a);
+  return op_done();
+}
+
+int tfm_op_wgrad_grouped(int32_t dtype, int32_t n, const int32_t* dims, const void* const* A, const void* const* B, void* const* C,
+                         void* const* colsum, void* stream) {
+  if ((dtype != TFM_FP16 && dtype != TFM_BF16) || n < 0 || n > WGRAD_GROUP_MAX || (n && (!dims || !A || !B || !C))) return TFM_EINVAL;
+  WgradJob jobs[WGRAD_GROUP_MAX];
+  for (int i = 0; i < n; ++i) {
+    const int32_t* q = dims + 6 * i;
+    WgradJob& j = jobs[i];
+    j.M = q[0]; j.N = q[1]; j.K = q[2]; j.lda = q[3]; j.ldb = q[4]; j.ldc = q[5];
+    j.A = A[i]; j.B = B[i]; j.C = C[i]; j.colsum = colsum ? colsum[i] : nullptr;
+    if (j.M <= 0 || j.N <= 0 || j.K <= 0 || !j.A || !j.B || !j.C || j.lda < j.M || j.ldb < j.N || j.ldc < j.N) return TFM_EINVAL;
+    if (!wgrad_group_supported(dtype, j)) return TFM_EINVAL;
+  }
+  launch_wgrad_grouped((hipStream_t)stream, dtype, jobs, n);
   return op_done();
 }
 

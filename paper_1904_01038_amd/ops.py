@@ -37,6 +37,17 @@ def gemm(form, A, B, C_out, M, N, K, lda=None, ldb=None, ldc=None, bias=None, re
                              _p(mask), _p(residual), _stream()), "tfm_op_gemm")
 
 
+def wgrad_grouped(jobs):
+    """jobs: list of (A[K, M], B[K, N], C[M, N], colsum[M] or None); C_i = A_i^T B_i and colsum_i = column sums of A_i, one launch."""
+    n = len(jobs)
+    dims = (C.c_int32 * (6 * n))()
+    pa, pb, pc, ps = ((C.c_void_p * n)() for _ in range(4))
+    for i, (A, B, Cm, cs) in enumerate(jobs):
+        dims[6 * i:6 * i + 6] = [A.shape[1], B.shape[1], A.shape[0], A.stride(0), B.stride(0), Cm.stride(0)]
+        pa[i], pb[i], pc[i], ps[i] = A.data_ptr(), B.data_ptr(), Cm.data_ptr(), (cs.data_ptr() if cs is not None else None)
+    _check(lib().tfm_op_wgrad_grouped(_dt(jobs[0][0]) if n else FP16, n, dims, pa, pb, pc, ps, _stream()), "tfm_op_wgrad_grouped")
+
+
 def attention_fwd(q, k, v, o, lse, q_off, k_off, H, dh, max_lq, max_lk, causal):
     B = q_off.numel() - 1
     _check(lib().tfm_op_attention_fwd(_dt(q), _p(q), q.stride(0), _p(k), k.stride(0), _p(v), v.stride(0), _p(o),

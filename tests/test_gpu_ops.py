@@ -93,6 +93,44 @@ def test_gemm_split_k_weight_gradient_is_exact_and_reproducible(prec, shape):
 
 
 @pytest.mark.parametrize("prec", ["fp16", "bf16"])
+@pytest.mark.parametrize("tile", ["small", "large"])
+def test_grouped_weight_gradients_with_bias_sums_are_exact(prec, tile):
+    """Several A^T B products of different shapes plus the column sums of A in one launch, against the float64 definitions.
+    Small integers make every product and sum exact.  "large" has enough tiles for the 256x256 configuration."""
+    import torch
+    import paper_1904_01038_amd as T
+    dt = _dtypes()[prec]
+    rng = np.random.default_rng(11)
+    if tile == "small":
+        shapes = [(136, 264, 300, True), (8, 8, 8, True), (384, 128, 1032, False), (200, 72, 77, True), (128, 512, 64, True)]
+    else:   # M, N, K, with column sums
+        shapes = [(1024, 1024, 520, True), (3072, 1024, 300, True), (1024, 4096, 264, False), (520, 264, 1000, True), (4096, 1024, 136, True)]
+    jobs, refs = [], []
+    for M, N, K, with_sum in shapes:
+        A = rng.integers(-2, 3, (K, M)).astype(np.float64)
+        B = rng.integers(-2, 3, (K, N)).astype(np.float64)
+        ld = M + 24                                                 # a strided view, as the fused QKV gradient is
+        tA = torch.zeros(K, ld, dtype=dt, device="cuda")
+        tA[:, :M] = _t(A, dt)
+        out = torch.full((M, N), 7.0, dtype=dt, device="cuda")
+        cs = torch.full((M,), 7.0, dtype=dt, device="cuda") if with_sum else None
+        jobs.append((tA[:, :M], _t(B, dt), out, cs))
+        refs.append((A.T @ B, A.sum(axis=0)))
+        assert np.abs(refs[-1][0]).max() < 2048 and np.abs(refs[-1][1]).max() < 256
+    for _ in range(2):                                              # twice: the same bits
+        T.ops.wgrad_grouped(jobs)
+        for (tA, tB, out, cs), (rc, rs) in zip(jobs, refs):
+            got = out.float().cpu().numpy().astype(np.float64)
+            want = _t(rc, dt).float().cpu().numpy().astype(np.float64)
+            assert np.array_equal(got, want), np.abs(got - want).max()
+            if cs is not None:
+                assert np.array_equal(cs.float().cpu().numpy().astype(np.float64), rs)
+    with pytest.raises(T.TfmError):                                 # a width that is not a multiple of 8 is refused, nothing runs
+        bad = torch.zeros(16, 12, dtype=dt, device="cuda")
+        T.ops.wgrad_grouped([(bad, bad, torch.zeros(12, 12, dtype=dt, device="cuda"), None)])
+
+
+@pytest.mark.parametrize("prec", ["fp16", "bf16"])
 @pytest.mark.parametrize("shape,bias,relu", [((280, 1024, 1024), True, False), ((192, 1024, 4096), True, True), ((72, 512, 640), False, False),
                                              ((320, 3072, 1024), True, False)])
 def test_gemm_few_rows_split_k_with_bias_and_relu_is_exact(prec, shape, bias, relu):
