@@ -84,9 +84,16 @@ void launch_residual_layernorm_fwd(hipStream_t s, int dt, const void* x, const v
                                    const void* beta, void* s_out, void* n_out, float* mean, float* rstd, int rows,
                                    int d, uint64_t key, float p);
 size_t layernorm_bwd_scratch_bytes(int rows, int d);
+// The backward kernel leaves per-block partial column sums in `scratch`; a second, tiny kernel adds them in a fixed order
+// into dgamma / dbeta / dbias (dbias may be null: then it is not formed).  With `defer` set that second kernel is NOT
+// launched: the job is described there instead, scratch must stay untouched until launch_ln_reduce_batched has run it,
+// and many such jobs go into one launch.
+struct LnReduceJob { const float* partial; int np; int slots; void *dgamma, *dbeta, *dbias; };
+constexpr int LN_REDUCE_MAX = 64;        // jobs per launch (more are split over several)
 void launch_layernorm_bwd(hipStream_t s, int dt, const void* dn, const void* add, const void* sres, const float* mean,
                           const float* rstd, const void* gamma, void* ds, void* ds_drop, void* dgamma, void* dbeta,
-                          void* dbias, int rows, int d, uint64_t key, float p, void* scratch);
+                          void* dbias, int rows, int d, uint64_t key, float p, void* scratch, LnReduceJob* defer = nullptr);
+void launch_ln_reduce_batched(hipStream_t s, int dt, const LnReduceJob* jobs, int n, int d);
 size_t colsum_scratch_bytes(int rows, int n);
 void launch_colsum(hipStream_t s, int dt, const void* x, int ld, int rows, int n, void* out, void* scratch);
 

@@ -105,7 +105,7 @@ template <typename T, int NCH>
 __global__ __launch_bounds__(64 * LNB_WAVES) void layernorm_bwd_kernel(
     const T* __restrict__ dn, const T* __restrict__ add, const T* __restrict__ sres, const float* __restrict__ mean,
     const float* __restrict__ rstd, const T* __restrict__ gamma, T* __restrict__ ds, T* __restrict__ ds_drop,
-    float* __restrict__ partial, int rows, int d, uint64_t key, uint32_t thr, float inv_keep) {
+    float* __restrict__ partial, int rows, int d, uint64_t key, uint32_t thr, float inv_keep, int nk) {
   extern __shared__ float lds[];     // [LNB_WAVES][d]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   float g[NCH][LN_VEC], ag[NCH][LN_VEC], ab[NCH][LN_VEC], ac[NCH][LN_VEC];
@@ -179,8 +179,7 @@ __global__ __launch_bounds__(64 * LNB_WAVES) void layernorm_bwd_kernel(
       }
     }
   }
-#pragma unroll
-  for (int k = 0; k < 3; ++k) {
+  for (int k = 0; k < nk; ++k) {                        // nk = 2: the bias sum is not wanted
     __syncthreads();
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
@@ -215,7 +214,7 @@ template <typename T, int NCH>
 __global__ __launch_bounds__(64 * LNR_WAVES) void layernorm_bwd_row_kernel(
     const T* __restrict__ dn, const T* __restrict__ add, const T* __restrict__ sres, const float* __restrict__ mean,
     const float* __restrict__ rstd, const T* __restrict__ gamma, T* __restrict__ ds, T* __restrict__ ds_drop,
-    float* __restrict__ partial, int rows, int d, uint64_t key, uint32_t thr, float inv_keep) {
+    float* __restrict__ partial, int rows, int d, uint64_t key, uint32_t thr, float inv_keep, int nk) {
   extern __shared__ float lds[];     // [LNR_WAVES][d]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int row = blockIdx.x * LNR_WAVES + w;
@@ -270,8 +269,7 @@ __global__ __launch_bounds__(64 * LNR_WAVES) void layernorm_bwd_row_kernel(
       }
     }
   }
-#pragma unroll
-  for (int k = 0; k < 3; ++k) {
+  for (int k = 0; k < nk; ++k) {                        // nk = 2: the bias sum is not wanted
     __syncthreads();
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
@@ -297,8 +295,7 @@ __global__ __launch_bounds__(64 * LNR_WAVES) void layernorm_bwd_row_kernel(
 // partials), then LDS combines the 32 lanes in a fixed order.
 constexpr int RP_LANES = 32;
 template <typename T>
-__global__ __launch_bounds__(32 * RP_LANES) void reduce_partials_kernel(const float* __restrict__ partial, int np, int nk, int n, T* o0,
-                                                                        T* o1, T* o2, int slots) {
+__device__ __forceinline__ void reduce_partials_body(const float* __restrict__ partial, int np, int nk, int n, T* o0, T* o1, T* o2, int slots) {
   __shared__ float sh[RP_LANES][33];
   const int cx = threadIdx.x & 31, py = threadIdx.x >> 5;
   const int k = blockIdx.y;
@@ -327,6 +324,19 @@ __global__ __launch_bounds__(32 * RP_LANES) void reduce_partials_kernel(const fl
     }
   }
 }
+template <typename T>
+__global__ __launch_bounds__(32 * RP_LANES) void reduce_partials_kernel(const float* __restrict__ partial, int np, int nk, int n, T* o0,
+                                                                        T* o1, T* o2, int slots) {
+  reduce_partials_body<T>(partial, np, nk, n, o0, o1, o2, slots);
+}
+// The reductions of many LayerNorm backward launches in one: blockIdx.z picks the job (the table travels in the kernel
+// arguments).  Every job has the [np][3][d] layout; an output that is null is skipped.
+struct LnReduceTable { LnReduceJob job[LN_REDUCE_MAX]; };
+template <typename T>
+__global__ __launch_bounds__(32 * RP_LANES) void reduce_partials_batched_kernel(LnReduceTable tab, int d) {
+  const LnReduceJob& j = tab.job[blockIdx.z];
+  reduce_partials_body<T>(j.partial, j.np, 3, d, (T*)j.dgamma, (T*)j.dbeta, (T*)j.dbias, j.slots);
+}
 
 static int lnb_blocks(int rows) {
   int b = (rows + LNB_WAVES - 1) / LNB_WAVES;
@@ -337,7 +347,8 @@ size_t layernorm_bwd_scratch_bytes(int rows, int d) { return (size_t)lnb_blocks(
 template <typename T>
 static void ln_bwd_dispatch(hipStream_t s, const void* dn, const void* add, const void* sres, const float* mean,
                             const float* rstd, const void* gamma, void* ds, void* ds_drop, void* dgamma, void* dbeta,
-                            void* dbias, int rows, int d, uint64_t key, float p, void* scratch) {
+                            void* dbias, int rows, int d, uint64_t key, float p, void* scratch, LnReduceJob* defer) {
+  const int nk = dbias ? 3 : 2;
   const uint32_t thr = (p > 0.f && ds_drop) ? drop_threshold(p) : 0u;
   const float inv_keep = 1.f / (1.f - p);
   const int nch = (d + 511) / 512;
@@ -347,9 +358,10 @@ static void ln_bwd_dispatch(hipStream_t s, const void* dn, const void* add, cons
 #define LN_BWD_ROW(N)                                                                                                   \
   hipLaunchKernelGGL((layernorm_bwd_row_kernel<T, N>), dim3(nbr), dim3(64 * LNR_WAVES), shr, s, (const T*)dn, (const T*)add,        \
                      (const T*)sres, mean, rstd, (const T*)gamma, (T*)ds, (T*)ds_drop, (float*)scratch, rows, d, key, thr, \
-                     inv_keep)
+                     inv_keep, nk)
     if (nch <= 1) LN_BWD_ROW(1); else LN_BWD_ROW(2);
 #undef LN_BWD_ROW
+    if (defer) { *defer = LnReduceJob{(const float*)scratch, nbr, 1, dgamma, dbeta, dbias}; return; }
     hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((d + 31) / 32, 3), dim3(32 * RP_LANES), 0, s, (const float*)scratch, nbr, 3, d,
                        (T*)dgamma, (T*)dbeta, (T*)dbias, 1);
     return;
@@ -359,19 +371,32 @@ static void ln_bwd_dispatch(hipStream_t s, const void* dn, const void* add, cons
 #define LN_BWD(N)                                                                                                       \
   hipLaunchKernelGGL((layernorm_bwd_kernel<T, N>), dim3(nb), dim3(64 * LNB_WAVES), shm, s, (const T*)dn, (const T*)add,             \
                      (const T*)sres, mean, rstd, (const T*)gamma, (T*)ds, (T*)ds_drop, (float*)scratch, rows, d, key, thr, \
-                     inv_keep)
+                     inv_keep, nk)
   if (nch <= 1) LN_BWD(1); else if (nch == 2) LN_BWD(2); else if (nch == 3) LN_BWD(3); else LN_BWD(4);
 #undef LN_BWD
+  if (defer) { *defer = LnReduceJob{(const float*)scratch, nb, 0, dgamma, dbeta, dbias}; return; }
   hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((d + 31) / 32, 3), dim3(32 * RP_LANES), 0, s, (const float*)scratch, nb, 3, d,
                      (T*)dgamma, (T*)dbeta, (T*)dbias, 0);
 }
 
 void launch_layernorm_bwd(hipStream_t s, int dt, const void* dn, const void* add, const void* sres, const float* mean,
                           const float* rstd, const void* gamma, void* ds, void* ds_drop, void* dgamma, void* dbeta,
-                          void* dbias, int rows, int d, uint64_t key, float p, void* scratch) {
-  if (dt == F32) ln_bwd_dispatch<float>(s, dn, add, sres, mean, rstd, gamma, ds, ds_drop, dgamma, dbeta, dbias, rows, d, key, p, scratch);
-  else if (dt == F16) ln_bwd_dispatch<half_t>(s, dn, add, sres, mean, rstd, gamma, ds, ds_drop, dgamma, dbeta, dbias, rows, d, key, p, scratch);
-  else ln_bwd_dispatch<bf16_t>(s, dn, add, sres, mean, rstd, gamma, ds, ds_drop, dgamma, dbeta, dbias, rows, d, key, p, scratch);
+                          void* dbias, int rows, int d, uint64_t key, float p, void* scratch, LnReduceJob* defer) {
+  if (dt == F32) ln_bwd_dispatch<float>(s, dn, add, sres, mean, rstd, gamma, ds, ds_drop, dgamma, dbeta, dbias, rows, d, key, p, scratch, defer);
+  else if (dt == F16) ln_bwd_dispatch<half_t>(s, dn, add, sres, mean, rstd, gamma, ds, ds_drop, dgamma, dbeta, dbias, rows, d, key, p, scratch, defer);
+  else ln_bwd_dispatch<bf16_t>(s, dn, add, sres, mean, rstd, gamma, ds, ds_drop, dgamma, dbeta, dbias, rows, d, key, p, scratch, defer);
+}
+
+void launch_ln_reduce_batched(hipStream_t s, int dt, const LnReduceJob* jobs, int n, int d) {
+  for (int i0 = 0; i0 < n; i0 += LN_REDUCE_MAX) {
+    const int m = n - i0 < LN_REDUCE_MAX ? n - i0 : LN_REDUCE_MAX;
+    LnReduceTable tab;
+    for (int i = 0; i < m; ++i) tab.job[i] = jobs[i0 + i];
+    const dim3 grid((d + 31) / 32, 3, m), block(32 * RP_LANES);
+    if (dt == F32) hipLaunchKernelGGL((reduce_partials_batched_kernel<float>), grid, block, 0, s, tab, d);
+    else if (dt == F16) hipLaunchKernelGGL((reduce_partials_batched_kernel<half_t>), grid, block, 0, s, tab, d);
+    else hipLaunchKernelGGL((reduce_partials_batched_kernel<bf16_t>), grid, block, 0, s, tab, d);
+  }
 }
 
 // ---- column sums --------------------------------------------------------------------------------------------------------

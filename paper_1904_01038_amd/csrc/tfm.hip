@@ -113,6 +113,12 @@ struct tfm_ctx {
   std::vector<double> wq_flops;
   long wq_tiles;
   long wq_flush_tiles;                              // flush once this many 128x128 tiles are queued
+  // Deferred reductions of the LayerNorm backward kernels' partial column sums: each launch keeps its partials in its own
+  // slice of ln_pool, and one batched kernel adds them up at the next flush.
+  std::vector<LnReduceJob> lnq;
+  char* ln_pool;
+  size_t ln_slice;
+  int ln_slices, ln_next;
   hipEvent_t kv_ready;                              // side-stream mark after the cross-attention K/V projections (null: none)
   bool kv_done;                                     // they were projected ahead and the main stream already waited
   // The Adam step also runs on the side stream, cut into chunks in the order the forward pass first touches the
@@ -371,6 +377,9 @@ size_t carve(tfm_ctx* c, char* base) {
   c->pe = (float*)a.take((size_t)cf.max_len * d * 4);
   const size_t red = std::max(layernorm_bwd_scratch_bytes((int)R, (int)d), colsum_scratch_bytes((int)R, (int)wide));
   c->red_scratch = a.take(red);
+  c->ln_slice = (layernorm_bwd_scratch_bytes((int)R, (int)d) + 255) & ~(size_t)255;
+  c->ln_slices = (int)(c->enc.blocks.size() + c->dec.blocks.size()) + 2;      // one LayerNorm backward per block, plus final norms
+  c->ln_pool = (char*)a.take(c->ln_slice * c->ln_slices);
   c->red_scratch_side = a.take(colsum_scratch_bytes((int)R, (int)wide));
   c->scan_scratch = a.take(scan_scratch_bytes(c->P));
   c->splitk_bytes = c->dt == F32 ? 0 : (size_t)8 * 128 * 128 * 128 * sizeof(float);   // 8 slices of up to 128 tiles
@@ -485,9 +494,15 @@ void gemm(tfm_ctx* c, int form, int M, int N, int K, const void* A, int lda, con
 // Launches the queued weight gradients as one grouped GEMM on the side stream (after everything enqueued on the main
 // stream so far, which produced their operands).
 void flush_wgrads(tfm_ctx* c) {
-  if (c->wq.empty()) return;
+  if (c->wq.empty() && c->lnq.empty()) return;
   hipStream_t stream = wstream(c);
   side_begin(c);
+  if (!c->lnq.empty()) {
+    const int d = c->cfg.d_model;
+    run(c, TFM_PROF_NORM, 0.0, 0.0, [&] { launch_ln_reduce_batched(stream, c->dt, c->lnq.data(), (int)c->lnq.size(), d); }, stream);
+    c->lnq.clear();
+  }
+  if (c->wq.empty()) return;
   double flops = 0, bytes = 0;
   for (size_t i = 0; i < c->wq.size(); ++i) {
     const WgradJob& j = c->wq[i];
@@ -897,7 +912,7 @@ void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const voi
   const int d = c->cfg.d_model, F = c->cfg.d_ffn, T = st.rows;
   const std::vector<int>& len = st.id ? s.tlen : s.slen;
   if (b.kind == SELF) {
-    wgrad(c, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d);
+    wgrad(c, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d, gr(c, b.b_o));
     gemm(c, 1, T, d, d, dy, d, wh(c, b.w_o), d, c->dctx, d);
     const char* qkv = (const char*)b.inter;
     char* dqkv = (char*)b.dint;
@@ -908,7 +923,7 @@ void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const voi
   } else if (b.kind == CROSS) {
     Stream& en = c->enc;
     const void* mem = en.norm[en.blocks.size()];
-    wgrad(c, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d);
+    wgrad(c, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d, gr(c, b.b_o));
     gemm(c, 1, T, d, d, dy, d, wh(c, b.w_o), d, c->dctx, d);
     const char* kv = (const char*)b.kv;
     char* dkv = (char*)b.dkv;
@@ -921,7 +936,7 @@ void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const voi
     wgrad(c, d, d, T, b.dint, d, fin, d, gr(c, b.w_a), d, gr(c, b.b_a));
     wgrad(c, 2 * d, d, en.rows, dkv, 2 * d, mem, d, gr(c, b.w_kv), d, gr(c, b.b_kv));
   } else {
-    wgrad(c, d, F, T, dy, d, b.inter, F, gr(c, b.w_o), F);
+    wgrad(c, d, F, T, dy, d, b.inter, F, gr(c, b.w_o), F, gr(c, b.b_o));
     gemm(c, 1, T, F, d, dy, d, wh(c, b.w_o), F, b.dint, F, nullptr, 0, b.inter, nullptr);
     gemm(c, 1, T, d, F, b.dint, F, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
     wgrad(c, F, d, T, b.dint, F, fin, d, gr(c, b.w_a), d, gr(c, b.b_a));
@@ -933,10 +948,15 @@ void ln_bwd(tfm_ctx* c, const void* dn, const void* add, const void* sres, const
   const int d = c->cfg.d_model;
   const bool drop = c->cfg.dropout > 0.f && ds_drop;
   const double bytes = (double)c->esz * rows * d * (2.0 + (add ? 1.0 : 0.0) + 1.0 + (drop ? 1.0 : 0.0));
+  // the partial sums wait in their own slice of the pool for the batched reduction of the next flush
+  LnReduceJob job;
+  const bool defer = c->ln_next < c->ln_slices;
+  void* scratch = defer ? (void*)(c->ln_pool + (size_t)c->ln_next * c->ln_slice) : c->red_scratch;
   run(c, TFM_PROF_NORM, 0.0, bytes, [&] {
     launch_layernorm_bwd(c->stream, c->dt, dn, add, sres, mean, rstd, wh(c, g), ds, drop ? ds_drop : nullptr, gr(c, g), gr(c, b),
-                         bias_param >= 0 ? gr(c, bias_param) : nullptr, rows, d, key, c->cfg.dropout, c->red_scratch);
+                         bias_param >= 0 ? gr(c, bias_param) : nullptr, rows, d, key, c->cfg.dropout, scratch, defer ? &job : nullptr);
   });
+  if (defer) { c->lnq.push_back(job); c->ln_next += 1; }
 }
 
 // Backward through a stream.  On entry c->dcur holds the gradient w.r.t. the stream output norm[K]; returns the buffer
@@ -955,7 +975,7 @@ void* stream_bwd(const StepCtx& s, Stream& st, void** dmem_cur, void** dmem_othe
       // with dropout the kernel writes both the residual branch's gradient (dsA) and the sub-layer's (b.dy); without, they
       // are the same tensor
       void* ds = drop ? c->dsA : b.dy;
-      ln_bwd(c, dn, nullptr, st.resid[k + 1], st.mean[k + 1], st.rstd[k + 1], b.ln_g, b.ln_b, ds, b.dy, b.b_o, T, block_key(s, st, k));
+      ln_bwd(c, dn, nullptr, st.resid[k + 1], st.mean[k + 1], st.rstd[k + 1], b.ln_g, b.ln_b, ds, b.dy, -1, T, block_key(s, st, k));
       void* out = k == 0 ? c->demb[st.id] : c->dcur;
       sublayer_bwd(s, st, k, b.dy, st.norm[k], ds, out, dmem_cur, dmem_other, dmem_valid);
       dn = out;
@@ -970,10 +990,9 @@ void* stream_bwd(const StepCtx& s, Stream& st, void** dmem_cur, void** dmem_othe
   for (int idx = K; idx >= 0; --idx) {
     const int g = idx < K ? st.blocks[idx].ln_g : st.lnf_g;
     const int b = idx < K ? st.blocks[idx].ln_b : st.lnf_b;
-    const int bias = idx >= 1 ? st.blocks[idx - 1].b_o : -1;
     void* bdy = idx >= 1 ? st.blocks[idx - 1].dy : nullptr;
     void* ds = idx == 0 ? c->demb[st.id] : (drop ? pp : bdy);
-    ln_bwd(c, dn, dR, st.resid[idx], st.mean[idx], st.rstd[idx], g, b, ds, bdy, bias, T, idx >= 1 ? block_key(s, st, idx - 1) : 0);
+    ln_bwd(c, dn, dR, st.resid[idx], st.mean[idx], st.rstd[idx], g, b, ds, bdy, -1, T, idx >= 1 ? block_key(s, st, idx - 1) : 0);
     if (idx == 0) return ds;
     sublayer_bwd(s, st, idx - 1, bdy, st.norm[idx - 1], nullptr, c->dcur, dmem_cur, dmem_other, dmem_valid);
     dn = c->dcur;
@@ -1214,6 +1233,8 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   c->sync_used = 0;
   c->wq.clear();
   c->wq_tiles = 0;
+  c->lnq.clear();
+  c->ln_next = 0;
   c->kv_ready = nullptr;
   c->kv_done = false;
   if (has_enc) {
