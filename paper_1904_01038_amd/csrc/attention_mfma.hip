@@ -13,6 +13,7 @@
 //          stores the row log-sum-exp.
 // Backward (one launch): blocks [0, nq) along x compute dQ with the forward's decomposition, recomputing P from the
 //           saved log-sum-exp; blocks [nq, nq+nk) own 64-key chunks and loop over query chunks for dK/dV.  No atomics.
+//           Launches whose sentences all fit one chunk use a kernel that forms all three gradients in one block.
 #include "common.h"
 #include "kernels.h"
 
@@ -70,23 +71,26 @@ struct AttnP {
 };
 
 // rows r0..r0+31 of a staged tile as an MFMA operand: lane -> row r0 + lane%32, columns kk*16 + (lane/32)*8 .. +8
+template <int P = PT>
 __device__ __forceinline__ u32x4 frag_direct(const uint16_t* S, int r0, int kk, int lane) {
-  return *reinterpret_cast<const u32x4*>(S + (r0 + (lane & 31)) * PT + kk * 16 + (lane >> 5) * 8);
+  return *reinterpret_cast<const u32x4*>(S + (r0 + (lane & 31)) * P + kk * 16 + (lane >> 5) * 8);
 }
 // columns c0..c0+31 of a staged tile as an MFMA operand whose contraction runs over 16 tile rows from kbase:
 // lane -> column c0 + lane%32; k-slot (half = lane/32, e) -> tile row kbase + 4*half + e (e < 4), kbase + 8 + 4*half + e-4.
 // This is the row order in which a 32x32 accumulator holds its rows, so an accumulator converts in place into the
 // other operand of the same product.
+template <int P = PT>
 __device__ __forceinline__ u32x4 frag_tr(const uint16_t* S, int c0, int kbase, int lane) {
   const int s = lane & 15, ibase = lane & 16, half = lane >> 5;
-  const uint16_t* p = S + (kbase + 4 * half + (s >> 2)) * PT + c0 + ibase + 4 * (s & 3);
+  const uint16_t* p = S + (kbase + 4 * half + (s >> 2)) * P + c0 + ibase + 4 * (s & 3);
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * PT));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * P));
   const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
   return u32x4{l2[0], l2[1], h2[0], h2[1]};
 }
 // 64 rows x 64 columns from global (row stride ld) into LDS, zero beyond nvalid rows.  128 threads, 4 vectors each.
+template <int P = PT>
 __device__ __forceinline__ void stage_tile(uint16_t* S, const uint16_t* __restrict__ G, int ld, int row0, int nvalid) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -94,7 +98,7 @@ __device__ __forceinline__ void stage_tile(uint16_t* S, const uint16_t* __restri
     const int r = v >> 3, c = (v & 7) * 8;
     u32x4 x = {0u, 0u, 0u, 0u};
     if (row0 + r < nvalid) x = *reinterpret_cast<const u32x4*>(G + (size_t)(row0 + r) * ld + c);
-    *reinterpret_cast<u32x4*>(S + r * PT + c) = x;
+    *reinterpret_cast<u32x4*>(S + r * P + c) = x;
   }
 }
 // The same in two halves, so that the next chunk's rows travel from memory while the current chunk is being used.
@@ -146,6 +150,29 @@ template <typename T>
 __device__ __forceinline__ void store4(uint16_t* p, float a, float b, float c, float d) {
   u32x2 v = {AMfma<T>::pack2(a, b), AMfma<T>::pack2(c, d)};
   *reinterpret_cast<u32x2*>(p) = v;
+}
+
+// Results leave the matrix cores with 4 consecutive columns of a row per register quadruple; stored directly, every
+// 128-byte row of a result would be written in eight 16-byte pieces.  A block instead parks its 64 x 64 result in an
+// LDS tile it no longer needs (pitch P halfs) and then stores whole rows, 8 threads x 16 bytes each.
+template <typename T, int P>
+__device__ __forceinline__ void park_rows(uint16_t* S, int r, int half, const f32x16 (&acc)[2], float mul) {
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg)
+      store4<T>(S + r * P + db * 32 + rg * 8 + half * 4, acc[db][rg * 4] * mul, acc[db][rg * 4 + 1] * mul, acc[db][rg * 4 + 2] * mul,
+                acc[db][rg * 4 + 3] * mul);
+}
+// rows [row0, row0 + 64) of the parked tile to G (row stride ld), rows at or beyond nvalid left out
+template <int P>
+__device__ __forceinline__ void store_rows(uint16_t* __restrict__ G, int ld, int row0, int nvalid, const uint16_t* S) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v = threadIdx.x + ATT_THREADS * i;
+    const int r = v >> 3, c = (v & 7) * 8;
+    if (row0 + r < nvalid) *reinterpret_cast<u32x4*>(G + (size_t)(row0 + r) * ld + c) = *reinterpret_cast<const u32x4*>(S + r * P + c);
+  }
 }
 
 // ---- forward ------------------------------------------------------------------------------------------------------------
@@ -223,19 +250,12 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_
         for (int db = 0; db < 2; ++db) acc[db] = AMfma<T>::run(frag_tr(Vs, db * 32, kb * 32 + ks * 16, lane), pf[ks], acc[db]);
     }
   }
-  if (!active) return;
   lsum += __shfl_xor(lsum, 32, 64);
-  if (qi < lq) {
-    const float inv = 1.f / lsum;
-    uint16_t* O = p.out + (size_t)(q0 + qi) * p.ldo + h * DH;
-#pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-      for (int rg = 0; rg < 4; ++rg)
-        store4<T>(O + db * 32 + rg * 8 + half * 4, acc[db][rg * 4] * inv, acc[db][rg * 4 + 1] * inv, acc[db][rg * 4 + 2] * inv,
-                  acc[db][rg * 4 + 3] * inv);
-    if (half == 0) p.lse[(size_t)h * p.total_q + q0 + qi] = m + logf(lsum);
-  }
+  __syncthreads();                                   // every wavefront is done with the K tile
+  park_rows<T, PT>(Ks, wave * 32 + (lane & 31), half, acc, active && qi < lq ? 1.f / lsum : 0.f);
+  if (active && qi < lq && half == 0) p.lse[(size_t)h * p.total_q + q0 + qi] = m + logf(lsum);
+  __syncthreads();
+  store_rows<PT>(p.out + (size_t)q0 * p.ldo + h * DH, p.ldo, qstart, lq, Ks);
 }
 
 // ---- backward: dQ ---------------------------------------------------------------------------------------------------------
@@ -307,14 +327,10 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnP& p, int chunk, uint
         for (int db = 0; db < 2; ++db) acc[db] = AMfma<T>::run(frag_tr(Ks, db * 32, kb * 32 + ks * 16, lane), df[ks], acc[db]);
     }
   }
-  if (!active || qi >= lq) return;
-  uint16_t* DQ = p.dq + (size_t)(q0 + qi) * p.lddq + h * DH;
-#pragma unroll
-  for (int db = 0; db < 2; ++db)
-#pragma unroll
-    for (int rg = 0; rg < 4; ++rg)
-      store4<T>(DQ + db * 32 + rg * 8 + half * 4, acc[db][rg * 4] * p.scale, acc[db][rg * 4 + 1] * p.scale,
-                acc[db][rg * 4 + 2] * p.scale, acc[db][rg * 4 + 3] * p.scale);
+  __syncthreads();
+  park_rows<T, PT>(Ks, wave * 32 + (lane & 31), half, acc, p.scale);
+  __syncthreads();
+  store_rows<PT>(p.dq + (size_t)q0 * p.lddq + h * DH, p.lddq, qstart, lq, Ks);
 }
 
 // ---- backward: dK, dV -------------------------------------------------------------------------------------------------------
@@ -406,17 +422,12 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnP& p, int chunk, uin
         }
     }
   }
-  if (!active || kj >= lk) return;
-  uint16_t* DK = p.dk + (size_t)(k0 + kj) * p.lddk + h * DH;
-  uint16_t* DV = p.dv + (size_t)(k0 + kj) * p.lddv + h * DH;
-#pragma unroll
-  for (int db = 0; db < 2; ++db)
-#pragma unroll
-    for (int rg = 0; rg < 4; ++rg) {
-      store4<T>(DK + db * 32 + rg * 8 + half * 4, ak[db][rg * 4] * p.scale, ak[db][rg * 4 + 1] * p.scale, ak[db][rg * 4 + 2] * p.scale,
-                ak[db][rg * 4 + 3] * p.scale);
-      store4<T>(DV + db * 32 + rg * 8 + half * 4, av[db][rg * 4], av[db][rg * 4 + 1], av[db][rg * 4 + 2], av[db][rg * 4 + 3]);
-    }
+  __syncthreads();
+  park_rows<T, PT>(Qs, wave * 32 + (lane & 31), half, ak, p.scale);
+  park_rows<T, PT>(Gs, wave * 32 + (lane & 31), half, av, 1.f);
+  __syncthreads();
+  store_rows<PT>(p.dk + (size_t)k0 * p.lddk + h * DH, p.lddk, kstart, lk, Qs);
+  store_rows<PT>(p.dv + (size_t)k0 * p.lddv + h * DH, p.lddv, kstart, lk, Gs);
 }
 
 // One launch for the whole backward: the first nq_chunks blocks along x compute dQ, the rest dK/dV; the two halves are
@@ -429,6 +440,147 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_BWD_MIN_WAVES) void attn_bwd_mfma_
   __shared__ __attribute__((aligned(16))) float Ds[CH];
   if ((int)blockIdx.x < nq_chunks) attn_bwd_dq_body<T>(p, blockIdx.x, S0, S1);
   else attn_bwd_dkv_body<T>(p, blockIdx.x - nq_chunks, S0, S1, Ls, Ds);
+}
+
+// ---- backward, sentences of at most 64 tokens: dQ, dK and dV of a (sentence, head) in one block --------------------------
+// When every sentence of the launch fits one chunk (most batches of the translation workloads: sentences of similar
+// length share a batch), the two halves above would each fetch the five tiles Q, K, V, O, dO of the same (sentence,
+// head).  Here one block stages them once and uses them for both: its wavefronts' queries against K, V (dQ) and their
+// keys against Q, dO (dK, dV).  The scores are formed in both orientations by the matrix cores, which are nearly idle in
+// this kernel anyway, so nothing is transposed through LDS; the operand fragments of the block's own rows also come from
+// the staged tiles, so every input is read from memory exactly once.  Four tiles at a 144-byte pitch (16 rows x 16
+// bytes cover the 64 banks once) keep four blocks resident per CU.
+constexpr int PF = 72;
+
+template <typename T>
+__global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p) {
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[CH * PF];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[CH * PF];
+  __shared__ __attribute__((aligned(16))) uint16_t Qs[CH * PF];
+  __shared__ __attribute__((aligned(16))) uint16_t Gs[CH * PF];
+  __shared__ __attribute__((aligned(16))) float Ls[CH];
+  __shared__ __attribute__((aligned(16))) float Ds[CH];
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;   // both in [1, 64]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
+  const int own0 = wave * 32;                        // first own row of this wavefront (a query for dQ, a key for dK/dV)
+  const int own = own0 + (lane & 31);
+  const uint16_t* Q = p.q + (size_t)q0 * p.ldq + h * DH;
+  const uint16_t* G = p.d_o + (size_t)q0 * p.lddo + h * DH;
+  const uint16_t* O = p.o + (size_t)q0 * p.ldo + h * DH;
+  stage_tile<PF>(Ks, p.k + (size_t)k0 * p.ldk + h * DH, p.ldk, 0, lk);
+  stage_tile<PF>(Vs, p.v + (size_t)k0 * p.ldv + h * DH, p.ldv, 0, lk);
+  // stage Q and dO; the 8 threads that share a row also form delta = dO . O for it
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v = threadIdx.x + ATT_THREADS * i;
+    const int r = v >> 3, cc = (v & 7) * 8;
+    u32x4 xq = {0u, 0u, 0u, 0u}, xg = xq, xo = xq;
+    if (r < lq) {
+      xq = *reinterpret_cast<const u32x4*>(Q + (size_t)r * p.ldq + cc);
+      xg = *reinterpret_cast<const u32x4*>(G + (size_t)r * p.lddo + cc);
+      xo = *reinterpret_cast<const u32x4*>(O + (size_t)r * p.ldo + cc);
+    }
+    *reinterpret_cast<u32x4*>(Qs + r * PF + cc) = xq;
+    *reinterpret_cast<u32x4*>(Gs + r * PF + cc) = xg;
+    float dl = dot8<T>(xg, xo);
+    dl += __shfl_xor(dl, 1, 64);
+    dl += __shfl_xor(dl, 2, 64);
+    dl += __shfl_xor(dl, 4, 64);
+    if ((v & 7) == 0) {
+      Ds[r] = dl;
+      Ls[r] = r < lq ? p.lse[(size_t)h * p.total_q + q0 + r] : 0.f;
+    }
+  }
+  __syncthreads();
+  f32x16 aq[2], ak[2], av[2];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) { aq[0][e] = aq[1][e] = ak[0][e] = ak[1][e] = av[0][e] = av[1][e] = 0.f; }
+  if (own0 < lq) {
+    // dQ^T[d][query] = K^T dS^T with S^T[key][query]: a lane owns one query, 16 keys in registers
+    const float delta = Ds[own], L = Ls[own];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const int j0 = kb * 32;
+      if (j0 >= lk) break;
+      f32x16 s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        s = AMfma<T>::run(frag_direct<PF>(Ks, j0, kk, lane), frag_direct<PF>(Qs, own0, kk, lane), s);
+        dp = AMfma<T>::run(frag_direct<PF>(Vs, j0, kk, lane), frag_direct<PF>(Gs, own0, kk, lane), dp);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int jj = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const bool ok = jj < lk && own < lq && (!p.causal || jj <= own);
+        const float pr = ok ? __expf(s[r] * p.scale - L) : 0.f;
+        s[r] = pr * (dp[r] - delta);
+      }
+      u32x4 df[2];
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) df[ks][w] = AMfma<T>::pack2(s[ks * 8 + 2 * w], s[ks * 8 + 2 * w + 1]);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) aq[db] = AMfma<T>::run(frag_tr<PF>(Ks, db * 32, j0 + ks * 16, lane), df[ks], aq[db]);
+    }
+  }
+  if (own0 < lk) {
+    // dK^T[d][key] = Q^T dS, dV^T[d][key] = dO^T P with S[query][key]: a lane owns one key, 16 queries in registers
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const int i0 = qb * 32;
+      if (i0 >= lq) break;
+      if (p.causal && i0 + 31 < own0) continue;      // every query of this block precedes every key of this wavefront
+      f32x16 s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        s = AMfma<T>::run(frag_direct<PF>(Qs, i0, kk, lane), frag_direct<PF>(Ks, own0, kk, lane), s);
+        dp = AMfma<T>::run(frag_direct<PF>(Gs, i0, kk, lane), frag_direct<PF>(Vs, own0, kk, lane), dp);
+      }
+      u32x4 pf[2], df[2];
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const int il = i0 + rg * 8 + half * 4;
+        const float4 l4 = *reinterpret_cast<const float4*>(Ls + il);
+        const float4 d4 = *reinterpret_cast<const float4*>(Ds + il);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
+        float pr[4], dsv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = il + e;
+          const bool ok = i < lq && own < lk && (!p.causal || own <= i);
+          pr[e] = ok ? __expf(s[rg * 4 + e] * p.scale - lv[e]) : 0.f;
+          dsv[e] = pr[e] * (dp[rg * 4 + e] - dv[e]);
+        }
+        pf[rg >> 1][(rg & 1) * 2] = AMfma<T>::pack2(pr[0], pr[1]);
+        pf[rg >> 1][(rg & 1) * 2 + 1] = AMfma<T>::pack2(pr[2], pr[3]);
+        df[rg >> 1][(rg & 1) * 2] = AMfma<T>::pack2(dsv[0], dsv[1]);
+        df[rg >> 1][(rg & 1) * 2 + 1] = AMfma<T>::pack2(dsv[2], dsv[3]);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          av[db] = AMfma<T>::run(frag_tr<PF>(Gs, db * 32, i0 + ks * 16, lane), pf[ks], av[db]);
+          ak[db] = AMfma<T>::run(frag_tr<PF>(Qs, db * 32, i0 + ks * 16, lane), df[ks], ak[db]);
+        }
+    }
+  }
+  __syncthreads();                                   // the tiles are no longer needed: park the three results in them
+  park_rows<T, PF>(Qs, own, half, aq, p.scale);
+  park_rows<T, PF>(Ks, own, half, ak, p.scale);
+  park_rows<T, PF>(Vs, own, half, av, 1.f);
+  __syncthreads();
+  store_rows<PF>(p.dq + (size_t)q0 * p.lddq + h * DH, p.lddq, 0, lq, Qs);
+  store_rows<PF>(p.dk + (size_t)k0 * p.lddk + h * DH, p.lddk, 0, lk, Ks);
+  store_rows<PF>(p.dv + (size_t)k0 * p.lddv + h * DH, p.lddv, 0, lk, Vs);
 }
 
 static bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
@@ -465,6 +617,12 @@ void launch_attention_fwd_mfma(hipStream_t s, const AttnArgs& a) {
 void launch_attention_bwd_mfma(hipStream_t s, const AttnArgs& a) {
   const AttnP p = make_params(a);
   const int nq = (a.max_lq + 63) / 64, nk = (a.max_lk + 63) / 64;
+  if (nq == 1 && nk == 1) {                              // every sentence fits one chunk: one block per (sentence, head)
+    dim3 grid(1, a.H, a.B), block(ATT_THREADS);
+    if (a.dt == F16) hipLaunchKernelGGL((attn_bwd_single_kernel<half_t>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((attn_bwd_single_kernel<bf16_t>), grid, block, 0, s, p);
+    return;
+  }
   dim3 grid(nq + nk, a.H, a.B), block(ATT_THREADS);
   if (a.dt == F16) hipLaunchKernelGGL((attn_bwd_mfma_kernel<half_t>), grid, block, 0, s, p, nq);
   else hipLaunchKernelGGL((attn_bwd_mfma_kernel<bf16_t>), grid, block, 0, s, p, nq);

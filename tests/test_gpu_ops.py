@@ -185,6 +185,14 @@ ATTN_CASES = [  # (query lengths, key lengths or None for self-attention, causal
     ([5, 1, 33, 64, 65, 100], None, True),
     ([7, 45, 80, 130], [9, 31, 97, 150], False),
     ([200, 3], None, True),
+    # every sentence within one 64-row chunk: the backward kernel that forms dQ, dK and dV in one block
+    ([5, 64, 33, 1], None, True),
+    ([7, 45, 64, 1], [9, 64, 31, 64], False),
+    # two chunks on one side or both
+    ([7, 45, 80, 128], [9, 31, 97, 66], False),
+    ([10, 60, 64], [70, 128, 1], False),
+    ([70, 128, 3], [10, 64, 64], False),
+    ([128, 127, 66, 2], None, True),
 ]
 
 
