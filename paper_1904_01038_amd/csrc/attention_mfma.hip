@@ -177,12 +177,14 @@ __device__ __forceinline__ void store_rows(uint16_t* __restrict__ G, int ld, int
 
 // ---- forward ------------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_kernel(AttnP p) {
+__global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_kernel(AttnP p, int H) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[CH * PT];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[CH * PT];
-  const int b = blockIdx.z, h = blockIdx.y;
+  // Blocks are dispatched x fastest: x walks the (sentence, head) pairs and y the query chunks from the last one down, so
+  // under a causal mask (chunk c loops over c + 1 key chunks) the longest blocks of the whole launch start first.
+  const int b = blockIdx.x / H, h = blockIdx.x - b * H;
   const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;
-  const int qstart = blockIdx.x * 64;
+  const int qstart = ((int)gridDim.y - 1 - (int)blockIdx.y) * 64;
   if (qstart >= lq) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int qi0 = qstart + wave * 32;
@@ -260,8 +262,7 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_
 
 // ---- backward: dQ ---------------------------------------------------------------------------------------------------------
 template <typename T>
-__device__ __forceinline__ void attn_bwd_dq_body(const AttnP& p, int chunk, uint16_t* Ks, uint16_t* Vs) {
-  const int b = blockIdx.z, h = blockIdx.y;
+__device__ __forceinline__ void attn_bwd_dq_body(const AttnP& p, int b, int h, int chunk, uint16_t* Ks, uint16_t* Vs) {
   const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;
   const int qstart = chunk * 64;
   if (qstart >= lq) return;
@@ -335,8 +336,7 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnP& p, int chunk, uint
 
 // ---- backward: dK, dV -------------------------------------------------------------------------------------------------------
 template <typename T>
-__device__ __forceinline__ void attn_bwd_dkv_body(const AttnP& p, int chunk, uint16_t* Qs, uint16_t* Gs, float* Ls, float* Ds) {
-  const int b = blockIdx.z, h = blockIdx.y;
+__device__ __forceinline__ void attn_bwd_dkv_body(const AttnP& p, int b, int h, int chunk, uint16_t* Qs, uint16_t* Gs, float* Ls, float* Ds) {
   const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;
   const int kstart = chunk * 64;
   if (kstart >= lk) return;
@@ -430,16 +430,27 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnP& p, int chunk, uin
   store_rows<PT>(p.dv + (size_t)k0 * p.lddv + h * DH, p.lddv, kstart, lk, Gs);
 }
 
-// One launch for the whole backward: the first nq_chunks blocks along x compute dQ, the rest dK/dV; the two halves are
-// independent, so they run side by side instead of one after the other.
+// One launch for the whole backward: nq_chunks blocks per (sentence, head) compute dQ, nk_chunks dK/dV; the two halves are
+// independent, so they run side by side instead of one after the other.  Blocks are dispatched x fastest: x walks the
+// (sentence, head) pairs and y the chunks in the order of decreasing work under a causal mask (dK/dV of key chunk c loops
+// over n - c query chunks, dQ of query chunk c over c + 1 key chunks), so the longest blocks of the whole launch start
+// first and the short ones fill the tail.
 template <typename T>
-__global__ __launch_bounds__(ATT_THREADS, ATT_BWD_MIN_WAVES) void attn_bwd_mfma_kernel(AttnP p, int nq_chunks) {
+__global__ __launch_bounds__(ATT_THREADS, ATT_BWD_MIN_WAVES) void attn_bwd_mfma_kernel(AttnP p, int nq_chunks, int nk_chunks, int H) {
   __shared__ __attribute__((aligned(16))) uint16_t S0[CH * PT];
   __shared__ __attribute__((aligned(16))) uint16_t S1[CH * PT];
   __shared__ __attribute__((aligned(16))) float Ls[CH];
   __shared__ __attribute__((aligned(16))) float Ds[CH];
-  if ((int)blockIdx.x < nq_chunks) attn_bwd_dq_body<T>(p, blockIdx.x, S0, S1);
-  else attn_bwd_dkv_body<T>(p, blockIdx.x - nq_chunks, S0, S1, Ls, Ds);
+  const int b = blockIdx.x / H, h = blockIdx.x - b * H;
+  // y = 0, 1, 2, 3, ... -> dK/dV chunk 0, dQ chunk nq-1, dK/dV chunk 1, dQ chunk nq-2, ... while both kinds last
+  const int r = blockIdx.y, pairs = min(nq_chunks, nk_chunks);
+  bool is_dq;
+  int chunk;
+  if (r < 2 * pairs) { is_dq = r & 1; chunk = is_dq ? nq_chunks - 1 - (r >> 1) : (r >> 1); }
+  else if (nq_chunks > nk_chunks) { is_dq = true; chunk = nq_chunks - 1 - (r - pairs); }
+  else { is_dq = false; chunk = r - pairs; }
+  if (is_dq) attn_bwd_dq_body<T>(p, b, h, chunk, S0, S1);
+  else attn_bwd_dkv_body<T>(p, b, h, chunk, S0, S1, Ls, Ds);
 }
 
 // ---- backward, sentences of at most 64 tokens: dQ, dK and dV of a (sentence, head) in one block --------------------------
@@ -609,9 +620,9 @@ static AttnP make_params(const AttnArgs& a) {
 
 void launch_attention_fwd_mfma(hipStream_t s, const AttnArgs& a) {
   const AttnP p = make_params(a);
-  dim3 grid((a.max_lq + 63) / 64, a.H, a.B), block(ATT_THREADS);
-  if (a.dt == F16) hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t>), grid, block, 0, s, p);
-  else hipLaunchKernelGGL((attn_fwd_mfma_kernel<bf16_t>), grid, block, 0, s, p);
+  dim3 grid(a.H * a.B, (a.max_lq + 63) / 64), block(ATT_THREADS);
+  if (a.dt == F16) hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t>), grid, block, 0, s, p, a.H);
+  else hipLaunchKernelGGL((attn_fwd_mfma_kernel<bf16_t>), grid, block, 0, s, p, a.H);
 }
 
 void launch_attention_bwd_mfma(hipStream_t s, const AttnArgs& a) {
@@ -623,9 +634,9 @@ void launch_attention_bwd_mfma(hipStream_t s, const AttnArgs& a) {
     else hipLaunchKernelGGL((attn_bwd_single_kernel<bf16_t>), grid, block, 0, s, p);
     return;
   }
-  dim3 grid(nq + nk, a.H, a.B), block(ATT_THREADS);
-  if (a.dt == F16) hipLaunchKernelGGL((attn_bwd_mfma_kernel<half_t>), grid, block, 0, s, p, nq);
-  else hipLaunchKernelGGL((attn_bwd_mfma_kernel<bf16_t>), grid, block, 0, s, p, nq);
+  dim3 grid(a.H * a.B, nq + nk), block(ATT_THREADS);
+  if (a.dt == F16) hipLaunchKernelGGL((attn_bwd_mfma_kernel<half_t>), grid, block, 0, s, p, nq, nk, a.H);
+  else hipLaunchKernelGGL((attn_bwd_mfma_kernel<bf16_t>), grid, block, 0, s, p, nq, nk, a.H);
 }
 
 }  // namespace tfm
