@@ -172,3 +172,22 @@ def test_half_precision_with_head_widths_other_than_64(prec):
         for k, v in oracle.G.items():
             assert cosine(gg[k], v) >= 0.999, (shape, k, cosine(gg[k], v))
         gpu.close()
+
+
+def test_more_weight_gradients_than_one_grouped_launch_holds():
+    """A deep, narrow encoder-decoder has more weight gradients per backward pass (4 per encoder layer, 7 per decoder
+    layer, 1 for the vocabulary) than the 48 products one grouped launch takes: the queue must flush on its own in the
+    middle of the decoder and again later, and every gradient must still match the oracle.  (fp16 only: through 14 layers
+    bf16's 8-bit mantissa alone takes the first layers' gradients to a cosine of 0.9989.)"""
+    import paper_1904_01038_amd as T
+    p = T.FP16
+    shape = ModelShape(5, 9, 64, 1, 128, 96)                 # 20 + 63 + 1 = 84 products; head width 64
+    gpu, oracle = make_pair(shape, p, dropout=0.1, init_loss_scale=4.0, max_sentences=8, max_len=40, max_tokens=256)
+    batch = make_batches("base", 1, shape=shape, max_tokens=200, lo=5, hi=38)[0]
+    rg, ro = step_both(gpu, oracle, batch)
+    assert rg["overflow"] == 0
+    assert abs(rg["loss_sum"] - ro["loss_sum"]) <= 1e-2 * abs(ro["loss_sum"])
+    gg = gpu.get_grads()
+    for k, v in oracle.G.items():
+        assert cosine(gg[k], v) >= 0.999, (k, cosine(gg[k], v))
+    gpu.close()
