@@ -60,3 +60,55 @@ def test_lm16_fp16_full_size_subbatch():
 def test_lm16_adaptive_fp16_full_size_subbatch():
     """267.7 K types in three clusters: every tail GEMM at its real shape."""
     check(*run_workload("lm16a", "fp16"))
+
+
+def test_big_fp16_delayed_updates_with_injected_overflows_full_size():
+    """The delayed-update workload at full size (big model, 16 sub-batches of sentences of 10-120 tokens per update, two
+    windows): sub-batches 5 and 11 of the first window run with the loss multiplied by 1e6, which must flag exactly those
+    two, skip that update with one halving of the scale (8 -> 4; with these random initial weights a scale of 128
+    overflows on its own, as the benchmark's first updates show) and leave every parameter bit-unchanged; the second
+    window applies with scale 4.  The oracle is too slow for 32 full-size sub-batches, so this checks the properties
+    that hold at any size; the values are compared at small size in test_gpu_scaler.py."""
+    import paper_1904_01038_amd as T
+    shape = PRESETS[WORKLOADS["big_accum"]["model"]]
+    batches = make_batches("big_accum", 32)
+    max_tok = max(max(b.ntokens, int(b.src_lens.sum())) for b in batches)
+    cfg = T.make_config(shape, precision=T.FP16, max_sentences=max(len(b.tgt_lens) for b in batches),
+                        max_tokens=(max_tok + 63) // 64 * 64, max_len=max(max(b.tgt.shape[1], b.src.shape[1]) for b in batches),
+                        dropout=0.1, init_loss_scale=8.0, label_smoothing=0.1)
+    gpu = T.Tfm(cfg)
+    gpu.set_params(init_params(shape, 0))
+    before = gpu.get_params()
+    names = [n for n in gpu.param_names if n == "embed" or n.endswith((".wqkv", ".w2", ".wkv"))]
+    assert len(names) >= 20
+    tokens = 0
+    for j in range(16):
+        b = batches[j]
+        if j in (5, 11):
+            gpu.debug_set_loss_multiplier(1e6)
+        r = gpu.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens)
+        tokens += r["ntokens"]
+        assert r["overflow"] == (1 if j in (5, 11) else 0), j
+        assert r["loss_scale"] == 8.0
+        if j not in (5, 11):
+            assert np.isfinite(r["loss_sum"]) and 0.5 * np.log(shape.vocab) < r["loss_sum"] / r["ntokens"] < 2.0 * np.log(shape.vocab)
+    u = gpu.apply_update(1e-4)
+    assert (u["skipped"], u["loss_scale_after"], u["num_updates"], u["ntokens_total"]) == (1, 4.0, 0, tokens)
+    after = gpu.get_params()
+    for n in before:
+        assert np.array_equal(before[n], after[n]), n
+    del after
+    tokens = 0
+    for j in range(16, 32):
+        b = batches[j]
+        r = gpu.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens)
+        tokens += r["ntokens"]
+        assert r["overflow"] == 0 and r["loss_scale"] == 4.0
+    u = gpu.apply_update(1e-4)
+    assert (u["skipped"], u["loss_scale_after"], u["num_updates"], u["ntokens_total"]) == (0, 4.0, 1, tokens)
+    assert np.isfinite(u["grad_norm"]) and u["grad_norm"] > 0
+    after = gpu.get_params()
+    changed = [n for n in names if not np.array_equal(before[n], after[n])]
+    assert changed == names                                  # Adam moved every weight matrix probed
+    assert all(np.isfinite(v).all() for v in after.values())
+    gpu.close()
