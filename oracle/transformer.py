@@ -78,8 +78,25 @@ def dropout_keep(key, row0, nrows, width, p):
 
 def site_id(stream, layer, sub):
     """Dropout site number.  stream: 0 encoder, 1 decoder.  layer: -1 for the embedding, else the layer index.
-    sub: 0 self-attention output, 1 cross-attention output, 2 feed-forward output."""
+    sub: 0 self-attention output, 1 cross-attention output, 2 feed-forward output, 3 self-attention weights,
+    4 cross-attention weights, 5 feed-forward hidden activations (after the ReLU)."""
     return 1000 * stream + 10 * (layer + 1) + sub
+
+
+def attention_keep(key, qrow0, n, n_heads, h, m, p):
+    """Boolean keep mask [n, m] for the attention weights of head h: queries are the packed rows qrow0.. of their
+    stream, keys j = 0..m-1 of the same sentence (m < 65536).
+
+    Element e = ((query row * n_heads + h) << 16) + j, then as in dropout_keep: one 64-bit word serves four
+    consecutive keys of one (query, head).
+    """
+    rows = np.arange(qrow0, qrow0 + n, dtype=np.uint64)[:, None]
+    cols = np.arange(m, dtype=np.uint64)[None, :]
+    e = ((rows * np.uint64(n_heads) + np.uint64(h)) << np.uint64(16)) + cols
+    with np.errstate(over="ignore"):
+        w = _mix64(np.uint64(key) + (e >> np.uint64(2)) * np.uint64(0x9E3779B97F4A7C15))
+    f = (w >> ((e & np.uint64(3)) * np.uint64(16))) & np.uint64(0xFFFF)
+    return f >= np.uint64(dropout_threshold(p))
 
 
 # ----------------------------------------------------------------------------------------------------------------
@@ -118,8 +135,12 @@ def softmax_rows(s):
     return e / e.sum(axis=-1, keepdims=True)
 
 
-def attention_fwd(q, k, v, n_heads, causal):
-    """softmax(q k^T / sqrt(d_h) [+ causal mask]) v per head; q [n,d], k,v [m,d]."""
+def attention_fwd(q, k, v, n_heads, causal, keep=None, p_drop=0.0):
+    """softmax(q k^T / sqrt(d_h) [+ causal mask]) v per head; q [n,d], k,v [m,d].
+
+    keep (optional): per head a boolean [n, m]; the attention weights are then multiplied by keep / (1 - p_drop)
+    (inverted dropout on the weights) before they average the values.
+    """
     n, d = q.shape
     dh = d // n_heads
     ctx = np.zeros((n, d))
@@ -131,20 +152,24 @@ def attention_fwd(q, k, v, n_heads, causal):
             s = np.where(np.arange(k.shape[0])[None, :] <= np.arange(n)[:, None], s, -np.inf)
         p = softmax_rows(s)
         probs.append(p)
-        ctx[:, sl] = p @ v[:, sl]
-    return ctx, (q, k, v, probs, n_heads)
+        pd = p if keep is None else np.where(keep[h], p / (1.0 - p_drop), 0.0)
+        ctx[:, sl] = pd @ v[:, sl]
+    return ctx, (q, k, v, probs, n_heads, keep, p_drop)
 
 
 def attention_bwd(dctx, cache):
-    q, k, v, probs, n_heads = cache
+    q, k, v, probs, n_heads, keep, p_drop = cache
     d = q.shape[1]
     dh = d // n_heads
     dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
     for h in range(n_heads):
         sl = slice(h * dh, (h + 1) * dh)
         p = probs[h]
-        dv[:, sl] = p.T @ dctx[:, sl]
-        dp = dctx[:, sl] @ v[:, sl].T
+        pd = p if keep is None else np.where(keep[h], p / (1.0 - p_drop), 0.0)
+        dv[:, sl] = pd.T @ dctx[:, sl]
+        dp = dctx[:, sl] @ v[:, sl].T                            # gradient w.r.t. the dropped weights ...
+        if keep is not None:
+            dp = np.where(keep[h], dp / (1.0 - p_drop), 0.0)     # ... and w.r.t. the softmax output
         ds = p * (dp - (dp * p).sum(axis=-1, keepdims=True))
         dq[:, sl] = ds @ k[:, sl] / np.sqrt(dh)
         dk[:, sl] = ds.T @ q[:, sl] / np.sqrt(dh)
@@ -174,7 +199,9 @@ def label_smoothed_nll(z, y, eps):
 # ----------------------------------------------------------------------------------------------------------------
 @dataclass
 class TrainConfig:
-    dropout: float = 0.0
+    dropout: float = 0.0            # on the embedding sums and on each sub-layer output before the residual sum
+    attn_dropout: float = 0.0       # on the attention weights (after the softmax)
+    relu_dropout: float = 0.0       # on the feed-forward hidden activations (after the ReLU)
     label_smoothing: float = 0.1
     adam_beta1: float = 0.9
     adam_beta2: float = 0.98
@@ -232,10 +259,22 @@ class OracleTransformer:
             return dy
         return np.where(keep, dy / (1.0 - self.cfg.dropout), 0.0)
 
-    def _self_attn_fwd(self, pre, x, causal):
+    def _attn_keep(self, site, sub, n, m):
+        """Keep masks of the attention weights, one per head, or None.  site = (stream, layer, first packed query row)."""
+        p = self.cfg.attn_dropout
+        if p <= 0.0:
+            return None
+        stream, layer, row0 = site
+        key = dropout_key(self.cfg.seed, self._step, site_id(stream, layer, sub))
+        H = self.shape.n_heads
+        return [attention_keep(key, row0, n, H, h, m, p) for h in range(H)]
+
+    def _self_attn_fwd(self, pre, x, causal, site=None):
         P, d = self.p, self.shape.d_model
         qkv = x @ P[pre + ".wqkv"].T + P[pre + ".bqkv"]
-        ctx, ac = attention_fwd(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], self.shape.n_heads, causal)
+        keep = self._attn_keep(site, 3, x.shape[0], x.shape[0])
+        ctx, ac = attention_fwd(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], self.shape.n_heads, causal, keep,
+                                self.cfg.attn_dropout)
         y = ctx @ P[pre + ".wo"].T + P[pre + ".bo"]
         return y, (x, ctx, ac)
 
@@ -250,11 +289,12 @@ class OracleTransformer:
         g.add(pre + ".bqkv", dqkv.sum(axis=0))
         return dqkv @ P[pre + ".wqkv"]
 
-    def _cross_attn_fwd(self, pre, x, mem):
+    def _cross_attn_fwd(self, pre, x, mem, site=None):
         P, d = self.p, self.shape.d_model
         q = x @ P[pre + ".wq"].T + P[pre + ".bq"]
         kv = mem @ P[pre + ".wkv"].T + P[pre + ".bkv"]
-        ctx, ac = attention_fwd(q, kv[:, :d], kv[:, d:], self.shape.n_heads, False)
+        keep = self._attn_keep(site, 4, x.shape[0], mem.shape[0])
+        ctx, ac = attention_fwd(q, kv[:, :d], kv[:, d:], self.shape.n_heads, False, keep, self.cfg.attn_dropout)
         y = ctx @ P[pre + ".wo"].T + P[pre + ".bo"]
         return y, (x, mem, ctx, ac)
 
@@ -271,18 +311,27 @@ class OracleTransformer:
         g.add(pre + ".bkv", dkv.sum(axis=0))
         return dq @ P[pre + ".wq"], dkv @ P[pre + ".wkv"]
 
-    def _ffn_fwd(self, pre, x):
+    def _ffn_fwd(self, pre, x, site=None):
         P = self.p
         a = x @ P[pre + ".w1"].T + P[pre + ".b1"]
         h = np.maximum(a, 0.0)
-        return h @ P[pre + ".w2"].T + P[pre + ".b2"], (x, a, h)
+        keep, pr = None, self.cfg.relu_dropout
+        if pr > 0.0:                                             # inverted dropout on the hidden activations
+            stream, layer, row0 = site
+            key = dropout_key(self.cfg.seed, self._step, site_id(stream, layer, 5))
+            keep = dropout_keep(key, row0, h.shape[0], h.shape[1], pr)
+            h = np.where(keep, h / (1.0 - pr), 0.0)
+        return h @ P[pre + ".w2"].T + P[pre + ".b2"], (x, a, h, keep)
 
     def _ffn_bwd(self, pre, dy, cache, g):
         P = self.p
-        x, a, h = cache
+        x, a, h, keep = cache
         g.add(pre + ".w2", dy.T @ h)
         g.add(pre + ".b2", dy.sum(axis=0))
-        da = (dy @ P[pre + ".w2"]) * (a > 0.0)
+        dh = dy @ P[pre + ".w2"]
+        if keep is not None:
+            dh = np.where(keep, dh / (1.0 - self.cfg.relu_dropout), 0.0)
+        da = dh * (a > 0.0)
         g.add(pre + ".w1", da.T @ x)
         g.add(pre + ".b1", da.sum(axis=0))
         return da @ P[pre + ".w1"]
@@ -403,10 +452,10 @@ class OracleTransformer:
             for i in range(sh.enc_layers):
                 pre = f"enc.{i}"
                 x, c1 = self._block_fwd(pre + ".ln_self", x,
-                                        lambda u, pre=pre: self._self_attn_fwd(pre + ".self", u, False),
+                                        lambda u, pre=pre, i=i: self._self_attn_fwd(pre + ".self", u, False, (0, i, srow0)),
                                         (0, i, 0, srow0))
                 x, c2 = self._block_fwd(pre + ".ln_ffn", x,
-                                        lambda u, pre=pre: self._ffn_fwd(pre + ".ffn", u), (0, i, 2, srow0))
+                                        lambda u, pre=pre, i=i: self._ffn_fwd(pre + ".ffn", u, (0, i, srow0)), (0, i, 2, srow0))
                 caches.append((c1, c2))
             if sh.pre_norm:
                 x, enc_lnf = layer_norm_fwd(x, P["enc.ln_final.g"], P["enc.ln_final.b"])
@@ -416,14 +465,15 @@ class OracleTransformer:
         for i in range(sh.dec_layers):
             pre = f"dec.{i}"
             y, c1 = self._block_fwd(pre + ".ln_self", y,
-                                    lambda u, pre=pre: self._self_attn_fwd(pre + ".self", u, True), (1, i, 0, trow0))
+                                    lambda u, pre=pre, i=i: self._self_attn_fwd(pre + ".self", u, True, (1, i, trow0)),
+                                    (1, i, 0, trow0))
             c2 = None
             if sh.enc_layers:
                 y, c2 = self._block_fwd(pre + ".ln_cross", y,
-                                        lambda u, pre=pre: self._cross_attn_fwd(pre + ".cross", u, mem),
+                                        lambda u, pre=pre, i=i: self._cross_attn_fwd(pre + ".cross", u, mem, (1, i, trow0)),
                                         (1, i, 1, trow0))
             y, c3 = self._block_fwd(pre + ".ln_ffn", y,
-                                    lambda u, pre=pre: self._ffn_fwd(pre + ".ffn", u), (1, i, 2, trow0))
+                                    lambda u, pre=pre, i=i: self._ffn_fwd(pre + ".ffn", u, (1, i, trow0)), (1, i, 2, trow0))
             dcaches.append((c1, c2, c3))
         if sh.pre_norm:
             y, dec_lnf = layer_norm_fwd(y, P["dec.ln_final.g"], P["dec.ln_final.b"])

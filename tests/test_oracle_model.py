@@ -32,12 +32,15 @@ SHAPES = {
 
 
 @pytest.mark.parametrize("name", list(SHAPES))
-@pytest.mark.parametrize("dropout", [0.0, 0.3])
+@pytest.mark.parametrize("dropout", [(0.0, 0.0, 0.0), (0.3, 0.0, 0.0), (0.2, 0.25, 0.3), (0.0, 0.4, 0.0), (0.0, 0.0, 0.3)])
 def test_finite_differences(name, dropout):
+    """dropout = (sub-layer outputs and embeddings, attention weights, feed-forward hidden activations); the masks are
+    functions of (seed, step, site, index) only, so they stay frozen while a parameter is perturbed."""
     shape = SHAPES[name]
     params = init_params(shape, 11, generic=True)
     batch = small_batch(shape, 5, lm=shape.enc_layers == 0)
-    cfg = TrainConfig(dropout=dropout, label_smoothing=0.1, init_loss_scale=1.0, seed=3)
+    cfg = TrainConfig(dropout=dropout[0], attn_dropout=dropout[1], relu_dropout=dropout[2], label_smoothing=0.1,
+                      init_loss_scale=1.0, seed=3)
     o = OracleTransformer(shape, params, cfg)
     o.train_step(batch.src, batch.tgt, batch.src_lens, batch.tgt_lens)
     rng = np.random.default_rng(0)

@@ -126,6 +126,79 @@ def test_attention_backward_against_autograd():
     np.testing.assert_allclose(dv, tv.grad.numpy(), atol=1e-12)
 
 
+def test_attention_weight_dropout_against_autograd_and_special_cases():
+    """Dropout on the attention weights with a given keep mask: value and all three gradients against an autograd
+    graph built from library primitives (softmax, masked scaling, matmul); one key -> v / (1-p) or 0; an all-true mask
+    with p = 0 is the plain attention; dropped weights contribute nothing to dV."""
+    rng = np.random.default_rng(14)
+    n, m, d, H, pd = 5, 7, 8, 2, 0.3
+    q, k, v, do = (rng.normal(size=s) for s in [(n, d), (m, d), (m, d), (n, d)])
+    keep = [rng.random((n, m)) >= pd for _ in range(H)]
+    for causal in (False, True):
+        mm = n if causal else m
+        kk, vv = k[:mm], v[:mm]
+        kp = [x[:, :mm] for x in keep]
+        ctx, cache = T.attention_fwd(q, kk, vv, H, causal, kp, pd)
+        dq, dk, dv = T.attention_bwd(do, cache)
+        tq, tk, tv = (torch.tensor(a, requires_grad=True) for a in (q, kk, vv))
+        outs = []
+        for h in range(H):
+            sl = slice(h * d // H, (h + 1) * d // H)
+            sc = tq[:, sl] @ tk[:, sl].T / math.sqrt(d // H)
+            if causal:
+                sc = sc.masked_fill(torch.triu(torch.ones(n, mm, dtype=torch.bool), 1), float("-inf"))
+            w = torch.softmax(sc, dim=-1) * torch.tensor(kp[h], dtype=torch.float64) / (1.0 - pd)
+            outs.append(w @ tv[:, sl])
+        o = torch.cat(outs, dim=1)
+        np.testing.assert_allclose(ctx, o.detach().numpy(), atol=1e-12)
+        (o * torch.tensor(do)).sum().backward()
+        np.testing.assert_allclose(dq, tq.grad.numpy(), atol=1e-12)
+        np.testing.assert_allclose(dk, tk.grad.numpy(), atol=1e-12)
+        np.testing.assert_allclose(dv, tv.grad.numpy(), atol=1e-12)
+    # one key: the single weight is 1, so the output is v / (1-p) where it is kept and 0 where it is dropped
+    v1 = rng.normal(size=(1, d))
+    kp1 = [np.array([[True], [False], [True], [False], [True]]), np.array([[False], [False], [True], [True], [True]])]
+    ctx, _ = T.attention_fwd(q, rng.normal(size=(1, d)), v1, H, False, kp1, pd)
+    for h in range(H):
+        sl = slice(h * d // H, (h + 1) * d // H)
+        np.testing.assert_allclose(ctx[:, sl], np.where(kp1[h], v1[:, sl] / (1 - pd), 0.0), atol=1e-14)
+    # nothing dropped, p = 0: the plain attention, bit for bit
+    all_true = [np.ones((n, m), bool)] * H
+    a, _ = T.attention_fwd(q, k, v, H, False, all_true, 0.0)
+    b, _ = T.attention_fwd(q, k, v, H, False)
+    assert np.array_equal(a, b)
+    # a key dropped for every query receives no value gradient
+    kp = [np.ones((n, m), bool) for _ in range(H)]
+    for x in kp:
+        x[:, 2] = False
+    _, cache = T.attention_fwd(q, k, v, H, False, kp, pd)
+    assert not T.attention_bwd(do, cache)[2][2].any()
+
+
+def test_attention_keep_mask_generator():
+    key = T.dropout_key(9, 2, T.site_id(1, 0, 3))
+    p, H = 0.1, 4
+    masks = [T.attention_keep(key, 11, 300, H, h, 50, p) for h in range(H)]
+    allm = np.stack(masks)
+    p_eff = T.dropout_threshold(p) / 65536.0
+    assert abs((1.0 - allm.mean()) - p_eff) < 5 * math.sqrt(p_eff * (1 - p_eff) / allm.size)
+    assert T.attention_keep(key, 11, 4, H, 0, 50, 0.0).all()
+    # queries are addressed by their packed row: a window equals the same rows of the big mask; keys by their index
+    np.testing.assert_array_equal(T.attention_keep(key, 20, 5, H, 2, 50, p), masks[2][9:14])
+    np.testing.assert_array_equal(T.attention_keep(key, 11, 300, H, 1, 33, p), masks[1][:, :33])
+    assert (masks[0] != masks[1]).mean() > 0.1                      # heads draw different bits
+    # scalar re-computation with Python integers
+    M = (1 << 64) - 1
+    def mix(z):
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M
+        return z ^ (z >> 31)
+    for (i, h, j) in [(0, 0, 0), (7, 3, 49), (299, 1, 18), (100, 2, 5)]:
+        e = (((11 + i) * H + h) << 16) + j
+        w = mix((int(key) + (e >> 2) * 0x9E3779B97F4A7C15) & M)
+        assert bool(masks[h][i, j]) == (((w >> (16 * (e & 3))) & 0xFFFF) >= int(p * 65536))
+
+
 # ---- layer norm -------------------------------------------------------------------------------------------------
 def test_layer_norm_invariants_and_library():
     rng = np.random.default_rng(5)
