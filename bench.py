@@ -173,6 +173,8 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=1100)
     ap.add_argument("--profile-steps", type=int, default=3)
     ap.add_argument("--no-overlap", action="store_true", help="enqueue weight-gradient work on the main stream too")
+    ap.add_argument("--attn-dropout", type=float, default=0.0, help="dropout on the attention weights (the named workloads use 0)")
+    ap.add_argument("--relu-dropout", type=float, default=0.0, help="dropout on the feed-forward hidden activations (default 0)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -196,7 +198,8 @@ def main():
     max_tok = max(max(b.ntokens, 0 if b.src is None else int(b.src_lens.sum())) for b in batches)
     max_sent = max(len(b.tgt_lens) for b in batches)
     cfg = T.make_config(shape, precision=prec, max_sentences=max_sent, max_len=max_len, max_tokens=(max_tok + 63) // 64 * 64,
-                        dropout=dropout, init_loss_scale=scale, seed=0, label_smoothing=0.0 if shape.cutoffs else 0.1)
+                        dropout=dropout, init_loss_scale=scale, seed=0, label_smoothing=0.0 if shape.cutoffs else 0.1,
+                        attn_dropout=args.attn_dropout, relu_dropout=args.relu_dropout)
     ctx = T.Tfm(cfg)
     ctx.set_params(init_params(shape, 0))
     ctx.set_overlap(not args.no_overlap)
@@ -273,7 +276,7 @@ def main():
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": prec_name, "data": "synthetic",
            "config": {"workload": args.workload, "model": w["model"], "params": count_params(shape),
-                      "update_freq": k, "dropout": dropout, "side_stream": not args.no_overlap, "tokens_per_step": tokens / args.steps,
+                      "update_freq": k, "dropout": dropout, "attn_dropout": args.attn_dropout, "relu_dropout": args.relu_dropout, "side_stream": not args.no_overlap, "tokens_per_step": tokens / args.steps,
                       "loss_scale_end": st["loss_scale"], "num_updates": st["num_updates"]},
            "roofline": roofline}
     if not args.no_cpu_baseline:

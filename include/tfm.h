@@ -61,6 +61,8 @@ typedef struct {
   int32_t precision;        /* TFM_FP32 | TFM_FP16 (dynamic loss scaling) | TFM_BF16 (scale fixed at its initial value) */
   int32_t pre_norm;         /* 0: LayerNorm after each residual sum; 1: before each sub-layer + a final one  */
   float   dropout;          /* on embeddings and on each sub-layer output before the residual sum; [0, 1)    */
+  float   attn_dropout;     /* on the attention weights, after the softmax; [0, 1)                           */
+  float   relu_dropout;     /* on the feed-forward hidden activations, after the ReLU; [0, 1)                */
   float   label_smoothing;  /* eps in q = (1-eps) onehot + eps/V                                             */
   float   adam_beta1, adam_beta2, adam_eps;
   float   clip_norm;        /* 0 = off; else the unscaled gradient is scaled down to this L2 norm            */
@@ -174,10 +176,15 @@ int tfm_op_gemm(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K, co
 
 /* Same as tfm_op_gemm with a caller-owned fp32 device workspace.  With it the "TN" form without epilogue may split K
  * across blocks when the output has few tiles (weight gradients); partial tiles are added in a fixed order, so the
- * result stays reproducible.  workspace may be NULL (then identical to tfm_op_gemm). */
+ * result stays reproducible.  workspace may be NULL (then identical to tfm_op_gemm).
+ * Two more epilogue steps, as the feed-forward layer with dropout on its hidden activations needs them: drop_p > 0
+ * applies inverted dropout after bias and ReLU (element m * N + n of the counter-based generator with key drop_key,
+ * kept values multiplied by 1 / (1 - drop_p)); with mask, the kept elements are also multiplied by mask_scale (pass 1
+ * otherwise). */
 int tfm_op_gemm_ws(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K, const void* A, int32_t lda,
                    const void* B, int32_t ldb, void* C, int32_t ldc, const void* bias, int32_t relu,
-                   const void* mask, const void* residual, void* workspace, size_t workspace_bytes, void* stream);
+                   const void* mask, const void* residual, void* workspace, size_t workspace_bytes, uint64_t drop_key,
+                   float drop_p, float mask_scale, void* stream);
 
 /* Grouped weight gradients, the form every linear layer's backward pass ends in (accumulated gradients of Implementation,
  * Multi-GPU training, are sums of exactly these): for i < n (n <= 48), C_i[M_i, N_i] = A_i^T B_i with A_i[K_i, M_i],
@@ -190,17 +197,20 @@ int tfm_op_wgrad_grouped(int32_t dtype, int32_t n, const int32_t* dims, const vo
 
 /* Multi-head attention over packed sentences.  q rows of sentence b are q_off[b]..q_off[b+1], keys/values
  * k_off[b]..k_off[b+1] (device int32 [B+1]).  Head h uses columns h*dh..(h+1)*dh.  o = softmax(q k^T/sqrt(dh)
- * [+ causal mask]) v; lse (device fp32 [H, q_off[B]]) receives the row log-sum-exp of the scaled scores. */
+ * [+ causal mask]) v; lse (device fp32 [H, q_off[B]]) receives the row log-sum-exp of the scaled scores.
+ * drop_p > 0: inverted dropout on the attention weights; weight (packed query row i, head h, key j of the sentence)
+ * uses element ((i * H + h) << 16) + j of the counter-based generator with key drop_key.  The backward call must be
+ * given the same key and probability. */
 int tfm_op_attention_fwd(int32_t dtype, const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v,
                          int32_t ldv, void* o, int32_t ldo, float* lse, const int32_t* q_off, const int32_t* k_off,
                          int32_t B, int32_t H, int32_t dh, int32_t max_lq, int32_t max_lk, int32_t total_q,
-                         int32_t causal, void* stream);
+                         int32_t causal, uint64_t drop_key, float drop_p, void* stream);
 int tfm_op_attention_bwd(int32_t dtype, const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v,
                          int32_t ldv, const void* o, int32_t ldo, const void* d_o, int32_t lddo, const float* lse,
                          void* dq, int32_t lddq, void* dk, int32_t lddk, void* dv, int32_t lddv,
                          const int32_t* q_off, const int32_t* k_off, int32_t B, int32_t H, int32_t dh,
                          int32_t max_lq, int32_t max_lk, int32_t total_q, int32_t total_k, int32_t causal,
-                         void* stream);
+                         uint64_t drop_key, float drop_p, void* stream);
 
 /* s = x + dropout(y) (y may be NULL: s = x), n = gamma * (s - mean)/sqrt(var + 1e-5) + beta.  [rows, d], contiguous.
  * s_out may be NULL.  mean, rstd: device fp32 [rows].  gamma/beta in `dtype`.  dropout: keep bits from (key, p). */

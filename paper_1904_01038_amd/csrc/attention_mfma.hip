@@ -68,7 +68,16 @@ struct AttnP {
   const int *q_off, *k_off;
   int total_q, causal;
   float scale;
+  // dropout on the attention weights (drop_thr = 0: off): weight (packed query row i, head h, key j) uses element
+  // ((i * H + h) << 16) + j of the counter-based generator; one 64-bit word serves four consecutive keys
+  uint64_t drop_key;
+  uint32_t drop_thr;
+  float inv_keep;
+  int H;
 };
+__device__ __forceinline__ uint64_t attn_drop_word(const AttnP& p, int qrow, int h, int j) {
+  return drop_word(p.drop_key, ((((uint64_t)qrow * (uint64_t)p.H + (uint64_t)h) << 16) + (uint64_t)j) >> 2);
+}
 
 // rows r0..r0+31 of a staged tile as an MFMA operand: lane -> row r0 + lane%32, columns kk*16 + (lane/32)*8 .. +8
 template <int P = PT>
@@ -176,7 +185,7 @@ __device__ __forceinline__ void store_rows(uint16_t* __restrict__ G, int ld, int
 }
 
 // ---- forward ------------------------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, bool DROP>
 __global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_kernel(AttnP p, int H) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[CH * PT];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[CH * PT];
@@ -237,6 +246,14 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_
       float ps = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[r] = __expf(s[r] - mn); ps += s[r]; }
+      if (DROP) {                                    // the row sum keeps every weight; only the weights that average V are dropped
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint64_t w = attn_drop_word(p, q0 + qi, h, j0 + 8 * g + 4 * half);
+#pragma unroll
+          for (int f = 0; f < 4; ++f) s[g * 4 + f] = drop_keep(w, f, p.drop_thr) ? s[g * 4 + f] * p.inv_keep : 0.f;
+        }
+      }
       lsum = lsum * alpha + ps;
       m = mn;
 #pragma unroll
@@ -261,7 +278,7 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_
 }
 
 // ---- backward: dQ ---------------------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, bool DROP>
 __device__ __forceinline__ void attn_bwd_dq_body(const AttnP& p, int b, int h, int chunk, uint16_t* Ks, uint16_t* Vs) {
   const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;
   const int qstart = chunk * 64;
@@ -311,11 +328,17 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnP& p, int b, int h, i
         dp = AMfma<T>::run(frag_direct(Vs, kb * 32, kk, lane), gf[kk], dp);
       }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const bool ok = j < lk && qi < lq && (!p.causal || j <= qi);
-        const float pr = ok ? __expf(s[r] * p.scale - L) : 0.f;
-        s[r] = pr * (dp[r] - delta);
+      for (int g = 0; g < 4; ++g) {
+        const uint64_t w = DROP ? attn_drop_word(p, q0 + qi, h, j0 + 8 * g + 4 * half) : 0;
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+          const int r = g * 4 + f;
+          const int j = j0 + 8 * g + 4 * half + f;
+          const bool ok = j < lk && qi < lq && (!p.causal || j <= qi);
+          const float pr = ok ? __expf(s[r] * p.scale - L) : 0.f;
+          const float dpd = !DROP ? dp[r] : (drop_keep(w, f, p.drop_thr) ? dp[r] * p.inv_keep : 0.f);   // d/d(softmax output)
+          s[r] = pr * (dpd - delta);
+        }
       }
       u32x4 df[2];
 #pragma unroll
@@ -335,7 +358,7 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnP& p, int b, int h, i
 }
 
 // ---- backward: dK, dV -------------------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, bool DROP>
 __device__ __forceinline__ void attn_bwd_dkv_body(const AttnP& p, int b, int h, int chunk, uint16_t* Qs, uint16_t* Gs, float* Ls, float* Ds) {
   const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;
   const int kstart = chunk * 64;
@@ -406,7 +429,15 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnP& p, int b, int h, 
           const int i = qc + il + e;
           const bool ok = i < lq && kj < lk && (!p.causal || kj <= i);
           pr[e] = ok ? __expf(s[rg * 4 + e] * p.scale - lv[e]) : 0.f;
-          dsv[e] = pr[e] * (dp[rg * 4 + e] - dv[e]);
+          float dpd = dp[rg * 4 + e];
+          if (DROP) {                                  // this lane's key, one query per register: a word per element
+            const bool keep = drop_keep(attn_drop_word(p, q0 + i, h, kj), kj & 3, p.drop_thr);
+            dpd = keep ? dpd * p.inv_keep : 0.f;
+            dsv[e] = pr[e] * (dpd - dv[e]);
+            pr[e] = keep ? pr[e] * p.inv_keep : 0.f;  // dV averages dO with the dropped weights
+          } else {
+            dsv[e] = pr[e] * (dpd - dv[e]);
+          }
         }
         pf[rg >> 1][(rg & 1) * 2] = AMfma<T>::pack2(pr[0], pr[1]);
         pf[rg >> 1][(rg & 1) * 2 + 1] = AMfma<T>::pack2(pr[2], pr[3]);
@@ -435,7 +466,7 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnP& p, int b, int h, 
 // (sentence, head) pairs and y the chunks in the order of decreasing work under a causal mask (dK/dV of key chunk c loops
 // over n - c query chunks, dQ of query chunk c over c + 1 key chunks), so the longest blocks of the whole launch start
 // first and the short ones fill the tail.
-template <typename T>
+template <typename T, bool DROP>
 __global__ __launch_bounds__(ATT_THREADS, ATT_BWD_MIN_WAVES) void attn_bwd_mfma_kernel(AttnP p, int nq_chunks, int nk_chunks, int H) {
   __shared__ __attribute__((aligned(16))) uint16_t S0[CH * PT];
   __shared__ __attribute__((aligned(16))) uint16_t S1[CH * PT];
@@ -449,8 +480,8 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_BWD_MIN_WAVES) void attn_bwd_mfma_
   if (r < 2 * pairs) { is_dq = r & 1; chunk = is_dq ? nq_chunks - 1 - (r >> 1) : (r >> 1); }
   else if (nq_chunks > nk_chunks) { is_dq = true; chunk = nq_chunks - 1 - (r - pairs); }
   else { is_dq = false; chunk = r - pairs; }
-  if (is_dq) attn_bwd_dq_body<T>(p, b, h, chunk, S0, S1);
-  else attn_bwd_dkv_body<T>(p, b, h, chunk, S0, S1, Ls, Ds);
+  if (is_dq) attn_bwd_dq_body<T, DROP>(p, b, h, chunk, S0, S1);
+  else attn_bwd_dkv_body<T, DROP>(p, b, h, chunk, S0, S1, Ls, Ds);
 }
 
 // ---- backward, sentences of at most 64 tokens: dQ, dK and dV of a (sentence, head) in one block --------------------------
@@ -463,7 +494,7 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_BWD_MIN_WAVES) void attn_bwd_mfma_
 // bytes cover the 64 banks once) keep four blocks resident per CU.
 constexpr int PF = 72;
 
-template <typename T>
+template <typename T, bool DROP>
 __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[CH * PF];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[CH * PF];
@@ -523,11 +554,17 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p
         dp = AMfma<T>::run(frag_direct<PF>(Vs, j0, kk, lane), frag_direct<PF>(Gs, own0, kk, lane), dp);
       }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int jj = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const bool ok = jj < lk && own < lq && (!p.causal || jj <= own);
-        const float pr = ok ? __expf(s[r] * p.scale - L) : 0.f;
-        s[r] = pr * (dp[r] - delta);
+      for (int g = 0; g < 4; ++g) {
+        const uint64_t w = DROP ? attn_drop_word(p, q0 + own, h, j0 + 8 * g + 4 * half) : 0;
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+          const int r = g * 4 + f;
+          const int jj = j0 + 8 * g + 4 * half + f;
+          const bool ok = jj < lk && own < lq && (!p.causal || jj <= own);
+          const float pr = ok ? __expf(s[r] * p.scale - L) : 0.f;
+          const float dpd = !DROP ? dp[r] : (drop_keep(w, f, p.drop_thr) ? dp[r] * p.inv_keep : 0.f);
+          s[r] = pr * (dpd - delta);
+        }
       }
       u32x4 df[2];
 #pragma unroll
@@ -568,7 +605,15 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p
           const int i = il + e;
           const bool ok = i < lq && own < lk && (!p.causal || own <= i);
           pr[e] = ok ? __expf(s[rg * 4 + e] * p.scale - lv[e]) : 0.f;
-          dsv[e] = pr[e] * (dp[rg * 4 + e] - dv[e]);
+          float dpd = dp[rg * 4 + e];
+          if (DROP) {
+            const bool keep = drop_keep(attn_drop_word(p, q0 + i, h, own), own & 3, p.drop_thr);
+            dpd = keep ? dpd * p.inv_keep : 0.f;
+            dsv[e] = pr[e] * (dpd - dv[e]);
+            pr[e] = keep ? pr[e] * p.inv_keep : 0.f;
+          } else {
+            dsv[e] = pr[e] * (dpd - dv[e]);
+          }
         }
         pf[rg >> 1][(rg & 1) * 2] = AMfma<T>::pack2(pr[0], pr[1]);
         pf[rg >> 1][(rg & 1) * 2 + 1] = AMfma<T>::pack2(pr[2], pr[3]);
@@ -615,28 +660,49 @@ static AttnP make_params(const AttnArgs& a) {
   p.ldq = a.ldq; p.ldk = a.ldk; p.ldv = a.ldv; p.ldo = a.ldo; p.lddo = a.lddo; p.lddq = a.lddq; p.lddk = a.lddk; p.lddv = a.lddv;
   p.lse = a.lse; p.q_off = a.q_off; p.k_off = a.k_off; p.total_q = a.total_q; p.causal = a.causal;
   p.scale = 1.f / sqrtf((float)a.dh);
+  p.drop_key = a.drop_key;
+  p.drop_thr = a.drop_p > 0.f ? drop_threshold(a.drop_p) : 0u;
+  p.inv_keep = 1.f / (1.f - a.drop_p);
+  p.H = a.H;
   return p;
 }
 
 void launch_attention_fwd_mfma(hipStream_t s, const AttnArgs& a) {
   const AttnP p = make_params(a);
   dim3 grid(a.H * a.B, (a.max_lq + 63) / 64), block(ATT_THREADS);
-  if (a.dt == F16) hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t>), grid, block, 0, s, p, a.H);
-  else hipLaunchKernelGGL((attn_fwd_mfma_kernel<bf16_t>), grid, block, 0, s, p, a.H);
+  const bool drop = p.drop_thr != 0;
+  if (a.dt == F16) {
+    if (drop) hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t, true>), grid, block, 0, s, p, a.H);
+    else hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t, false>), grid, block, 0, s, p, a.H);
+  } else {
+    if (drop) hipLaunchKernelGGL((attn_fwd_mfma_kernel<bf16_t, true>), grid, block, 0, s, p, a.H);
+    else hipLaunchKernelGGL((attn_fwd_mfma_kernel<bf16_t, false>), grid, block, 0, s, p, a.H);
+  }
 }
 
 void launch_attention_bwd_mfma(hipStream_t s, const AttnArgs& a) {
   const AttnP p = make_params(a);
   const int nq = (a.max_lq + 63) / 64, nk = (a.max_lk + 63) / 64;
+  const bool drop = p.drop_thr != 0;
   if (nq == 1 && nk == 1) {                              // every sentence fits one chunk: one block per (sentence, head)
     dim3 grid(1, a.H, a.B), block(ATT_THREADS);
-    if (a.dt == F16) hipLaunchKernelGGL((attn_bwd_single_kernel<half_t>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((attn_bwd_single_kernel<bf16_t>), grid, block, 0, s, p);
+    if (a.dt == F16) {
+      if (drop) hipLaunchKernelGGL((attn_bwd_single_kernel<half_t, true>), grid, block, 0, s, p);
+      else hipLaunchKernelGGL((attn_bwd_single_kernel<half_t, false>), grid, block, 0, s, p);
+    } else {
+      if (drop) hipLaunchKernelGGL((attn_bwd_single_kernel<bf16_t, true>), grid, block, 0, s, p);
+      else hipLaunchKernelGGL((attn_bwd_single_kernel<bf16_t, false>), grid, block, 0, s, p);
+    }
     return;
   }
   dim3 grid(a.H * a.B, nq + nk), block(ATT_THREADS);
-  if (a.dt == F16) hipLaunchKernelGGL((attn_bwd_mfma_kernel<half_t>), grid, block, 0, s, p, nq, nk, a.H);
-  else hipLaunchKernelGGL((attn_bwd_mfma_kernel<bf16_t>), grid, block, 0, s, p, nq, nk, a.H);
+  if (a.dt == F16) {
+    if (drop) hipLaunchKernelGGL((attn_bwd_mfma_kernel<half_t, true>), grid, block, 0, s, p, nq, nk, a.H);
+    else hipLaunchKernelGGL((attn_bwd_mfma_kernel<half_t, false>), grid, block, 0, s, p, nq, nk, a.H);
+  } else {
+    if (drop) hipLaunchKernelGGL((attn_bwd_mfma_kernel<bf16_t, true>), grid, block, 0, s, p, nq, nk, a.H);
+    else hipLaunchKernelGGL((attn_bwd_mfma_kernel<bf16_t, false>), grid, block, 0, s, p, nq, nk, a.H);
+  }
 }
 
 }  // namespace tfm

@@ -8,13 +8,21 @@ namespace tfm {
 
 constexpr int AN_THREADS = 128;
 
+// Dropout on the attention weights (thr = 0: off): weight (packed query row, head h, key j) uses element
+// ((row * H + h) << 16) + j of the counter-based generator.
+struct AttnDrop { uint64_t key; uint32_t thr; float inv_keep; int H; };
+__device__ __forceinline__ bool attn_keep(const AttnDrop& d, int qrow, int h, int j) {
+  const uint64_t e = (((uint64_t)qrow * (uint64_t)d.H + (uint64_t)h) << 16) + (uint64_t)j;
+  return drop_keep(drop_word(d.key, e >> 2), (int)(e & 3), d.thr);
+}
+
 // grid: (max_lq, H, B).  LDS: q row [dh] + scores [max_lk].
 template <typename T>
 __global__ __launch_bounds__(AN_THREADS) void attn_fwd_naive_kernel(const T* __restrict__ q, int ldq, const T* __restrict__ k, int ldk,
                                                                     const T* __restrict__ v, int ldv, T* __restrict__ o, int ldo,
                                                                     float* __restrict__ lse, const int* __restrict__ q_off,
                                                                     const int* __restrict__ k_off, int dh, int total_q, int causal,
-                                                                    float scale) {
+                                                                    float scale, AttnDrop drop) {
   extern __shared__ float lds[];
   __shared__ float sh[16];
   const int b = blockIdx.z, h = blockIdx.y, i = blockIdx.x;
@@ -36,7 +44,11 @@ __global__ __launch_bounds__(AN_THREADS) void attn_fwd_naive_kernel(const T* __r
   }
   const float m = block_max(lmax, sh);
   float se = 0.f;
-  for (int j = threadIdx.x; j < nk; j += AN_THREADS) { const float e = __expf(sc[j] - m); sc[j] = e; se += e; }
+  for (int j = threadIdx.x; j < nk; j += AN_THREADS) {
+    const float e = __expf(sc[j] - m);
+    se += e;                                         // the row sum keeps every weight; only those that average V are dropped
+    sc[j] = !drop.thr ? e : (attn_keep(drop, q0 + i, h, j) ? e * drop.inv_keep : 0.f);
+  }
   se = block_sum(se, sh);
   __syncthreads();
   const float inv = 1.f / se;
@@ -53,7 +65,7 @@ template <typename T>
 __global__ __launch_bounds__(AN_THREADS) void attn_bwd_dq_naive_kernel(
     const T* __restrict__ q, int ldq, const T* __restrict__ k, int ldk, const T* __restrict__ v, int ldv, const T* __restrict__ o,
     int ldo, const T* __restrict__ d_o, int lddo, const float* __restrict__ lse, T* __restrict__ dq, int lddq,
-    const int* __restrict__ q_off, const int* __restrict__ k_off, int dh, int total_q, int causal, float scale) {
+    const int* __restrict__ q_off, const int* __restrict__ k_off, int dh, int total_q, int causal, float scale, AttnDrop drop) {
   extern __shared__ float lds[];
   __shared__ float sh[16];
   const int b = blockIdx.z, h = blockIdx.y, i = blockIdx.x;
@@ -79,6 +91,7 @@ __global__ __launch_bounds__(AN_THREADS) void attn_bwd_dq_naive_kernel(
     float s = 0.f, dp = 0.f;
     for (int c = 0; c < dh; ++c) { s += qs[c] * to_f<T>(kr[c]); dp += dos[c] * to_f<T>(vr[c]); }
     const float p = __expf(s * scale - L);
+    if (drop.thr) dp = attn_keep(drop, q0 + i, h, j) ? dp * drop.inv_keep : 0.f;
     dsv[j] = p * (dp - delta);
   }
   __syncthreads();
@@ -95,7 +108,7 @@ __global__ __launch_bounds__(AN_THREADS) void attn_bwd_dkv_naive_kernel(
     const T* __restrict__ q, int ldq, const T* __restrict__ k, int ldk, const T* __restrict__ v, int ldv, const T* __restrict__ o,
     int ldo, const T* __restrict__ d_o, int lddo, const float* __restrict__ lse, T* __restrict__ dk, int lddk, T* __restrict__ dv,
     int lddv, const int* __restrict__ q_off, const int* __restrict__ k_off, int dh, int total_q, int max_lq, int causal,
-    float scale) {
+    float scale, AttnDrop drop) {
   extern __shared__ float lds[];
   const int b = blockIdx.z, h = blockIdx.y, j = blockIdx.x;
   const int q0 = q_off[b], lq = q_off[b + 1] - q0, k0 = k_off[b], lk = k_off[b + 1] - k0;
@@ -122,7 +135,9 @@ __global__ __launch_bounds__(AN_THREADS) void attn_bwd_dkv_naive_kernel(
       delta += g * to_f<T>(orow[c]);
     }
     const float p = __expf(s * scale - lse[(size_t)h * total_q + q0 + i]);
-    ps[i] = p;
+    const bool keep = !drop.thr || attn_keep(drop, q0 + i, h, j);
+    if (drop.thr) dp = keep ? dp * drop.inv_keep : 0.f;
+    ps[i] = !drop.thr ? p : (keep ? p * drop.inv_keep : 0.f);      // dV averages dO with the dropped weights
     dss[i] = p * (dp - delta);
   }
   __syncthreads();
@@ -137,13 +152,16 @@ __global__ __launch_bounds__(AN_THREADS) void attn_bwd_dkv_naive_kernel(
   }
 }
 
+static AttnDrop make_drop(const AttnArgs& a) {
+  return AttnDrop{a.drop_key, a.drop_p > 0.f ? drop_threshold(a.drop_p) : 0u, 1.f / (1.f - a.drop_p), a.H};
+}
 template <typename T>
 static void attn_fwd_naive(hipStream_t s, const AttnArgs& a) {
   const float scale = 1.f / sqrtf((float)a.dh);
   dim3 grid(a.max_lq, a.H, a.B), block(AN_THREADS);
   const size_t shm = (size_t)(a.dh + a.max_lk) * sizeof(float);
   hipLaunchKernelGGL((attn_fwd_naive_kernel<T>), grid, block, shm, s, (const T*)a.q, a.ldq, (const T*)a.k, a.ldk, (const T*)a.v,
-                     a.ldv, (T*)a.o, a.ldo, a.lse, a.q_off, a.k_off, a.dh, a.total_q, a.causal, scale);
+                     a.ldv, (T*)a.o, a.ldo, a.lse, a.q_off, a.k_off, a.dh, a.total_q, a.causal, scale, make_drop(a));
 }
 template <typename T>
 static void attn_bwd_naive(hipStream_t s, const AttnArgs& a) {
@@ -153,14 +171,14 @@ static void attn_bwd_naive(hipStream_t s, const AttnArgs& a) {
     const size_t shm = (size_t)(2 * a.dh + a.max_lk) * sizeof(float);
     hipLaunchKernelGGL((attn_bwd_dq_naive_kernel<T>), grid, block, shm, s, (const T*)a.q, a.ldq, (const T*)a.k, a.ldk,
                        (const T*)a.v, a.ldv, (const T*)a.o, a.ldo, (const T*)a.d_o, a.lddo, a.lse, (T*)a.dq, a.lddq, a.q_off,
-                       a.k_off, a.dh, a.total_q, a.causal, scale);
+                       a.k_off, a.dh, a.total_q, a.causal, scale, make_drop(a));
   }
   {
     dim3 grid(a.max_lk, a.H, a.B), block(AN_THREADS);
     const size_t shm = (size_t)(2 * a.dh + 2 * a.max_lq) * sizeof(float);
     hipLaunchKernelGGL((attn_bwd_dkv_naive_kernel<T>), grid, block, shm, s, (const T*)a.q, a.ldq, (const T*)a.k, a.ldk,
                        (const T*)a.v, a.ldv, (const T*)a.o, a.ldo, (const T*)a.d_o, a.lddo, a.lse, (T*)a.dk, a.lddk, (T*)a.dv,
-                       a.lddv, a.q_off, a.k_off, a.dh, a.total_q, a.max_lq, a.causal, scale);
+                       a.lddv, a.q_off, a.k_off, a.dh, a.total_q, a.max_lq, a.causal, scale, make_drop(a));
   }
 }
 

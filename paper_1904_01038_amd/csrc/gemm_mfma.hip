@@ -70,6 +70,8 @@ struct MfmaGemmParams {
   int ksteps_per_split;                                  // split-K: K-steps per blockIdx.y slice
   float* partial;                                        // split-K: fp32 partial tiles [split][M][N], else null
   uint32_t a_bytes, b_bytes;                             // extents for the range-checked loads
+  uint64_t drop_key; uint32_t drop_thr; float inv_keep;  // dropout on the result (thr = 0: off), see GemmArgs
+  float mask_scale;
   uint16_t* colsum;                                      // grouped weight gradients: [M] sums of A's rows over K (a bias gradient), or null
 };
 
@@ -357,12 +359,13 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaGemmParams& p, int tile
 #pragma unroll
           for (int e = 0; e < 8; ++e) w[e] = fmaxf(w[e], 0.f);
         }
+        if (p.drop_thr) drop_apply<8>(w, p.drop_key, (uint64_t)m * p.N + nn, p.drop_thr, p.inv_keep);
         const size_t o = (size_t)m * p.ldc + nn;
         if (mask) {
           float k[8];
           load_f<T, 8>(mask + o, k);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) w[e] = k[e] > 0.f ? w[e] : 0.f;
+          for (int e = 0; e < 8; ++e) w[e] = k[e] > 0.f ? w[e] * p.mask_scale : 0.f;
         }
         if (res) {
           float k[8];
@@ -419,6 +422,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4) ? 2 : 1) void gemm_mfm
   p.partial = nullptr;
   p.a_bytes = g.a_bytes; p.b_bytes = g.b_bytes;
   p.colsum = g.colsum;
+  p.drop_key = 0; p.drop_thr = 0; p.inv_keep = 1.f; p.mask_scale = 1.f;
   gemm_mfma_tile<T, BM, BN, WM, WN, BK, STAGES, true, true, true>(p, tile - g.tile_begin, 0);
 }
 
@@ -480,6 +484,8 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   p.A = (const uint16_t*)a.A; p.lda = a.lda; p.B = (const uint16_t*)a.B; p.ldb = a.ldb; p.C = (uint16_t*)a.C; p.ldc = a.ldc;
   p.bias = (const uint16_t*)a.bias; p.relu = a.relu; p.mask = (const uint16_t*)a.mask; p.residual = (const uint16_t*)a.residual;
   p.colsum = nullptr;
+  p.drop_key = a.drop_key; p.drop_thr = a.drop_p > 0.f ? drop_threshold(a.drop_p) : 0u; p.inv_keep = 1.f / (1.f - a.drop_p);
+  p.mask_scale = a.mask_scale;
   p.tiles_n = (a.N + BN - 1) / BN;
   p.tiles_m = (a.M + BM - 1) / BM;
   p.tiles_total = p.tiles_n * p.tiles_m;
@@ -493,10 +499,10 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   // blockIdx.y, fp32 partial tiles go to the caller's workspace and are added in a fixed order.
   const int nk = (a.K + BK - 1) / BK;
   int splits = 1;
-  if (a.form == 2 && a.splitk_ws && !a.bias && !a.relu && !a.mask && !a.residual && p.tiles_total <= 128 && nk >= 32) {
+  if (a.form == 2 && a.splitk_ws && !a.bias && !a.relu && !a.mask && !a.residual && !p.drop_thr && p.tiles_total <= 128 && nk >= 32) {
     splits = 256 / p.tiles_total;
     if (splits > 8) splits = 8;
-  } else if (a.form == 0 && BM == 64 && a.splitk_ws && !a.mask && !a.residual && p.tiles_total <= 128 && nk >= 8) {
+  } else if (a.form == 0 && BM == 64 && a.splitk_ws && !a.mask && !a.residual && !p.drop_thr && p.tiles_total <= 128 && nk >= 8) {
     // X W^T with few rows (a decoding step): the weights stream through more CUs; every slice keeps >= 4 K-steps and
     // bias / ReLU move into the reduction
     splits = std::min(std::min(256 / p.tiles_total, nk / 4), 8);

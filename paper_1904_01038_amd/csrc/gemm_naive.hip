@@ -10,7 +10,8 @@ template <typename T, int FORM>
 __global__ __launch_bounds__(256) void gemm_naive_kernel(int M, int N, int K, const T* __restrict__ A, int lda,
                                                          const T* __restrict__ B, int ldb, T* __restrict__ C, int ldc,
                                                          const T* __restrict__ bias, int relu, const T* __restrict__ mask,
-                                                         const T* __restrict__ residual) {
+                                                         const T* __restrict__ residual, uint64_t drop_key, uint32_t drop_thr,
+                                                         float inv_keep, float mask_scale) {
   __shared__ float As[16][64 + 1];
   __shared__ float Bs[16][64 + 1];
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -57,8 +58,12 @@ __global__ __launch_bounds__(256) void gemm_naive_kernel(int M, int N, int K, co
       float v = acc[i][j];
       if (bias) v += to_f<T>(bias[gn]);
       if (relu) v = fmaxf(v, 0.f);
+      if (drop_thr) {
+        const uint64_t e = (uint64_t)gm * N + gn;
+        v = drop_keep(drop_word(drop_key, e >> 2), (int)(e & 3), drop_thr) ? v * inv_keep : 0.f;
+      }
       const size_t o = (size_t)gm * ldc + gn;
-      if (mask && !(to_f<T>(mask[o]) > 0.f)) v = 0.f;
+      if (mask) v = to_f<T>(mask[o]) > 0.f ? v * mask_scale : 0.f;
       if (residual) v += to_f<T>(residual[o]);
       C[o] = from_f<T>(v);
     }
@@ -68,9 +73,11 @@ __global__ __launch_bounds__(256) void gemm_naive_kernel(int M, int N, int K, co
 template <typename T>
 static void gemm_naive_dispatch(hipStream_t s, const GemmArgs& a) {
   dim3 grid((a.N + 63) / 64, (a.M + 63) / 64), block(256);
+  const uint32_t thr = a.drop_p > 0.f ? drop_threshold(a.drop_p) : 0u;
 #define GN(F)                                                                                                          \
   hipLaunchKernelGGL((gemm_naive_kernel<T, F>), grid, block, 0, s, a.M, a.N, a.K, (const T*)a.A, a.lda, (const T*)a.B, a.ldb, \
-                     (T*)a.C, a.ldc, (const T*)a.bias, a.relu, (const T*)a.mask, (const T*)a.residual)
+                     (T*)a.C, a.ldc, (const T*)a.bias, a.relu, (const T*)a.mask, (const T*)a.residual, a.drop_key, thr,  \
+                     1.f / (1.f - a.drop_p), a.mask_scale)
   if (a.form == 0) GN(0); else if (a.form == 1) GN(1); else GN(2);
 #undef GN
 }

@@ -42,6 +42,11 @@ struct GemmArgs {
   const void* residual;      // [M, N] stride ldc or null: added last (must not alias C)
   void* splitk_ws = nullptr; // optional fp32 workspace that allows split-K for small weight-gradient outputs
   size_t splitk_ws_bytes = 0;
+  // Inverted dropout on the result (after bias and ReLU, before mask and residual): element m * N + n is kept when its
+  // counter-based bit says so (see common.h) and multiplied by 1 / (1 - drop_p).  drop_p = 0: off.
+  uint64_t drop_key = 0;
+  float drop_p = 0.f;
+  float mask_scale = 1.f;    // with mask: the kept elements are also multiplied by this (the dropout scale of the masked layer)
 };
 void launch_gemm(hipStream_t s, const GemmArgs& a);
 bool gemm_mfma_supported(const GemmArgs& a);
@@ -71,6 +76,11 @@ struct AttnArgs {
   // backward only
   const void* d_o; int lddo;
   void *dq, *dk, *dv; int lddq, lddk, lddv;
+  // Inverted dropout on the attention weights: weight (query row i of the packed stream, head h, key j of the sentence)
+  // uses element ((i * H + h) << 16) + j of the counter-based generator (see common.h); drop_p = 0: off.  Forward and
+  // backward regenerate the same bits from the key.
+  uint64_t drop_key = 0;
+  float drop_p = 0.f;
 };
 void launch_attention_fwd(hipStream_t s, const AttnArgs& a);
 void launch_attention_bwd(hipStream_t s, const AttnArgs& a);

@@ -278,6 +278,8 @@ int validate(const tfm_config& c, char* msg) {
   if (c.precision < 0 || c.precision > 2) BAD("precision must be 0, 1 or 2");
   if (c.pre_norm != 0 && c.pre_norm != 1) BAD("pre_norm must be 0 or 1");
   if (!(c.dropout >= 0.f && c.dropout < 1.f)) BAD("dropout must be in [0, 1)");
+  if (!(c.attn_dropout >= 0.f && c.attn_dropout < 1.f)) BAD("attn_dropout must be in [0, 1)");
+  if (!(c.relu_dropout >= 0.f && c.relu_dropout < 1.f)) BAD("relu_dropout must be in [0, 1)");
   if (!(c.label_smoothing >= 0.f && c.label_smoothing < 1.f)) BAD("label_smoothing must be in [0, 1)");
   if (!(c.adam_beta1 >= 0.f && c.adam_beta1 < 1.f && c.adam_beta2 >= 0.f && c.adam_beta2 < 1.f && c.adam_eps > 0.f)) BAD("bad Adam constants");
   if (!(c.clip_norm >= 0.f)) BAD("clip_norm must be >= 0");
@@ -480,9 +482,11 @@ inline void* wh(tfm_ctx* c, int i) { return (char*)c->Wh + c->params[i].off * c-
 inline void* gr(tfm_ctx* c, int i) { return (char*)c->g + c->params[i].off * c->esz; }
 
 void gemm(tfm_ctx* c, int form, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C, int ldc,
-          const void* bias = nullptr, int relu = 0, const void* mask = nullptr, const void* residual = nullptr, bool side = false) {
+          const void* bias = nullptr, int relu = 0, const void* mask = nullptr, const void* residual = nullptr, bool side = false,
+          uint64_t drop_key = 0, float drop_p = 0.f, float mask_scale = 1.f) {
   if (M <= 0 || N <= 0) return;
   GemmArgs a{c->dt, form, M, N, K, A, lda, B, ldb, C, ldc, bias, relu, mask, residual};
+  a.drop_key = drop_key; a.drop_p = drop_p; a.mask_scale = mask_scale;
   side = side && c->overlap;
   hipStream_t stream = side ? c->side : c->stream;
   a.splitk_ws = side ? c->splitk_ws_side : c->splitk_ws;
@@ -821,8 +825,8 @@ uint64_t block_key(const StepCtx& s, const Stream& st, int k) {
 
 void attention(const StepCtx& s, bool bwd, const Stream& qs, const Stream& ks, const std::vector<int>& lq,
                const std::vector<int>& lk, const void* q, int ldq, const void* k, int ldk, const void* v, int ldv, void* o,
-               float* lse, bool causal, const void* d_o = nullptr, void* dq = nullptr, int lddq = 0, void* dk = nullptr,
-               int lddk = 0, void* dv = nullptr, int lddv = 0) {
+               float* lse, bool causal, uint64_t drop_key, const void* d_o = nullptr, void* dq = nullptr, int lddq = 0,
+               void* dk = nullptr, int lddk = 0, void* dv = nullptr, int lddv = 0) {
   tfm_ctx* c = s.c;
   const int d = c->cfg.d_model, H = c->cfg.n_heads;
   AttnArgs a{};
@@ -830,6 +834,7 @@ void attention(const StepCtx& s, bool bwd, const Stream& qs, const Stream& ks, c
   a.q_off = qs.off; a.k_off = ks.off; a.B = s.B; a.H = H; a.dh = d / H; a.max_lq = qs.max_len; a.max_lk = ks.max_len;
   a.total_q = qs.rows; a.total_k = ks.rows; a.causal = causal ? 1 : 0;
   a.d_o = d_o; a.lddo = d; a.dq = dq; a.dk = dk; a.dv = dv; a.lddq = lddq; a.lddk = lddk; a.lddv = lddv;
+  a.drop_key = drop_key; a.drop_p = c->cfg.attn_dropout;          // dropout on the attention weights (0: off)
   const double f = attn_flops(lq, lk, d, causal);
   const double bytes = (double)c->esz * d * (bwd ? (4.0 * qs.rows + 4.0 * ks.rows) : (2.0 * qs.rows + 2.0 * ks.rows));
   if (!bwd) run(c, TFM_PROF_ATTENTION, f, bytes, [&] { launch_attention_fwd(c->stream, a); });
@@ -846,7 +851,8 @@ void sublayer_fwd(const StepCtx& s, Stream& st, int k, const void* fin, void* y)
   if (b.kind == SELF) {
     gemm(c, 0, T, 3 * d, d, fin, d, wh(c, b.w_a), d, b.inter, 3 * d, wh(c, b.b_a));
     const char* qkv = (const char*)b.inter;
-    attention(s, false, st, st, len, len, qkv, 3 * d, qkv + d * c->esz, 3 * d, qkv + 2 * d * c->esz, 3 * d, b.ctx, b.lse, st.id == 1);
+    attention(s, false, st, st, len, len, qkv, 3 * d, qkv + d * c->esz, 3 * d, qkv + 2 * d * c->esz, 3 * d, b.ctx, b.lse, st.id == 1,
+              site_key(s, st.id, b.layer, 3));
     gemm(c, 0, T, d, d, b.ctx, d, wh(c, b.w_o), d, y, d, wh(c, b.b_o));
   } else if (b.kind == CROSS) {
     Stream& en = c->enc;
@@ -855,10 +861,13 @@ void sublayer_fwd(const StepCtx& s, Stream& st, int k, const void* fin, void* y)
     if (c->kv_ready) { main_wait(c, c->kv_ready); c->kv_done = true; }   // projected ahead on the side stream (see tfm_train_step) ...
     else if (!c->kv_done) gemm(c, 0, en.rows, 2 * d, d, mem, d, wh(c, b.w_kv), d, b.kv, 2 * d, wh(c, b.b_kv));   // ... or here
     const char* kv = (const char*)b.kv;
-    attention(s, false, st, en, s.tlen, s.slen, b.inter, d, kv, 2 * d, kv + d * c->esz, 2 * d, b.ctx, b.lse, false);
+    attention(s, false, st, en, s.tlen, s.slen, b.inter, d, kv, 2 * d, kv + d * c->esz, 2 * d, b.ctx, b.lse, false,
+              site_key(s, st.id, b.layer, 4));
     gemm(c, 0, T, d, d, b.ctx, d, wh(c, b.w_o), d, y, d, wh(c, b.b_o));
   } else {
-    gemm(c, 0, T, F, d, fin, d, wh(c, b.w_a), d, b.inter, F, wh(c, b.b_a), 1);
+    // (dropout on the hidden activations, if configured, is applied by the same epilogue after the ReLU)
+    gemm(c, 0, T, F, d, fin, d, wh(c, b.w_a), d, b.inter, F, wh(c, b.b_a), 1, nullptr, nullptr, false, site_key(s, st.id, b.layer, 5),
+         c->cfg.relu_dropout);
     gemm(c, 0, T, d, F, b.inter, F, wh(c, b.w_o), F, y, d, wh(c, b.b_o));
   }
 }
@@ -917,7 +926,7 @@ void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const voi
     const char* qkv = (const char*)b.inter;
     char* dqkv = (char*)b.dint;
     attention(s, true, st, st, len, len, qkv, 3 * d, qkv + d * c->esz, 3 * d, qkv + 2 * d * c->esz, 3 * d, b.ctx, b.lse, st.id == 1,
-              c->dctx, dqkv, 3 * d, dqkv + d * c->esz, 3 * d, dqkv + 2 * d * c->esz, 3 * d);
+              site_key(s, st.id, b.layer, 3), c->dctx, dqkv, 3 * d, dqkv + d * c->esz, 3 * d, dqkv + 2 * d * c->esz, 3 * d);
     gemm(c, 1, T, d, 3 * d, dqkv, 3 * d, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
     wgrad(c, 3 * d, d, T, dqkv, 3 * d, fin, d, gr(c, b.w_a), d, gr(c, b.b_a));
   } else if (b.kind == CROSS) {
@@ -927,8 +936,8 @@ void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const voi
     gemm(c, 1, T, d, d, dy, d, wh(c, b.w_o), d, c->dctx, d);
     const char* kv = (const char*)b.kv;
     char* dkv = (char*)b.dkv;
-    attention(s, true, st, en, s.tlen, s.slen, b.inter, d, kv, 2 * d, kv + d * c->esz, 2 * d, b.ctx, b.lse, false, c->dctx,
-              b.dint, d, dkv, 2 * d, dkv + d * c->esz, 2 * d);
+    attention(s, true, st, en, s.tlen, s.slen, b.inter, d, kv, 2 * d, kv + d * c->esz, 2 * d, b.ctx, b.lse, false,
+              site_key(s, st.id, b.layer, 4), c->dctx, b.dint, d, dkv, 2 * d, dkv + d * c->esz, 2 * d);
     gemm(c, 1, T, d, d, b.dint, d, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
     gemm(c, 1, en.rows, d, 2 * d, dkv, 2 * d, wh(c, b.w_kv), d, *dmem_other, d, nullptr, 0, nullptr, *dmem_valid ? *dmem_cur : nullptr);
     std::swap(*dmem_cur, *dmem_other);
@@ -937,7 +946,10 @@ void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const voi
     wgrad(c, 2 * d, d, en.rows, dkv, 2 * d, mem, d, gr(c, b.w_kv), d, gr(c, b.b_kv));
   } else {
     wgrad(c, d, F, T, dy, d, b.inter, F, gr(c, b.w_o), F, gr(c, b.b_o));
-    gemm(c, 1, T, F, d, dy, d, wh(c, b.w_o), F, b.dint, F, nullptr, 0, b.inter, nullptr);
+    // the saved hidden activations are positive exactly where the ReLU passed AND the unit was kept: the mask, times the
+    // dropout scale
+    gemm(c, 1, T, F, d, dy, d, wh(c, b.w_o), F, b.dint, F, nullptr, 0, b.inter, nullptr, false, 0, 0.f,
+         1.f / (1.f - c->cfg.relu_dropout));
     gemm(c, 1, T, d, F, b.dint, F, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
     wgrad(c, F, d, T, b.dint, F, fin, d, gr(c, b.w_a), d, gr(c, b.b_a));
   }
@@ -1547,10 +1559,10 @@ int tfm_decoder_begin(tfm_decoder* D, const int32_t* src, const int32_t* src_len
     off[B] = r;
     HIP_TRY(c, hipMemcpyAsync(c->enc.ids, D->h_in, (2 * R + B + 1) * 4, hipMemcpyHostToDevice, c->stream));
     c->enc.rows = (int)Ts; c->enc.max_len = maxs;
-    const float p_train = c->cfg.dropout;
-    c->cfg.dropout = 0.f;
+    const float p_train = c->cfg.dropout, pa_train = c->cfg.attn_dropout, pr_train = c->cfg.relu_dropout;
+    c->cfg.dropout = c->cfg.attn_dropout = c->cfg.relu_dropout = 0.f;
     stream_fwd(s, c->enc);
-    c->cfg.dropout = p_train;
+    c->cfg.dropout = p_train; c->cfg.attn_dropout = pa_train; c->cfg.relu_dropout = pr_train;
     const void* mem = c->enc.norm[c->enc.blocks.size()];
     const int d = cf.d_model;
     int layer = 0;
@@ -1648,10 +1660,12 @@ int tfm_op_gemm(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K, co
 
 int tfm_op_gemm_ws(int32_t dtype, int32_t form, int32_t M, int32_t N, int32_t K, const void* A, int32_t lda, const void* B,
                    int32_t ldb, void* C, int32_t ldc, const void* bias, int32_t relu, const void* mask, const void* residual,
-                   void* workspace, size_t workspace_bytes, void* stream) {
+                   void* workspace, size_t workspace_bytes, uint64_t drop_key, float drop_p, float mask_scale, void* stream) {
   if (dtype < 0 || dtype > 2 || form < 0 || form > 2 || M < 0 || N < 0 || K < 0 || !A || !B || !C) return TFM_EINVAL;
   if (lda < (form == 2 ? M : K) || ldb < (form == 0 ? K : N) || ldc < N) return TFM_EINVAL;
+  if (!(drop_p >= 0.f && drop_p < 1.f)) return TFM_EINVAL;
   GemmArgs a{dtype, form, M, N, K, A, lda, B, ldb, C, ldc, bias, relu, mask, residual};
+  a.drop_key = drop_key; a.drop_p = drop_p; a.mask_scale = mask_scale;
   a.splitk_ws = workspace;
   a.splitk_ws_bytes = workspace ? workspace_bytes : 0;
   launch_gemm((hipStream_t)stream, a);
@@ -1676,13 +1690,14 @@ int tfm_op_wgrad_grouped(int32_t dtype, int32_t n, const int32_t* dims, const vo
 
 int tfm_op_attention_fwd(int32_t dtype, const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v, int32_t ldv,
                          void* o, int32_t ldo, float* lse, const int32_t* q_off, const int32_t* k_off, int32_t B, int32_t H,
-                         int32_t dh, int32_t max_lq, int32_t max_lk, int32_t total_q, int32_t causal, void* stream) {
+                         int32_t dh, int32_t max_lq, int32_t max_lk, int32_t total_q, int32_t causal, uint64_t drop_key, float drop_p,
+                         void* stream) {
   if (dtype < 0 || dtype > 2 || !q || !k || !v || !o || !lse || !q_off || !k_off || B < 1 || H < 1 || dh < 1 || dh > 128) return TFM_EINVAL;
-  if (max_lq < 1 || max_lk < 1 || max_lq > 4096 || max_lk > 4096) return TFM_EINVAL;
+  if (max_lq < 1 || max_lk < 1 || max_lq > 4096 || max_lk > 4096 || !(drop_p >= 0.f && drop_p < 1.f)) return TFM_EINVAL;
   AttnArgs a{};
   a.dt = dtype; a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.o = o; a.ldo = ldo; a.lse = lse;
   a.q_off = q_off; a.k_off = k_off; a.B = B; a.H = H; a.dh = dh; a.max_lq = max_lq; a.max_lk = max_lk; a.total_q = total_q;
-  a.causal = causal;
+  a.causal = causal; a.drop_key = drop_key; a.drop_p = drop_p;
   launch_attention_fwd((hipStream_t)stream, a);
   return op_done();
 }
@@ -1691,14 +1706,15 @@ int tfm_op_attention_bwd(int32_t dtype, const void* q, int32_t ldq, const void* 
                          const void* o, int32_t ldo, const void* d_o, int32_t lddo, const float* lse, void* dq, int32_t lddq,
                          void* dk, int32_t lddk, void* dv, int32_t lddv, const int32_t* q_off, const int32_t* k_off, int32_t B,
                          int32_t H, int32_t dh, int32_t max_lq, int32_t max_lk, int32_t total_q, int32_t total_k, int32_t causal,
-                         void* stream) {
+                         uint64_t drop_key, float drop_p, void* stream) {
   if (dtype < 0 || dtype > 2 || !q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !q_off || !k_off) return TFM_EINVAL;
   if (B < 1 || H < 1 || dh < 1 || dh > 128 || max_lq < 1 || max_lk < 1 || max_lq > 4096 || max_lk > 4096) return TFM_EINVAL;
+  if (!(drop_p >= 0.f && drop_p < 1.f)) return TFM_EINVAL;
   AttnArgs a{};
   a.dt = dtype; a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.o = const_cast<void*>(o); a.ldo = ldo;
   a.lse = const_cast<float*>(lse); a.q_off = q_off; a.k_off = k_off; a.B = B; a.H = H; a.dh = dh; a.max_lq = max_lq;
   a.max_lk = max_lk; a.total_q = total_q; a.total_k = total_k; a.causal = causal; a.d_o = d_o; a.lddo = lddo; a.dq = dq;
-  a.dk = dk; a.dv = dv; a.lddq = lddq; a.lddk = lddk; a.lddv = lddv;
+  a.dk = dk; a.dv = dv; a.lddq = lddq; a.lddk = lddk; a.lddv = lddv; a.drop_key = drop_key; a.drop_p = drop_p;
   launch_attention_bwd((hipStream_t)stream, a);
   return op_done();
 }

@@ -24,13 +24,14 @@ def _check(rc, what):
 
 
 def gemm(form, A, B, C_out, M, N, K, lda=None, ldb=None, ldc=None, bias=None, relu=False, mask=None, residual=None,
-         workspace=None):
+         workspace=None, drop_key=0, drop_p=0.0, mask_scale=1.0):
     lda = A.stride(0) if lda is None else lda
     ldb = B.stride(0) if ldb is None else ldb
     ldc = C_out.stride(0) if ldc is None else ldc
-    if workspace is not None:
+    if workspace is not None or drop_p > 0.0 or mask_scale != 1.0:
+        wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
         _check(lib().tfm_op_gemm_ws(_dt(A), form, M, N, K, _p(A), lda, _p(B), ldb, _p(C_out), ldc, _p(bias), int(relu),
-                                    _p(mask), _p(residual), _p(workspace), workspace.numel() * workspace.element_size(),
+                                    _p(mask), _p(residual), _p(workspace), wsb, int(drop_key), float(drop_p), float(mask_scale),
                                     _stream()), "tfm_op_gemm_ws")
         return
     _check(lib().tfm_op_gemm(_dt(A), form, M, N, K, _p(A), lda, _p(B), ldb, _p(C_out), ldc, _p(bias), int(relu),
@@ -48,19 +49,21 @@ def wgrad_grouped(jobs):
     _check(lib().tfm_op_wgrad_grouped(_dt(jobs[0][0]) if n else FP16, n, dims, pa, pb, pc, ps, _stream()), "tfm_op_wgrad_grouped")
 
 
-def attention_fwd(q, k, v, o, lse, q_off, k_off, H, dh, max_lq, max_lk, causal):
+def attention_fwd(q, k, v, o, lse, q_off, k_off, H, dh, max_lq, max_lk, causal, drop_key=0, drop_p=0.0):
     B = q_off.numel() - 1
     _check(lib().tfm_op_attention_fwd(_dt(q), _p(q), q.stride(0), _p(k), k.stride(0), _p(v), v.stride(0), _p(o),
                                       o.stride(0), _p(lse), _p(q_off), _p(k_off), B, H, dh, max_lq, max_lk,
-                                      lse.shape[1], int(causal), _stream()), "tfm_op_attention_fwd")
+                                      lse.shape[1], int(causal), int(drop_key), float(drop_p), _stream()), "tfm_op_attention_fwd")
 
 
-def attention_bwd(q, k, v, o, d_o, lse, dq, dk, dv, q_off, k_off, H, dh, max_lq, max_lk, total_k, causal):
+def attention_bwd(q, k, v, o, d_o, lse, dq, dk, dv, q_off, k_off, H, dh, max_lq, max_lk, total_k, causal, drop_key=0,
+                  drop_p=0.0):
     B = q_off.numel() - 1
     _check(lib().tfm_op_attention_bwd(_dt(q), _p(q), q.stride(0), _p(k), k.stride(0), _p(v), v.stride(0), _p(o),
                                       o.stride(0), _p(d_o), d_o.stride(0), _p(lse), _p(dq), dq.stride(0), _p(dk),
                                       dk.stride(0), _p(dv), dv.stride(0), _p(q_off), _p(k_off), B, H, dh, max_lq,
-                                      max_lk, lse.shape[1], total_k, int(causal), _stream()), "tfm_op_attention_bwd")
+                                      max_lk, lse.shape[1], total_k, int(causal), int(drop_key), float(drop_p), _stream()),
+           "tfm_op_attention_bwd")
 
 
 def residual_layernorm_fwd(x, y, gamma, beta, s_out, n_out, mean, rstd, key=0, p=0.0):

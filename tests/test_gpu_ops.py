@@ -92,6 +92,43 @@ def test_gemm_split_k_weight_gradient_is_exact_and_reproducible(prec, shape):
     assert np.array_equal(out.float().cpu().numpy().astype(np.float64), want)
 
 
+@pytest.mark.parametrize("prec", ["fp32", "fp16", "bf16"])
+@pytest.mark.parametrize("shape", [(200, 136, 72), (333, 264, 200), (257, 4096, 64)])
+def test_gemm_result_dropout_and_scaled_mask_are_exact(prec, shape):
+    """The two epilogue steps of the feed-forward layer with dropout on its hidden activations: relu(A B^T + b) with
+    inverted dropout (p = 1/2: kept values double, exact on small integers; keep bits from the oracle's generator), and
+    the masked product multiplied by the dropout scale."""
+    import torch
+    import paper_1904_01038_amd as T
+    from oracle.transformer import dropout_keep, dropout_key, site_id
+    M, N, K = shape
+    dt = _dtypes()[prec]
+    rng = np.random.default_rng(M + N)
+    A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+    B = rng.integers(-3, 4, (N, K)).astype(np.float64)
+    bias = rng.integers(-4, 5, N).astype(np.float64)
+    key = int(dropout_key(3, 9, site_id(0, 1, 5)))
+    keep = dropout_keep(key, 0, M, N, 0.5)
+    assert 0.4 < keep.mean() < 0.6
+    ref = np.where(keep, np.maximum(A @ B.T + bias, 0.0) * 2.0, 0.0)
+    assert np.abs(ref).max() < 2048
+    out = torch.full((M, N), 7.0, dtype=dt, device="cuda")
+    T.ops.gemm(0, _t(A, dt), _t(B, dt), out, M, N, K, bias=_t(bias, dt), relu=True, drop_key=key, drop_p=0.5)
+    got = out.float().cpu().numpy().astype(np.float64)
+    want = _t(ref, dt).float().cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, want), np.abs(got - want).max()
+    # masked input gradient: (dY W) * [h > 0] * 2
+    W = rng.integers(-2, 3, (K, N)).astype(np.float64)      # "NN": B is [K, N]
+    mask = np.where(keep, np.maximum(A @ B.T + bias, 0.0), 0.0)
+    ref2 = np.where(mask > 0, (A @ W) * 2.0, 0.0)
+    assert np.abs(ref2).max() < 2048
+    out2 = torch.full((M, N), 7.0, dtype=dt, device="cuda")
+    T.ops.gemm(1, _t(A, dt), _t(W, dt), out2, M, N, K, mask=_t(mask, dt), mask_scale=2.0)
+    got2 = out2.float().cpu().numpy().astype(np.float64)
+    want2 = _t(ref2, dt).float().cpu().numpy().astype(np.float64)
+    assert np.array_equal(got2, want2), np.abs(got2 - want2).max()
+
+
 @pytest.mark.parametrize("prec", ["fp16", "bf16"])
 @pytest.mark.parametrize("tile", ["small", "large"])
 def test_grouped_weight_gradients_with_bias_sums_are_exact(prec, tile):
@@ -196,13 +233,17 @@ ATTN_CASES = [  # (query lengths, key lengths or None for self-attention, causal
 ]
 
 
+@pytest.mark.parametrize("p_drop", [0.0, 0.25])
 @pytest.mark.parametrize("prec,dh", [("fp32", 16), ("fp32", 64), ("fp16", 64), ("bf16", 64), ("fp16", 32)])
 @pytest.mark.parametrize("case", ATTN_CASES)
-def test_attention_forward_backward(prec, dh, case):
+def test_attention_forward_backward(prec, dh, case, p_drop):
+    """p_drop > 0: dropout on the attention weights; both sides derive the keep bits from the same key, query row, head and
+    key index, each with its own implementation of the generator."""
     import torch
     import paper_1904_01038_amd as T
-    from oracle.transformer import attention_fwd, attention_bwd
+    from oracle.transformer import attention_fwd, attention_bwd, attention_keep, dropout_key, site_id
     lq, lk, causal = case
+    dkey = int(dropout_key(17, 4, site_id(1, 2, 3)))
     lk = lq if lk is None else lk
     H = 3
     d = H * dh
@@ -218,14 +259,20 @@ def test_attention_forward_backward(prec, dh, case):
     k_off = torch.tensor(np.concatenate([[0], np.cumsum(lk)]), dtype=torch.int32).cuda()
     o = torch.zeros(Tq, d, dtype=dt, device="cuda")
     lse = torch.zeros(H, Tq, dtype=torch.float32, device="cuda")
-    T.ops.attention_fwd(q, k, v, o, lse, q_off, k_off, H, dh, max(lq), max(lk), causal)
+    T.ops.attention_fwd(q, k, v, o, lse, q_off, k_off, H, dh, max(lq), max(lk), causal, dkey, p_drop)
     dq, dk, dv = (torch.zeros_like(x) for x in (q, k, v))
-    T.ops.attention_bwd(q, k, v, o, do, lse, dq, dk, dv, q_off, k_off, H, dh, max(lq), max(lk), Tk, causal)
+    T.ops.attention_bwd(q, k, v, o, do, lse, dq, dk, dv, q_off, k_off, H, dh, max(lq), max(lk), Tk, causal, dkey, p_drop)
     qd, kd, vd, dod = (x.double().cpu().numpy() for x in (q, k, v, do))
-    tol = {"fp32": 2e-5, "fp16": 4e-3, "bf16": 3e-2}[prec]
+    # With dropout the kept weights, and with them the outputs and their rounding, grow by 1 / (1 - p_drop); and where a
+    # sentence has a single key, dS = P (dP - dO.O) vanishes only in exact arithmetic: the backward pass forms dO.O from the
+    # rounded output, and dK sums that residue over all queries (reference exactly 0, so the bound is absolute).
+    tol = {"fp32": 2e-5, "fp16": 4e-3, "bf16": 3e-2}[prec] * (1.0 if p_drop == 0 else 2.0 / (1.0 - p_drop))
     for b in range(len(lq)):
         qs, ks = slice(int(q_off[b]), int(q_off[b + 1])), slice(int(k_off[b]), int(k_off[b + 1]))
-        ctx, cache = attention_fwd(qd[qs], kd[ks], vd[ks], H, causal)
+        keep = None
+        if p_drop > 0:
+            keep = [attention_keep(dkey, int(q_off[b]), lq[b], H, h, lk[b], p_drop) for h in range(H)]
+        ctx, cache = attention_fwd(qd[qs], kd[ks], vd[ks], H, causal, keep, p_drop)
         rq, rk, rv = attention_bwd(dod[qs], cache)
         for name, got, ref in [("o", o[qs], ctx), ("dq", dq[qs], rq), ("dk", dk[ks], rk), ("dv", dv[ks], rv)]:
             got = got.double().cpu().numpy()

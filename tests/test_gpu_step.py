@@ -66,6 +66,48 @@ def test_small_models_fp32(name, dropout):
     check_params_after_update(gpu.get_params(), oracle, gb, 5e-3)
 
 
+@pytest.mark.parametrize("name", list(SMALL))
+def test_small_models_fp32_with_attention_and_relu_dropout(name):
+    """All three dropout kinds at once (sub-layer outputs, attention weights, feed-forward hidden activations): the
+    generic kernels, two steps, then the update."""
+    import paper_1904_01038_amd as T
+    shape = SMALL[name]
+    gpu, oracle = make_pair(shape, T.FP32, dropout=0.2, attn_dropout=0.25, relu_dropout=0.3, seed=7)
+    lm = shape.enc_layers == 0
+    for it in range(2):
+        batch = small_batch(shape, 40 + it, lm=lm)
+        rg, ro = step_both(gpu, oracle, batch)
+        check_fp32(gpu, oracle, rg, ro)
+    gb = oracle.unscaled_grads()
+    ug, uo = gpu.apply_update(5e-3), oracle.apply_update(5e-3)
+    check_params_after_update(gpu.get_params(), oracle, gb, 5e-3)
+
+
+@pytest.mark.parametrize("precision", ["fp16", "bf16"])
+@pytest.mark.parametrize("name", ["post", "lm_pre"])
+def test_half_precision_models_with_attention_and_relu_dropout(precision, name):
+    """The matrix-core kernels with dropout on the attention weights (heads of width 64, sentences of one and of several
+    64-row chunks) and on the feed-forward hidden activations (GEMM epilogue and the masked input gradient)."""
+    import paper_1904_01038_amd as T
+    shape = {"post": ModelShape(2, 2, 128, 2, 256, 512), "lm_pre": ModelShape(0, 2, 128, 2, 256, 512, pre_norm=1)}[name]
+    prec = T.FP16 if precision == "fp16" else T.BF16
+    scale = 128.0 if precision == "fp16" else 1.0
+    for hi in (40, 150):                      # every sentence within one chunk / up to three chunks
+        gpu, oracle = make_pair(shape, prec, generic=True, init_loss_scale=scale, max_sentences=64, max_len=160, max_tokens=2048,
+                                dropout=0.1, attn_dropout=0.2, relu_dropout=0.15, seed=3)
+        if shape.enc_layers:
+            batch = make_batches("base", 1, shape=shape, max_tokens=600, lo=5, hi=hi)[0]
+        else:
+            batch = make_batches("lm16", 1, shape=shape, hi=hi, max_sentences=6)[0]
+        rg, ro = step_both(gpu, oracle, batch)
+        assert rg["overflow"] == 0 and ro["overflow"] == 0
+        assert abs(rg["loss_sum"] - ro["loss_sum"]) <= HALF_LOSS * abs(ro["loss_sum"])
+        gg = gpu.get_grads()
+        for k, v in oracle.G.items():
+            assert cosine(gg[k], v) >= HALF_COS, (hi, k, cosine(gg[k], v))
+        gpu.close()
+
+
 @pytest.mark.parametrize("precision", ["fp16", "bf16"])
 @pytest.mark.parametrize("name", ["post", "lm_pre"])
 def test_half_precision_models(precision, name):
