@@ -206,6 +206,7 @@ class TrainConfig:
     adam_beta1: float = 0.9
     adam_beta2: float = 0.98
     adam_eps: float = 1e-8
+    weight_decay: float = 0.0       # L2 form: weight_decay * w joins the (unscaled, clipped) gradient inside the Adam step
     clip_norm: float = 0.0
     init_loss_scale: float = 128.0
     scale_window: int = 2000
@@ -605,7 +606,7 @@ class OracleTransformer:
             t = self.num_updates
             b1, b2 = cfg.adam_beta1, cfg.adam_beta2
             for k in self.p:
-                gk = gr[k] * coef
+                gk = gr[k] * coef + cfg.weight_decay * self.p[k]
                 self.m[k] = b1 * self.m[k] + (1.0 - b1) * gk
                 self.v[k] = b2 * self.v[k] + (1.0 - b2) * gk * gk
                 mhat = self.m[k] / (1.0 - b1 ** t)

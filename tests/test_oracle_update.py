@@ -2,6 +2,7 @@
 import os
 
 import numpy as np
+import pytest
 import torch
 
 from oracle.transformer import OracleTransformer, TrainConfig
@@ -30,11 +31,13 @@ def test_power_of_two_scale_is_exactly_transparent():
         assert np.array_equal(a.m[k], b.m[k]) and np.array_equal(a.v[k], b.v[k])
 
 
-def test_adam_matches_library_and_closed_forms():
+@pytest.mark.parametrize("wd", [0.0, 0.05])
+def test_adam_matches_library_and_closed_forms(wd):
+    """wd > 0: weight decay in the L2 form of the library routine (wd * w joins the gradient inside the step)."""
     params = init_params(SHAPE, 3, generic=True)
-    o = OracleTransformer(SHAPE, params, TrainConfig(init_loss_scale=4.0))
+    o = OracleTransformer(SHAPE, params, TrainConfig(init_loss_scale=4.0, weight_decay=wd))
     tp = {k: torch.tensor(v.copy(), requires_grad=True) for k, v in params.items()}
-    opt = torch.optim.Adam(list(tp.values()), lr=3e-3, betas=(0.9, 0.98), eps=1e-8)
+    opt = torch.optim.Adam(list(tp.values()), lr=3e-3, betas=(0.9, 0.98), eps=1e-8, weight_decay=wd)
     for u in range(4):
         b = small_batch(SHAPE, 50 + u)
         o.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens)
@@ -46,9 +49,10 @@ def test_adam_matches_library_and_closed_forms():
             tp[k].grad = torch.tensor(g[k])
         opt.step()
         r = o.apply_update(3e-3)
-        if u == 0:                                   # step 1: delta = -lr * g / (|g| + eps)
+        if u == 0:                                   # step 1: delta = -lr * g / (|g| + eps), g including the decay term
             for k in w0:
-                np.testing.assert_allclose(o.p[k] - w0[k], -3e-3 * g0[k] / (np.abs(g0[k]) + 1e-8), rtol=1e-9, atol=1e-15)
+                ge = g0[k] + wd * w0[k]
+                np.testing.assert_allclose(o.p[k] - w0[k], -3e-3 * ge / (np.abs(ge) + 1e-8), rtol=1e-9, atol=1e-15)
         assert r["skipped"] == 0 and r["num_updates"] == u + 1
         for k in tp:
             np.testing.assert_allclose(o.p[k], tp[k].detach().numpy(), rtol=1e-12, atol=1e-15, err_msg=k)
