@@ -65,6 +65,7 @@ typedef struct {
   float   relu_dropout;     /* on the feed-forward hidden activations, after the ReLU; [0, 1)                */
   float   label_smoothing;  /* eps in q = (1-eps) onehot + eps/V                                             */
   float   adam_beta1, adam_beta2, adam_eps;
+  float   weight_decay;     /* L2 form: weight_decay * w joins the unscaled (and clipped) gradient; 0 = off  */
   float   clip_norm;        /* 0 = off; else the unscaled gradient is scaled down to this L2 norm            */
   float   init_loss_scale;  /* a power of two; use 1 for fp32/bf16                                           */
   int32_t scale_window;     /* clean updates after which the scale doubles                                   */
@@ -233,11 +234,11 @@ int tfm_op_loss(int32_t dtype, void* z, const int32_t* labels, float* loss_rows,
                 int32_t V, float eps, float scale, void* stream);
 
 /* Adam on a flat fp32 range with gradient g (dtype gdtype) pre-multiplied by 1/inv_scale:
- * gg = g * grad_mult; m = b1 m + (1-b1) gg; v = b2 v + (1-b2) gg^2; w -= lr * (m/bc1) / (sqrt(v/bc2) + eps);
- * half copy (dtype hdtype, may be NULL) = w. */
+ * gg = g * grad_mult + weight_decay * w; m = b1 m + (1-b1) gg; v = b2 v + (1-b2) gg^2;
+ * w -= lr * (m/bc1) / (sqrt(v/bc2) + eps); half copy (dtype hdtype, may be NULL) = w. */
 int tfm_op_adam(float* w, float* m, float* v, const void* g, int32_t gdtype, void* half_copy, int32_t hdtype,
-                int64_t n, float lr, float beta1, float beta2, float eps, float grad_mult, float bc1, float bc2,
-                void* stream);
+                int64_t n, float lr, float beta1, float beta2, float eps, float weight_decay, float grad_mult,
+                float bc1, float bc2, void* stream);
 
 /* result[0] = 1.0f if any element of x[n] is non-finite else 0; result[1] = sum of squares (fp32 device [2]). */
 int tfm_op_scan(int32_t dtype, const void* x, int64_t n, float* result, void* scratch, void* stream);

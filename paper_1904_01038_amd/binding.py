@@ -30,7 +30,7 @@ class TfmConfig(C.Structure):
                 ("max_sentences", C.c_int32), ("max_len", C.c_int32), ("max_tokens", C.c_int32),
                 ("precision", C.c_int32), ("pre_norm", C.c_int32), ("dropout", C.c_float),
                 ("attn_dropout", C.c_float), ("relu_dropout", C.c_float), ("label_smoothing", C.c_float), ("adam_beta1", C.c_float), ("adam_beta2", C.c_float),
-                ("adam_eps", C.c_float), ("clip_norm", C.c_float), ("init_loss_scale", C.c_float),
+                ("adam_eps", C.c_float), ("weight_decay", C.c_float), ("clip_norm", C.c_float), ("init_loss_scale", C.c_float),
                 ("scale_window", C.c_int32), ("min_loss_scale", C.c_float), ("seed", C.c_uint64),
                 ("n_cutoffs", C.c_int32), ("cutoffs", C.c_int32 * 3), ("adaptive_factor", C.c_int32)]
 
@@ -108,7 +108,7 @@ def lib():
         L.tfm_op_layernorm_bwd_scratch.restype = C.c_size_t
         L.tfm_op_layernorm_bwd.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, u64, f32, vp, vp]
         L.tfm_op_loss.argtypes = [i32, vp, vp, vp, vp, i32, i32, f32, f32, vp]
-        L.tfm_op_adam.argtypes = [vp, vp, vp, vp, i32, vp, i32, i64, f32, f32, f32, f32, f32, f32, f32, vp]
+        L.tfm_op_adam.argtypes = [vp, vp, vp, vp, i32, vp, i32, i64, f32, f32, f32, f32, f32, f32, f32, f32, vp]
         L.tfm_op_scan_scratch.argtypes = [i64]
         L.tfm_op_scan_scratch.restype = C.c_size_t
         L.tfm_op_scan.argtypes = [i32, vp, i64, vp, vp, vp]
@@ -121,12 +121,12 @@ def lib():
 
 def make_config(shape, *, precision, max_sentences, max_len, max_tokens, dropout=0.0, label_smoothing=0.1,
                 adam_beta1=0.9, adam_beta2=0.98, adam_eps=1e-8, clip_norm=0.0, init_loss_scale=128.0,
-                scale_window=2000, min_loss_scale=2.0 ** -14, seed=0, attn_dropout=0.0, relu_dropout=0.0):
+                scale_window=2000, min_loss_scale=2.0 ** -14, seed=0, attn_dropout=0.0, relu_dropout=0.0, weight_decay=0.0):
     """shape: any object with enc_layers, dec_layers, d_model, n_heads, d_ffn, vocab, pad_id, eos_id, pre_norm."""
     cut = tuple(getattr(shape, "cutoffs", ()))
     return TfmConfig(shape.enc_layers, shape.dec_layers, shape.d_model, shape.n_heads, shape.d_ffn, shape.vocab,
                      shape.pad_id, shape.eos_id, max_sentences, max_len, max_tokens, precision, shape.pre_norm,
-                     dropout, attn_dropout, relu_dropout, label_smoothing, adam_beta1, adam_beta2, adam_eps, clip_norm, init_loss_scale,
+                     dropout, attn_dropout, relu_dropout, label_smoothing, adam_beta1, adam_beta2, adam_eps, weight_decay, clip_norm, init_loss_scale,
                      scale_window, min_loss_scale, seed, len(cut), (C.c_int32 * 3)(*(list(cut) + [0] * (3 - len(cut)))),
                      getattr(shape, "factor", 4))
 

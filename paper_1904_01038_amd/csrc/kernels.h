@@ -146,6 +146,7 @@ void launch_convert(hipStream_t s, int src_dt, const void* src, int dst_dt, void
 struct AdamArgs {
   float *w, *m, *v; const void* g; int gdt; void* half_copy; int hdt; int64_t n;
   float lr, beta1, beta2, eps;
+  float weight_decay;        // L2 form: weight_decay * w joins the unscaled gradient
   const DevState* st;        // if non-null: skip flag, grad_mult, bc1, bc2 come from the device state
   float grad_mult, bc1, bc2;
 };

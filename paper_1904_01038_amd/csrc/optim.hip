@@ -156,7 +156,7 @@ template <typename GT, typename HT>
 __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ w, float* __restrict__ m, float* __restrict__ v,
                                                    const GT* __restrict__ g, HT* __restrict__ hcopy, int64_t n, float lr, float beta1,
                                                    float beta2, float eps, const DevState* __restrict__ st, float grad_mult,
-                                                   float bc1, float bc2) {
+                                                   float bc1, float bc2, float wd) {
   if (st) {
     if (st->skipped) return;
     grad_mult = st->grad_mult; bc1 = st->bc1; bc2 = st->bc2;
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ w, float*
     load_f<GT, ADAM_VEC>(g + i, gv);
 #pragma unroll
     for (int k = 0; k < ADAM_VEC; ++k) {
-      const float gg = gv[k] * grad_mult;
+      const float gg = gv[k] * grad_mult + wd * wv[k];
       mv[k] = beta1 * mv[k] + (1.f - beta1) * gg;
       vv[k] = beta2 * vv[k] + (1.f - beta2) * gg * gg;
       wv[k] -= step * mv[k] / (sqrtf(vv[k] * rbc2) + eps);
@@ -190,7 +190,7 @@ static void adam_dispatch(hipStream_t s, const AdamArgs& a) {
   dim3 grid((unsigned)(b < 1 ? 1 : b)), block(256);
 #define ADAM(HT)                                                                                                       \
   hipLaunchKernelGGL((adam_kernel<GT, HT>), grid, block, 0, s, a.w, a.m, a.v, (const GT*)a.g, (HT*)a.half_copy, a.n, a.lr, \
-                     a.beta1, a.beta2, a.eps, a.st, a.grad_mult, a.bc1, a.bc2)
+                     a.beta1, a.beta2, a.eps, a.st, a.grad_mult, a.bc1, a.bc2, a.weight_decay)
   if (a.hdt == F16) ADAM(half_t); else if (a.hdt == BF16) ADAM(bf16_t); else ADAM(float);
 #undef ADAM
 }

@@ -283,6 +283,7 @@ int validate(const tfm_config& c, char* msg) {
   if (!(c.label_smoothing >= 0.f && c.label_smoothing < 1.f)) BAD("label_smoothing must be in [0, 1)");
   if (!(c.adam_beta1 >= 0.f && c.adam_beta1 < 1.f && c.adam_beta2 >= 0.f && c.adam_beta2 < 1.f && c.adam_eps > 0.f)) BAD("bad Adam constants");
   if (!(c.clip_norm >= 0.f)) BAD("clip_norm must be >= 0");
+  if (!(c.weight_decay >= 0.f) || !std::isfinite(c.weight_decay)) BAD("weight_decay must be >= 0");
   if (!(c.init_loss_scale > 0.f) || !std::isfinite(c.init_loss_scale)) BAD("init_loss_scale must be positive");
   if (c.scale_window < 1) BAD("scale_window must be >= 1");
   if (!(c.min_loss_scale >= 0.f)) BAD("min_loss_scale must be >= 0");
@@ -1340,7 +1341,7 @@ int tfm_apply_update(tfm_ctx* c, float lr, tfm_update_out* out) {
   a.w = c->W; a.m = c->M; a.v = c->V; a.n = c->P;
   a.g = single ? c->g : (const void*)c->G; a.gdt = single ? c->dt : (int)F32;
   a.half_copy = c->dt == F32 ? nullptr : c->Wh; a.hdt = c->dt;
-  a.lr = lr; a.beta1 = cf.adam_beta1; a.beta2 = cf.adam_beta2; a.eps = cf.adam_eps; a.st = c->st;
+  a.lr = lr; a.beta1 = cf.adam_beta1; a.beta2 = cf.adam_beta2; a.eps = cf.adam_eps; a.weight_decay = cf.weight_decay; a.st = c->st;
   const double bpp = 24.0 + (single ? c->esz : 4.0) + (c->dt == F32 ? 0.0 : 2.0);
   if (!c->overlap) {
     run(c, TFM_PROF_OPTIM, 0.0, (double)c->P * bpp, [&] { launch_adam(c->stream, a); });
@@ -1747,9 +1748,10 @@ int tfm_op_loss(int32_t dtype, void* z, const int32_t* labels, float* loss_rows,
 }
 
 int tfm_op_adam(float* w, float* m, float* v, const void* g, int32_t gdtype, void* half_copy, int32_t hdtype, int64_t n,
-                float lr, float beta1, float beta2, float eps, float grad_mult, float bc1, float bc2, void* stream) {
+                float lr, float beta1, float beta2, float eps, float weight_decay, float grad_mult, float bc1, float bc2,
+                void* stream) {
   if (!w || !m || !v || !g || gdtype < 0 || gdtype > 2 || hdtype < 0 || hdtype > 2 || n < 0 || n % 8) return TFM_EINVAL;
-  AdamArgs a{w, m, v, g, gdtype, half_copy, hdtype, n, lr, beta1, beta2, eps, nullptr, grad_mult, bc1, bc2};
+  AdamArgs a{w, m, v, g, gdtype, half_copy, hdtype, n, lr, beta1, beta2, eps, weight_decay, nullptr, grad_mult, bc1, bc2};
   launch_adam((hipStream_t)stream, a);
   return op_done();
 }

@@ -88,10 +88,10 @@ def loss(z, labels, loss_rows, nll_rows, eps, scale):
            "tfm_op_loss")
 
 
-def adam(w, m, v, g, half_copy, lr, beta1, beta2, eps, grad_mult, bc1, bc2):
+def adam(w, m, v, g, half_copy, lr, beta1, beta2, eps, grad_mult, bc1, bc2, weight_decay=0.0):
     hd = FP32 if half_copy is None else _dt(half_copy)
     _check(lib().tfm_op_adam(_p(w), _p(m), _p(v), _p(g), _dt(g), _p(half_copy), hd, w.numel(), lr, beta1, beta2, eps,
-                             grad_mult, bc1, bc2, _stream()), "tfm_op_adam")
+                             float(weight_decay), grad_mult, bc1, bc2, _stream()), "tfm_op_adam")
 
 
 def scan(x, result):

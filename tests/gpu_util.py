@@ -7,7 +7,7 @@ from synth import init_params
 
 def make_pair(shape, precision, *, dropout=0.0, seed_params=0, max_sentences=64, max_len=64, max_tokens=1024,
               init_loss_scale=1.0, scale_window=2000, clip_norm=0.0, label_smoothing=0.1, seed=0, generic=True,
-              round_params=True, attn_dropout=0.0, relu_dropout=0.0):
+              round_params=True, attn_dropout=0.0, relu_dropout=0.0, weight_decay=0.0):
     import paper_1904_01038_amd as T
     params = init_params(shape, seed_params, generic=generic)
     if round_params:
@@ -18,11 +18,11 @@ def make_pair(shape, precision, *, dropout=0.0, seed_params=0, max_sentences=64,
     cfg = T.make_config(shape, precision=precision, max_sentences=max_sentences, max_len=max_len, max_tokens=max_tokens,
                         dropout=dropout, label_smoothing=label_smoothing, init_loss_scale=init_loss_scale,
                         scale_window=scale_window, clip_norm=clip_norm, seed=seed, attn_dropout=attn_dropout,
-                        relu_dropout=relu_dropout)
+                        relu_dropout=relu_dropout, weight_decay=weight_decay)
     gpu = T.Tfm(cfg)
     assert gpu.param_names == list(params.keys())
     gpu.set_params(params)
-    ocfg = TrainConfig(dropout=dropout, attn_dropout=attn_dropout, relu_dropout=relu_dropout, label_smoothing=label_smoothing, init_loss_scale=init_loss_scale,
+    ocfg = TrainConfig(weight_decay=weight_decay, dropout=dropout, attn_dropout=attn_dropout, relu_dropout=relu_dropout, label_smoothing=label_smoothing, init_loss_scale=init_loss_scale,
                        scale_window=scale_window, clip_norm=clip_norm, fp16_overflow=(precision == T.FP16),
                        dynamic_scale=(precision == T.FP16), seed=seed)
     return gpu, OracleTransformer(shape, params, ocfg)

@@ -285,3 +285,30 @@ def test_attention_forward_backward(prec, dh, case, p_drop):
                 s = np.where(np.arange(s.shape[1])[None, :] <= np.arange(s.shape[0])[:, None], s, -np.inf)
             ref = np.log(np.exp(s - s.max(1, keepdims=True)).sum(1)) + s.max(1)
             assert np.abs(lse[h, qs].cpu().numpy() - ref).max() <= max(tol, 1e-4) * 4
+
+
+@pytest.mark.parametrize("gprec", ["fp32", "fp16", "bf16"])
+@pytest.mark.parametrize("wd", [0.0, 0.05])
+def test_adam_kernel_against_the_library_optimiser(gprec, wd):
+    """Three steps of the Adam kernel (gradient in fp32/fp16/bf16, unscaled by grad_mult, optional L2 weight decay) against
+    torch.optim.Adam on the CPU in float64 fed with the same (rounded) gradients; the half copy equals the rounded master."""
+    import torch
+    import paper_1904_01038_amd as T
+    n, lr, b1, b2, eps, mult = 4096, 3e-3, 0.9, 0.98, 1e-8, 1.0 / 64.0
+    rng = np.random.default_rng(5)
+    w0 = rng.normal(size=n)
+    gdt = _dtypes()[gprec]
+    w = torch.tensor(w0, dtype=torch.float32).cuda()
+    m = torch.zeros(n, dtype=torch.float32, device="cuda")
+    v = torch.zeros(n, dtype=torch.float32, device="cuda")
+    half = torch.zeros(n, dtype=torch.float16, device="cuda")
+    ref = torch.tensor(w.cpu().numpy().astype(np.float64), requires_grad=True)
+    opt = torch.optim.Adam([ref], lr=lr, betas=(b1, b2), eps=eps, weight_decay=wd)
+    for t in range(1, 4):
+        g = _t(rng.normal(size=n) * 64.0, gdt)
+        T.ops.adam(w, m, v, g, half, lr, b1, b2, eps, mult, 1.0 - b1 ** t, 1.0 - b2 ** t, weight_decay=wd)
+        ref.grad = g.double().cpu() * mult
+        opt.step()
+        got = w.double().cpu().numpy()
+        assert np.abs(got - ref.detach().numpy()).max() <= 2e-6 * t, (t, np.abs(got - ref.detach().numpy()).max())
+        assert torch.equal(half, w.half())

@@ -168,3 +168,17 @@ def test_bad_arguments_are_rejected_without_side_effects():
     big = small_batch(shape, 3)
     with pytest.raises(T.TfmError):     # 3 sentences fit, but not with > max_tokens tokens
         gpu.train_step(np.tile(big.src, (2, 1)), np.tile(big.tgt, (2, 1)), np.tile(big.src_lens, 2), np.tile(big.tgt_lens, 2))
+
+
+def test_weight_decay_fp32_update_matches_the_oracle():
+    import paper_1904_01038_amd as T
+    shape = SMALL["post"]
+    gpu, oracle = make_pair(shape, T.FP32, weight_decay=0.1, seed=2)
+    for it in range(3):
+        rg, ro = step_both(gpu, oracle, small_batch(shape, 60 + it))
+        check_fp32(gpu, oracle, rg, ro)
+        gb = oracle.unscaled_grads()
+        gb = {k: v + 0.1 * oracle.p[k] for k, v in gb.items()}      # what the step divides by: gradient plus decay term
+        ug, uo = gpu.apply_update(5e-3), oracle.apply_update(5e-3)
+        assert abs(ug["grad_norm"] - uo["grad_norm"]) <= 1e-4 * uo["grad_norm"]     # the reported norm excludes the decay term
+        check_params_after_update(gpu.get_params(), oracle, gb, 5e-3)
