@@ -271,6 +271,14 @@ def main():
                 "avg_launch_ms": g["ms"] / max(g["launches"], 1), "launches_per_step": g["launches"] / args.profile_steps,
                 "timed_with": "all launches on one stream (each kernel alone on the GPU)",
                 "classes": classes, "overlapped": overlapped}
+    # what this device sustains on the two resources, beside the published peaks (a register-only matrix-core loop; a plain
+    # 1 GiB copy, bytes read plus written)
+    ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+    if prec != T.FP32:
+        roofline["measured_ceilings"] = {"mfma_only_loop_tflops": T.ops.probe_mfma(prec), "copy_kernel_gbs": T.ops.probe_copy(1 << 30),
+                                         "published": {"mfma_tflops": MFMA_PEAK_TFLOPS, "hbm_gbs": HBM_PEAK_GBS}}
 
     out = {"metric": "target tokens/sec per training step on 1 MI355X", "value": tokens / dt, "unit": "tokens/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,

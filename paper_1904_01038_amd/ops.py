@@ -106,3 +106,22 @@ def dropout_mask(key, p, out):
 
 def dropout_key(seed, step, stream, layer, sub):
     return lib().tfm_dropout_key(seed, step, stream, layer, sub)
+
+
+def probe_mfma(dtype=FP16):
+    """TFLOP/s of a register-only matrix-core loop on every compute unit."""
+    import torch
+    scratch = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    out = C.c_double()
+    _check(lib().tfm_probe_mfma(dtype, _p(scratch), scratch.numel(), C.byref(out), _stream()), "tfm_probe_mfma")
+    return out.value
+
+
+def probe_copy(nbytes=1 << 30):
+    """GB/s (read + written) of a plain device copy of nbytes."""
+    import torch
+    a = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    b = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    out = C.c_double()
+    _check(lib().tfm_probe_copy(_p(a), _p(b), nbytes, C.byref(out), _stream()), "tfm_probe_copy")
+    return out.value

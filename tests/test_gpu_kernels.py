@@ -119,3 +119,13 @@ def test_scan_flag_and_sum_of_squares(prec, n):
     # twice the same bits (fixed-order partial sums)
     T.ops.scan(x, res)
     assert res.cpu().numpy()[1] == ss
+
+
+def test_measured_ceilings_are_plausible():
+    """The two probes behind bench.py's `measured_ceilings`: below the published peaks, above half of them."""
+    import paper_1904_01038_amd as T
+    for dt in (T.FP16, T.BF16):
+        tf = T.ops.probe_mfma(dt)
+        assert 1000.0 < tf <= 2500.0 * 1.02, tf
+    gbs = T.ops.probe_copy(1 << 28)
+    assert 2000.0 < gbs <= 8000.0 * 1.02, gbs
