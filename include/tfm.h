@@ -304,6 +304,16 @@ int tfm_decoder_get_logprobs(tfm_decoder* dec, float* host, int64_t n);
  * warmup = 0 means no warm-up: peak_lr / sqrt(max(t, 1)).  Returns NaN for t < 0 or warmup < 0. */
 double tfm_lr_inverse_sqrt(int64_t t, int64_t warmup, double peak_lr, double init_lr);
 
+/* Cyclical learning-rate schedule with warm restarts (Components, Learning Rate Schedulers: "cyclical schedulers
+ * based on warm restarts", the cosine schedule of the work cited there).  Update t = 1, 2, ...:
+ *   t <= warmup:  init_lr + (max_lr - init_lr) * t / warmup         (linear warm-up; warmup = 0: none)
+ *   afterwards cycle i = 0, 1, ... lasts T_i = period * t_mult^i updates and runs
+ *                 min_lr + (max_lr * shrink^i - min_lr) * (1 + cos(pi * T_cur / T_i)) / 2,
+ * T_cur = updates since the cycle began (0 at its first update, which therefore runs at the cycle's maximum).
+ * period > 0, t_mult >= 1 (need not be integers); returns NaN otherwise or for t < 0, warmup < 0. */
+double tfm_lr_cosine_restarts(int64_t t, int64_t warmup, double max_lr, double min_lr, double period, double t_mult,
+                              double shrink, double init_lr);
+
 /* Token-capped batches of sentences of similar length (Implementation, Batching).  Sentences are ordered by
  * (max(src_len, tgt_len), index) ascending and cut greedily: a batch takes the next sentence while
  * (sentences + 1) * (longest sentence so far in the batch, counting the candidate) <= max_tokens and

@@ -5,6 +5,8 @@ baseline may import it.  It shares no code with the HIP/C++ library.
 
   lr_inverse_sqrt   Components, Learning Rate Schedulers: the inverse square-root schedule of the Transformer paper the
                     text cites, lr = d^-1/2 * min(t^-1/2, t * w^-3/2), generalised to a peak rate and a start rate.
+  lr_cosine_restarts  Components, Learning Rate Schedulers: the cyclical schedule "based on warm restarts" of the work
+                    the text cites: inside cycle i, lr = min + (max_i - min) (1 + cos(pi T_cur / T_i)) / 2.
   batch_by_length   Implementation, Batching: mini-batches group sentences of similar length, hold up to a given
                     number of tokens and keep their content from epoch to epoch.
   shuffle_batches   Implementation, Batching: the batches themselves are visited in a new random order every epoch.
@@ -25,6 +27,25 @@ def lr_inverse_sqrt(t, warmup, peak_lr, init_lr=0.0):
     if t <= warmup:
         return init_lr + (peak_lr - init_lr) * (t / warmup)
     return peak_lr * math.sqrt(warmup / t)
+
+
+def lr_cosine_restarts(t, warmup, max_lr, min_lr, period, t_mult=1.0, shrink=1.0, init_lr=0.0):
+    """Update t = 1, 2, ...: linear warm-up from init_lr to max_lr over `warmup` updates, then cosine cycles with warm
+    restarts.  Cycle i = 0, 1, ... lasts T_i = period * t_mult^i updates (a real number when t_mult is not an integer)
+    and starts at max_i = max_lr * shrink^i; T_cur counts the updates since the cycle began, so the first update after
+    the warm-up (and after every restart) runs at max_i."""
+    if t < 0 or warmup < 0 or period <= 0 or t_mult < 1.0:
+        return math.nan
+    if t <= warmup:
+        return max_lr if warmup == 0 else init_lr + (max_lr - init_lr) * (t / warmup)
+    t_cur = float(t - warmup - 1)                     # 0 at the first update of the first cycle
+    i, length = 0, float(period)
+    while t_cur >= length:                            # walk the cycles one by one
+        t_cur -= length
+        length *= t_mult
+        i += 1
+    top = max_lr * shrink ** i
+    return min_lr + 0.5 * (top - min_lr) * (1.0 + math.cos(math.pi * t_cur / length))
 
 
 def batch_by_length(src_lens, tgt_lens, max_tokens, max_sentences, multiple=1):

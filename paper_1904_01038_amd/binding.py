@@ -92,6 +92,8 @@ def lib():
         L.tfm_decoder_get_logprobs.argtypes = [vp, vp, i64]
         L.tfm_lr_inverse_sqrt.argtypes = [i64, i64, C.c_double, C.c_double]
         L.tfm_lr_inverse_sqrt.restype = C.c_double
+        L.tfm_lr_cosine_restarts.argtypes = [i64, i64, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double]
+        L.tfm_lr_cosine_restarts.restype = C.c_double
         L.tfm_batch_by_length.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, C.POINTER(i64)]
         L.tfm_shuffle_batches.argtypes = [i64, u64, u64, vp]
         L.tfm_profile_read.argtypes = [vp, C.POINTER(ProfEntry), i32]
@@ -315,6 +317,11 @@ class Decoder:
 
 def lr_inverse_sqrt(t, warmup, peak_lr, init_lr=0.0):
     return lib().tfm_lr_inverse_sqrt(int(t), int(warmup), float(peak_lr), float(init_lr))
+
+
+def lr_cosine_restarts(t, warmup, max_lr, min_lr, period, t_mult=1.0, shrink=1.0, init_lr=0.0):
+    return lib().tfm_lr_cosine_restarts(int(t), int(warmup), float(max_lr), float(min_lr), float(period), float(t_mult),
+                                        float(shrink), float(init_lr))
 
 
 def batch_by_length(src_lens, tgt_lens, max_tokens, max_sentences, multiple=1):

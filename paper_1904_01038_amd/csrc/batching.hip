@@ -29,6 +29,31 @@ double tfm_lr_inverse_sqrt(int64_t t, int64_t warmup, double peak_lr, double ini
   return peak_lr * std::sqrt((double)warmup / (double)t);
 }
 
+double tfm_lr_cosine_restarts(int64_t t, int64_t warmup, double max_lr, double min_lr, double period, double t_mult, double shrink,
+                              double init_lr) {
+  const double nan = std::numeric_limits<double>::quiet_NaN();
+  if (t < 0 || warmup < 0 || !(period > 0.0) || !(t_mult >= 1.0)) return nan;
+  if (t <= warmup) return warmup == 0 ? max_lr : init_lr + (max_lr - init_lr) * ((double)t / (double)warmup);
+  const double u = (double)(t - warmup - 1);             // updates since the first cycle began
+  double cycle, start, length;
+  if (t_mult == 1.0) {
+    cycle = std::floor(u / period);
+    start = cycle * period;
+    length = period;
+  } else {
+    // cycles end at period * (t_mult^(i+1) - 1) / (t_mult - 1): invert the geometric sum, then settle rounding at the edges
+    cycle = std::floor(std::log1p(u * (t_mult - 1.0) / period) / std::log(t_mult));
+    auto begin_of = [&](double i) { return period * (std::pow(t_mult, i) - 1.0) / (t_mult - 1.0); };
+    while (cycle > 0 && begin_of(cycle) > u) cycle -= 1.0;
+    while (begin_of(cycle + 1.0) <= u) cycle += 1.0;
+    start = begin_of(cycle);
+    length = period * std::pow(t_mult, cycle);
+  }
+  const double top = max_lr * std::pow(shrink, cycle);
+  const double pi = 3.14159265358979323846;
+  return min_lr + 0.5 * (top - min_lr) * (1.0 + std::cos(pi * (u - start) / length));
+}
+
 int tfm_batch_by_length(const int32_t* src_lens, const int32_t* tgt_lens, int64_t n, int32_t max_tokens,
                         int32_t max_sentences, int32_t multiple, int64_t* order, int64_t* batch_begin,
                         int64_t* n_batches) {

@@ -7,7 +7,7 @@ from collections import Counter
 import numpy as np
 import pytest
 
-from oracle.schedule_batching import lr_inverse_sqrt, batch_by_length, shuffle_batches, _finalise
+from oracle.schedule_batching import lr_inverse_sqrt, lr_cosine_restarts, batch_by_length, shuffle_batches, _finalise
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -33,6 +33,38 @@ def test_lr_shape():
     assert all(a < b for a, b in zip(up, up[1:])) and all(a > b for a, b in zip(down, down[1:]))
     assert math.isnan(lr_inverse_sqrt(-1, w, peak)) and math.isnan(lr_inverse_sqrt(1, -1, peak))
     assert lr_inverse_sqrt(9, 0, 3.0) == 1.0 and lr_inverse_sqrt(0, 0, 3.0) == 3.0
+
+
+def test_cosine_restarts_is_the_cited_schedule():
+    """eta_t = eta_min + (eta_max - eta_min) (1 + cos(pi T_cur / T_i)) / 2 with T_cur = 0 at a (re)start: checked on values
+    the formula fixes by hand, on periodicity, monotonicity inside a cycle, doubling periods and shrinking maxima."""
+    mx, mn, T0 = 1e-3, 1e-5, 100
+    f = lambda t, **kw: lr_cosine_restarts(t, 0, mx, mn, T0, **kw)
+    assert f(1) == mx                                              # T_cur = 0: the maximum
+    assert math.isclose(f(1 + T0 // 2), (mx + mn) / 2, rel_tol=1e-12)      # half-way: the mean of the two
+    assert math.isclose(f(1 + T0 // 4), mn + (mx - mn) * (1 + math.sqrt(0.5)) / 2, rel_tol=1e-12)   # cos(pi/4)
+    assert f(T0) > mn and math.isclose(f(T0), mn + (mx - mn) * (1 + math.cos(math.pi * 0.99)) / 2, rel_tol=1e-9)
+    assert f(T0 + 1) == mx                                         # warm restart
+    for t in range(1, 3 * T0):                                     # fixed period: periodic, decreasing inside a cycle
+        assert math.isclose(f(t), f(t + T0), rel_tol=1e-12)
+        if t % T0:
+            assert f(t + 1) < f(t)
+    # periods 100, 200, 400 with maxima 1, 1/2, 1/4: restarts at updates 1, 101, 301, 701
+    g = lambda t: lr_cosine_restarts(t, 0, mx, mn, T0, 2.0, 0.5)
+    for start, i in [(1, 0), (101, 1), (301, 2), (701, 3)]:
+        assert g(start) == mx * 0.5 ** i, (start, g(start))
+        assert g(start - 1) < g(start) or start == 1
+        half = start + (T0 * 2 ** i) // 2
+        assert math.isclose(g(half), (mx * 0.5 ** i + mn) / 2, rel_tol=1e-12)
+    # warm-up first: linear to the maximum, the first cycle begins right after it
+    h = lambda t: lr_cosine_restarts(t, 50, mx, mn, T0, 1.0, 1.0, 1e-7)
+    assert h(0) == 1e-7 and h(50) == mx and math.isclose(h(25), (mx + 1e-7) / 2, rel_tol=1e-12)
+    assert h(51) == mx and math.isclose(h(51 + T0 // 2), (mx + mn) / 2, rel_tol=1e-12) and h(151) == mx
+    # a period that is not an integer number of updates
+    k = lambda t: lr_cosine_restarts(t, 0, 1.0, 0.0, 2.5, 1.5)
+    assert k(1) == 1.0 and math.isclose(k(2), (1 + math.cos(math.pi / 2.5)) / 2) and math.isclose(k(4), (1 + math.cos(math.pi * 0.5 / 3.75)) / 2)
+    assert all(math.isnan(x) for x in (lr_cosine_restarts(-1, 0, mx, mn, T0), lr_cosine_restarts(1, -1, mx, mn, T0),
+                                       lr_cosine_restarts(1, 0, mx, mn, 0), lr_cosine_restarts(1, 0, mx, mn, T0, 0.5)))
 
 
 def read_example():
@@ -124,6 +156,18 @@ def test_library_lr_matches(T):
         for t in [0, 1, 2, 3, 999, 4000, 4001, 16000, 10 ** 6, 10 ** 12]:
             assert T.lr_inverse_sqrt(t, w, peak, init) == lr_inverse_sqrt(t, w, peak, init), (w, t)
     assert math.isnan(T.lr_inverse_sqrt(-1, 10, 1.0)) and math.isnan(T.lr_inverse_sqrt(1, -2, 1.0))
+
+
+def test_library_cosine_restarts_matches(T):
+    """The library inverts the geometric sum of the cycle lengths in closed form; the oracle walks the cycles."""
+    cases = [(0, 1e-3, 1e-5, 100, 1.0, 1.0, 0.0), (50, 1e-3, 1e-5, 100, 2.0, 0.5, 1e-7), (10, 2e-3, 0.0, 37.5, 1.3, 0.9, 1e-4),
+             (0, 1.0, 0.1, 1, 1.0, 1.0, 0.0), (4000, 7e-4, 1e-9, 25000, 1.0, 0.75, 1e-7)]
+    for (w, mx, mn, per, tm, sh, init) in cases:
+        ts = list(range(0, 400)) + [1000, 4001, 29000, 29001, 54001, 10 ** 6, 10 ** 7 + 3]
+        for t in ts:
+            a, b = T.lr_cosine_restarts(t, w, mx, mn, per, tm, sh, init), lr_cosine_restarts(t, w, mx, mn, per, tm, sh, init)
+            assert math.isclose(a, b, rel_tol=1e-9, abs_tol=1e-15), (w, per, tm, t, a, b)
+    assert math.isnan(T.lr_cosine_restarts(-1, 0, 1.0, 0.0, 10)) and math.isnan(T.lr_cosine_restarts(1, 0, 1.0, 0.0, 10, 0.9))
 
 
 def test_library_batching_matches(T):
