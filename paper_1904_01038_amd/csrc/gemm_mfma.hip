@@ -24,8 +24,12 @@
 //    bias / ReLU / ReLU-mask / residual reads and the stores are whole 128-byte lines.
 //  * Block ids are re-mapped so that each XCD (blocks are dealt round-robin to the 8 XCDs, each with its own L2) works
 //    on a contiguous run of tiles.
-//  * Weight-gradient shapes with few output tiles split K across blockIdx.y; fp32 partial tiles are added in a fixed
-//    order by a second kernel (no atomics, reproducible).
+//  * Weight gradients: a single projection's dY^T X has 16-256 output tiles, too few for 256 compute units.  The training
+//    step therefore queues them and launches the tiles of up to 48 products end to end as ONE grouped launch
+//    (gemm_mfma_grouped_kernel; problem table in the kernel arguments; the first tile column of each product also sums
+//    the rows of dY^T it already holds as fragments, which is the bias gradient).  A weight gradient launched on its
+//    own can instead split K across blockIdx.y; fp32 partial tiles are then added in a fixed order by a second kernel
+//    (no atomics, reproducible).
 #include <stdlib.h>
 
 #include <algorithm>
