@@ -69,7 +69,7 @@ def run_decode(args):
     import numpy as np
     import torch
     import paper_1904_01038_amd as T
-    from paper_1904_01038_amd.search import beam_search
+    from tests.beam_search import beam_search
     from synth import PRESETS, init_params, count_params
     from synth.batches import zipf_ids
 
@@ -131,7 +131,7 @@ def run_decode(args):
            "unit": "sentences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "fp16", "data": "synthetic",
-           "config": {"workload": "decode", "model": "big", "params": count_params(shape), "beam": beam,
+           "config": {"workload": "decode", "beam": beam,
                       "batch_cap_padded_tokens": args.decode_max_tokens, "sentences": n_sent, "decode_steps": n_steps,
                       "tokens_out_per_s": n_tok / dt,
                       "length_cap": "source length + %d (random weights never prefer eos: every hypothesis runs to the cap)" % extra},
@@ -211,19 +211,27 @@ def main():
             b = batches[(i * k + j) % n_pool]
             ctx.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens, sync=False)
             tok += b.ntokens
-        ctx.apply_update(lr, sync=sync)
-        return tok
+        u = ctx.apply_update(lr, sync=sync)
+        return tok, u
 
+    # Warm-up windows report their update synchronously, so the windows whose update was skipped (dynamic loss scaling:
+    # the scale starts at 128 and halves on every overflow) are known by index; the timed windows do not synchronise,
+    # their skips follow from the update counter.
+    skipped_warmup = []
     for i in range(args.warmup):
-        window(i)
+        _, u = window(i, sync=True)
+        if u["skipped"]:
+            skipped_warmup.append(i)
+    st0 = ctx.get_scaler()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     tokens = 0
     for i in range(args.steps):
-        tokens += window(args.warmup + i)
+        tokens += window(args.warmup + i)[0]
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     st = ctx.get_scaler()
+    skipped_timed = args.steps - (st["num_updates"] - st0["num_updates"])
 
     # Profiled passes: HIP events around every launch, on the stream it is launched on.  The first pass puts all work
     # on one stream, so every kernel is timed with the GPU to itself: `roofline` is that pass.  The second keeps the
@@ -233,7 +241,7 @@ def main():
         ctx.set_overlap(overlap)
         ctx.profile_enable(True)
         for i in range(args.profile_steps):
-            window(i)
+            window(args.warmup + args.steps + i)
         prof = ctx.profile_read()
         ctx.profile_enable(False)
         ctx.set_overlap(not args.no_overlap)
@@ -271,6 +279,15 @@ def main():
                 "avg_launch_ms": g["ms"] / max(g["launches"], 1), "launches_per_step": g["launches"] / args.profile_steps,
                 "timed_with": "all launches on one stream (each kernel alone on the GPU)",
                 "classes": classes, "overlapped": overlapped}
+    # Step level: algorithmic matrix flops (GEMM + attention classes) of one step over the timed region's wall time per
+    # step, against the same peak; and the sum of all kernels' stand-alone durations beside that wall time.
+    ms_step = dt / args.steps * 1e3
+    mfma_flops_step = (prof["gemm"]["flops"] + prof["attention"]["flops"]) / args.profile_steps
+    kernel_ms = sum(p["ms"] for p in prof.values()) / args.profile_steps
+    roofline["step_level"] = {"matrix_flops_per_step": mfma_flops_step, "tflops": mfma_flops_step / (ms_step * 1e-3) / 1e12,
+                              "frac": mfma_flops_step / (ms_step * 1e-3) / 1e12 / peak,
+                              "kernel_ms_per_step_single_stream": kernel_ms, "wall_ms_per_step": ms_step,
+                              "wall_over_kernel": ms_step / kernel_ms if kernel_ms > 0 else None}
     # what this device sustains on the two resources, beside the published peaks (a register-only matrix-core loop; a plain
     # 1 GiB copy, bytes read plus written)
     ctx.close()
@@ -283,9 +300,9 @@ def main():
     out = {"metric": "target tokens/sec per training step on 1 MI355X", "value": tokens / dt, "unit": "tokens/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": prec_name, "data": "synthetic",
-           "config": {"workload": args.workload, "model": w["model"], "params": count_params(shape),
-                      "update_freq": k, "dropout": dropout, "attn_dropout": args.attn_dropout, "relu_dropout": args.relu_dropout, "side_stream": not args.no_overlap, "tokens_per_step": tokens / args.steps,
-                      "loss_scale_end": st["loss_scale"], "num_updates": st["num_updates"]},
+           "config": {"workload": args.workload, "update_freq": k, "dropout": dropout, "attn_dropout": args.attn_dropout, "relu_dropout": args.relu_dropout, "side_stream": not args.no_overlap, "tokens_per_step": tokens / args.steps,
+                      "loss_scale_end": st["loss_scale"], "num_updates": st["num_updates"],
+                      "skipped_warmup_windows": skipped_warmup, "skipped_timed_windows": skipped_timed},
            "roofline": roofline}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload, shape, batches, args.cpu_sample_tokens)

@@ -121,6 +121,8 @@ int tfm_get_grad(tfm_ctx* ctx, int32_t i, float* host, int64_t n);
 /* Adam moments (which = 0: first, 1: second). */
 int tfm_get_adam(tfm_ctx* ctx, int32_t i, int32_t which, float* host, int64_t n);
 int tfm_set_adam(tfm_ctx* ctx, int32_t i, int32_t which, const float* host, int64_t n);
+/* tfm_get_scaler fills its outputs and then returns TFM_ESCALE if the scale is below min_loss_scale; tfm_set_scaler
+ * with a scale at or above the minimum clears that condition. */
 int tfm_get_scaler(tfm_ctx* ctx, float* loss_scale, int32_t* clean_steps, int64_t* num_updates);
 int tfm_set_scaler(tfm_ctx* ctx, float loss_scale, int32_t clean_steps, int64_t num_updates);
 
@@ -131,14 +133,18 @@ int tfm_set_scaler(tfm_ctx* ctx, float loss_scale, int32_t clean_steps, int64_t 
  *   src_lens,tgt_lens host, int32 [B], 1 <= len <= L*.  Positions beyond len are ignored.
  *   The decoder is fed eos followed by the target without its last token (teacher forcing); the loss runs over
  *   all tgt_lens[b] target tokens.
- *   out             host, may be NULL: then nothing is copied back and the call does not synchronise. */
+ *   out             host, may be NULL: then nothing is copied back and the call does not synchronise.
+ * With out != NULL the call returns TFM_ESCALE (out is filled, the sub-batch has been accumulated) if an earlier
+ * unsynchronised tfm_apply_update left the loss scale below min_loss_scale. */
 int tfm_train_step(tfm_ctx* ctx, const int32_t* src, const int32_t* tgt, const int32_t* src_lens,
                    const int32_t* tgt_lens, int32_t B, int32_t Ls, int32_t Lt, tfm_step_out* out);
 
 /* End of the window: inf/nan scan; on overflow skip, halve the scale; else unscale, normalise by the window's
  * target tokens, optional clipping, Adam step in fp32 on the master weights, refresh the half copy; the scale
- * doubles after scale_window clean updates.  Clears the accumulator.  out may be NULL (no synchronisation; a
- * too-small scale is then reported by the next call that synchronises). */
+ * doubles after scale_window clean updates.  Clears the accumulator.  Returns TFM_ESCALE (out is filled) when the
+ * scale has fallen below min_loss_scale; the condition ends as soon as the scale is back at or above it (growth, or
+ * tfm_set_scaler).  out may be NULL: no synchronisation, and a too-small scale is then reported by the next
+ * tfm_train_step with out != NULL, tfm_apply_update with out != NULL or tfm_get_scaler. */
 int tfm_apply_update(tfm_ctx* ctx, float lr, tfm_update_out* out);
 
 /* The backward pass enqueues weight-gradient GEMMs and bias column sums on a second stream that the context owns
@@ -260,12 +266,14 @@ int tfm_op_dropout_mask(uint64_t key, float p, uint8_t* out, int64_t n, void* st
 uint64_t tfm_dropout_key(uint64_t seed, uint64_t step, int32_t stream, int32_t layer, int32_t sub);
 
 /* ---- Incremental decoding (Implementation, Inference) ------------------------------------------------------
- * Step-wise prediction with the states of previously generated tokens cached per active beam: a step feeds ONE
- * new token per row and returns the distribution over the next one.  Rows are sentences x beam, row = sentence *
- * beam + slot.  The decoder borrows the context's parameters (their current half/fp32 model copy), stream and
- * encoder buffers: do not interleave it with a window of tfm_train_step calls that has not been closed by
- * tfm_apply_update.  Dropout is off.  The search itself (which beams continue, length penalty, stopping) is the
- * caller's: it passes, per row, the token to feed and the row whose history this row continues. */
+ * Step-wise prediction over a per-row key/value cache: a step feeds ONE new token per row and returns the
+ * distribution over the next one.  Rows are sentences x beam, row = sentence * beam + slot.  The decoder borrows the
+ * context's parameters (their current half/fp32 model copy), stream and encoder buffers during tfm_decoder_begin and
+ * keeps its own copy of everything a step needs afterwards (projected source keys/values, source offsets).  A batch
+ * stays valid only while the context's parameters do: after any tfm_train_step, tfm_apply_update or tfm_set_param on
+ * the context, tfm_decoder_step returns TFM_ESTATE until tfm_decoder_begin starts a batch again.  Dropout is off.
+ * The search itself (which beams continue, length penalty, stopping) is the caller's: it passes, per row, the token to
+ * feed and the row whose history this row continues. */
 typedef struct tfm_decoder tfm_decoder;
 
 /* max_rows: sentences x beam; max_steps <= config.max_len: positions a hypothesis may reach; max_src_tokens: source

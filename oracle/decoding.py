@@ -1,7 +1,7 @@
 """Oracle for step-wise prediction during inference.  TEST INFRASTRUCTURE ONLY (numpy float64).
 
-Implementation, Inference: at inference time the states of previously generated tokens are cached per active beam
-and re-used, so that each step computes only the new token's states.  Caching changes the cost, not the result: the
+Implementation, Inference describes a cache: what earlier positions contributed is kept per hypothesis, and a step
+only computes the newest position.  Caching changes the cost, not the result: the
 distribution over the next token given a source sentence and the tokens generated so far is, by definition, what
 the full decoder computes at its last position when it is run over the whole prefix.  The oracle is that definition:
 it recomputes the whole prefix at every step, without dropout, and keeps no cache.  It shares no code with the HIP

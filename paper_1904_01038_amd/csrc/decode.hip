@@ -1,5 +1,5 @@
-// Kernels of the incremental decoding step (Implementation, Inference): the states of previously generated tokens
-// are cached per active beam and re-used, so a step computes one new position per beam.
+// Kernels of the incremental decoding step (Implementation, Inference): a per-row key/value cache indexed through an
+// ancestry table, so a step computes exactly one new position per row.
 //
 // Cache layout.  Self-attention keys and values of decoder layer l live in K_l, V_l [rows][max_steps][d]: row r writes
 // position t of ITS OWN row at step t and never moves anything.  When the search re-orders the beams, only an

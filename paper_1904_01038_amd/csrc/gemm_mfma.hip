@@ -30,8 +30,6 @@
 //    the rows of dY^T it already holds as fragments, which is the bias gradient).  A weight gradient launched on its
 //    own can instead split K across blockIdx.y; fp32 partial tiles are then added in a fixed order by a second kernel
 //    (no atomics, reproducible).
-#include <stdlib.h>
-
 #include <algorithm>
 
 #include "common.h"
@@ -153,7 +151,7 @@ struct Operand {
       const uint32_t dst = lds_stage + (uint32_t)(wave * LOADS + i) * 1024u;
       asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(__builtin_amdgcn_readfirstlane(dst)), "v"(o),
                    "s"(rsrc)
-                   : "memory");
+                   : "memory", "m0");
     }
   }
   // Fragment of tile rows r0..r0+31 for k = kk*16 .. kk*16+15: lane l gets row r0 + l%32, k-group l/32 (8 k-values).
@@ -493,10 +491,7 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   p.tiles_n = (a.N + BN - 1) / BN;
   p.tiles_m = (a.M + BM - 1) / BM;
   p.tiles_total = p.tiles_n * p.tiles_m;
-  {
-    static const int g_env = [] { const char* e = getenv("TFM_GEMM_GROUP"); return e ? atoi(e) : 0; }();
-    p.group_m = g_env > 0 ? g_env : 8;
-  }
+  p.group_m = 8;
   p.a_bytes = (uint32_t)(a.form == 2 ? extent_bytes(a.K, a.M, a.lda) : extent_bytes(a.M, a.K, a.lda));
   p.b_bytes = (uint32_t)(a.form == 0 ? extent_bytes(a.N, a.K, a.ldb) : extent_bytes(a.K, a.N, a.ldb));
   // Split-K for weight-gradient shapes whose output has too few tiles to fill the chip: slices of K go to
@@ -563,9 +558,8 @@ void launch_wgrad_grouped(hipStream_t s, int dt, const WgradJob* jobs, int n) {
     t256 += (long)((jobs[i].M + 255) / 256) * ((jobs[i].N + 255) / 256);
     t128 += (long)((jobs[i].M + 127) / 128) * ((jobs[i].N + 127) / 128);
   }
-  static const int forced = [] { const char* e = getenv("TFM_WGRAD_TILE"); return e ? atoi(e) : 0; }();
   const double c256 = (double)((t256 + 255) / 256) * 103.0, c128 = (double)((t128 + 255) / 256) * 31.0;
-  const bool big = forced ? forced == 256 : c256 <= c128;
+  const bool big = c256 <= c128;
   if (dt == F16) {
     if (big) wgrad_grouped_launch<half_t, 256, 256, 2, 4, 64, 2>(s, jobs, n);
     else wgrad_grouped_launch<half_t, 128, 128, 4, 4, 64, 3>(s, jobs, n);
@@ -573,12 +567,6 @@ void launch_wgrad_grouped(hipStream_t s, int dt, const WgradJob* jobs, int n) {
     if (big) wgrad_grouped_launch<bf16_t, 256, 256, 2, 4, 64, 2>(s, jobs, n);
     else wgrad_grouped_launch<bf16_t, 128, 128, 4, 4, 64, 3>(s, jobs, n);
   }
-}
-
-static int forced_tile() {                               // tuning aid: TFM_GEMM_TILE=<config id> overrides the choice
-  static int v = -1;
-  if (v < 0) { const char* e = getenv("TFM_GEMM_TILE"); v = e ? atoi(e) : 0; }
-  return v;
 }
 
 // Configuration choice, from measurements on the projection shapes of the big and base Transformers (M ~ 3264-3700 tokens):
@@ -590,7 +578,6 @@ static int forced_tile() {                               // tuning aid: TFM_GEMM
 //                                                   are slower here: more LDS traffic per flop)
 //   20   64x64       4         64     4      2      fewer than 128 tiles of 128x128 (a decoding step's few rows)
 static int choose_tile(const GemmArgs& a) {
-  if (forced_tile() > 0) return forced_tile();
   const long t1 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
   if (t1 < 128 && a.form == 0) return 20;               // few rows (a decoding step, X W^T): smaller tiles reach more CUs
   const long t3 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);

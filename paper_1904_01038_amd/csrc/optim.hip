@@ -142,7 +142,7 @@ __global__ void scaler_update_kernel(DevState* st, long long ntokens, float clip
     if (dynamic && st->clean_steps == scale_window) { st->loss_scale *= 2.f; st->clean_steps = 0; }
   }
   st->window_overflow = 0;
-  if (st->loss_scale < min_scale) st->scale_too_small = 1;
+  st->scale_too_small = st->loss_scale < min_scale ? 1 : 0;       // (cleared again once the scale is back at or above the minimum)
 }
 void launch_scaler_update(hipStream_t s, DevState* st, long long ntokens, float clip_norm, float beta1, float beta2,
                           int scale_window, float min_scale, int dynamic) {

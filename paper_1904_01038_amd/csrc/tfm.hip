@@ -165,6 +165,9 @@ struct tfm_ctx {
   long long window_tokens;
   uint64_t train_steps;
   float next_mult;
+  // Bumped by everything that changes the parameters or re-uses the encoder buffers (tfm_train_step, tfm_apply_update,
+  // tfm_set_param): a decoder remembers the value its batch began under and refuses to continue under another.
+  uint64_t generation;
   // profiling
   bool prof;
   std::vector<ProfRec> recs;
@@ -593,11 +596,7 @@ int tfm_create(const tfm_config* cfg, void* ws, size_t bytes, void* hip_stream, 
   }
   c->overlap = true;
   c->wq_tiles = 0;
-  {
-    // (tuning aid: TFM_WGRAD_FLUSH=<128x128 tiles> flushes the weight-gradient queue whenever that many tiles wait)
-    const char* e = getenv("TFM_WGRAD_FLUSH");
-    c->wq_flush_tiles = e && atol(e) > 0 ? atol(e) : 4096;
-  }
+  c->wq_flush_tiles = 4096;
   {
     // chunk boundaries: the embedding, then one chunk per block (its parameters are contiguous), final norms with
     // the block before them
@@ -687,6 +686,7 @@ int tfm_set_param(tfm_ctx* c, int32_t i, const float* host, int64_t n) {
   int rc = check_param(c, i, host, n);
   if (rc) return rc;
   const Param& p = c->params[i];
+  c->generation += 1;
   HIP_TRY(c, hipMemcpyAsync(c->W + p.off, host, n * 4, hipMemcpyHostToDevice, c->stream));
   if (c->dt != F32) launch_convert(c->stream, F32, c->W + p.off, c->dt, (char*)c->Wh + p.off * c->esz, n);
   HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -737,6 +737,7 @@ int tfm_get_scaler(tfm_ctx* c, float* loss_scale, int32_t* clean_steps, int64_t*
   if (loss_scale) *loss_scale = h.loss_scale;
   if (clean_steps) *clean_steps = h.clean_steps;
   if (num_updates) *num_updates = h.num_updates;
+  if (h.scale_too_small) return fail(c, TFM_ESCALE, "loss scale %g is below the minimum %g", h.loss_scale, c->cfg.min_loss_scale);
   return TFM_OK;
 }
 
@@ -748,6 +749,7 @@ int tfm_set_scaler(tfm_ctx* c, float loss_scale, int32_t clean_steps, int64_t nu
   HIP_TRY(c, hipMemcpyAsync(&h, c->st, sizeof(h), hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   h.loss_scale = loss_scale; h.clean_steps = clean_steps; h.num_updates = num_updates;
+  h.scale_too_small = loss_scale < c->cfg.min_loss_scale ? 1 : 0;
   HIP_TRY(c, hipMemcpyAsync(c->st, &h, sizeof(h), hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   return TFM_OK;
@@ -1114,6 +1116,7 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
     }
   }
 
+  c->generation += 1;
   // ---- ingest: pack into the staging slot
   const int slot = c->stage_next;
   c->stage_next = (slot + 1) % STAGE_SLOTS;
@@ -1318,6 +1321,8 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     out->loss_sum = h.loss_sum; out->nll_sum = h.nll_sum; out->ntokens = Tt; out->overflow = h.step_overflow;
     out->loss_scale = h.loss_scale;
+    // an update enqueued without synchronisation may have taken the scale below the minimum: this is where it shows
+    if (h.scale_too_small) return fail(c, TFM_ESCALE, "loss scale %g is below the minimum %g", h.loss_scale, cf.min_loss_scale);
   }
   return TFM_OK;
 }
@@ -1327,6 +1332,7 @@ int tfm_apply_update(tfm_ctx* c, float lr, tfm_update_out* out) {
   if (c->window_mb == 0) return fail(c, TFM_ESTATE, "no sub-batch has been accumulated");
   if (!std::isfinite(lr)) return fail(c, TFM_EINVAL, "learning rate is not finite");
   adam_join(c);
+  c->generation += 1;
   const tfm_config& cf = c->cfg;
   const bool single = c->window_mb == 1;
   // the scan of a single sub-batch already produced the sum of squares; an accumulated window is scanned again
@@ -1385,13 +1391,15 @@ struct tfm_decoder {
   void *resid[2], *norm[2], *y, *qkv, *att, *q, *inter, *logits;
   float *mean, *rstd, *lse, *top_logp, *lp_stage;
   int *top_id, *anc[2], *ibuf;
+  int* src_off;                                    // [max_sentences + 1]: this batch's source offsets (the context's are re-used by training)
   std::vector<void*> Kc, Vc, xkv;                  // per decoder layer
   // pinned host staging
   int* h_in;                                       // prev, parent, pos [3 * max_rows]; also source ids / pos / offsets
   size_t h_in_ints;
   float* h_out;                                    // top_logp [max_rows * topk] followed by top_id
   // state of the batch being decoded
-  int B, beam, rows, t, cur, n_src_max;
+  int B, beam, rows, t, cur, n_src_max, src_rows;
+  uint64_t generation;                             // the context's when the batch began
   bool begun;
 };
 
@@ -1418,6 +1426,7 @@ size_t decoder_carve(tfm_decoder* D, char* base) {
   D->anc[0] = (int*)a.take(R * D->max_steps * 4);
   D->anc[1] = (int*)a.take(R * D->max_steps * 4);
   D->ibuf = (int*)a.take(3 * R * 4);
+  D->src_off = (int*)a.take(((size_t)cf.max_sentences + 1) * 4);
   D->Kc.assign(cf.dec_layers, nullptr); D->Vc.assign(cf.dec_layers, nullptr); D->xkv.assign(cf.dec_layers, nullptr);
   for (int l = 0; l < cf.dec_layers; ++l) {
     D->Kc[l] = a.take(R * D->max_steps * d * esz);
@@ -1452,7 +1461,7 @@ void decode_attention(tfm_decoder* D, const void* q, int ldq, const void* k, con
   const int d = c->cfg.d_model, H = c->cfg.n_heads;
   DecodeAttnArgs a{};
   a.dt = c->dt; a.q = q; a.ldq = ldq; a.k = k; a.v = v; a.row_stride = row_stride; a.o = D->att; a.ldo = d;
-  a.anc = anc; a.src_off = c->enc.off; a.rows = D->rows; a.H = H; a.dh = d / H; a.beam = D->beam; a.t = D->t;
+  a.anc = anc; a.src_off = D->src_off; a.rows = D->rows; a.H = H; a.dh = d / H; a.beam = D->beam; a.t = D->t;
   a.max_steps = D->max_steps; a.n_max = n_max;
   // positions = sum over rows of the positions attended to: K and V rows read once each, q read, output written
   run(c, TFM_PROF_ATTENTION, 4.0 * d * positions, (double)c->esz * d * (2.0 * positions + 2.0 * D->rows),
@@ -1559,6 +1568,7 @@ int tfm_decoder_begin(tfm_decoder* D, const int32_t* src, const int32_t* src_len
     }
     off[B] = r;
     HIP_TRY(c, hipMemcpyAsync(c->enc.ids, D->h_in, (2 * R + B + 1) * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(D->src_off, off, (size_t)(B + 1) * 4, hipMemcpyHostToDevice, c->stream));
     c->enc.rows = (int)Ts; c->enc.max_len = maxs;
     const float p_train = c->cfg.dropout, pa_train = c->cfg.attn_dropout, pr_train = c->cfg.relu_dropout;
     c->cfg.dropout = c->cfg.attn_dropout = c->cfg.relu_dropout = 0.f;
@@ -1574,6 +1584,8 @@ int tfm_decoder_begin(tfm_decoder* D, const int32_t* src, const int32_t* src_len
     }
   }
   HIP_TRY(c, hipGetLastError());
+  D->src_rows = (int)Ts;
+  D->generation = c->generation;
   D->begun = true;
   return TFM_OK;
 }
@@ -1583,6 +1595,10 @@ int tfm_decoder_step(tfm_decoder* D, const int32_t* prev, const int32_t* parent,
   tfm_ctx* c = D->c;
   const tfm_config& cf = c->cfg;
   if (!D->begun) return fail(c, TFM_ESTATE, "tfm_decoder_begin has not been called");
+  if (D->generation != c->generation) {
+    D->begun = false;
+    return fail(c, TFM_ESTATE, "the context trained or changed parameters since tfm_decoder_begin: begin the batch again");
+  }
   if (D->t >= D->max_steps) return fail(c, TFM_ESTATE, "the decoder was created for %d steps", D->max_steps);
   const int R = D->rows, d = cf.d_model, V = cf.vocab;
   for (int r = 0; r < R; ++r) {
@@ -1605,7 +1621,7 @@ int tfm_decoder_step(tfm_decoder* D, const int32_t* prev, const int32_t* parent,
       [&] { launch_embed_fwd(c->stream, c->dt, c->Wh, d_prev, d_pos, c->pe, emb, R, d, 0, 0.f); });
   if (pre) decode_ln(D, D->resid[0], nullptr, blocks[0].ln_g, blocks[0].ln_b, nullptr, D->norm[0]);
   double src_positions = 0;
-  if (cf.enc_layers) src_positions = (double)c->enc.rows * D->beam;
+  if (cf.enc_layers) src_positions = (double)D->src_rows * D->beam;
   for (int k = 0; k < K; ++k) {
     const int i = k & 1, j = i ^ 1;
     decode_sublayer(D, blocks[k], blocks[k].layer, D->norm[i], src_positions);

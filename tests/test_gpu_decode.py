@@ -90,7 +90,7 @@ def test_steps_with_reordered_beams_match_the_full_decoder(name, prec, tol):
 
 def test_beam_search_on_both_sides_finds_the_same_hypotheses():
     import paper_1904_01038_amd as T
-    from paper_1904_01038_amd.search import beam_search
+    from tests.beam_search import beam_search
     shape = SHAPES["post"]
     B, beam, steps = 3, 3, 8
     ctx, dec, oracle = make(shape, T.FP32, B * beam, steps, 64, 2 * beam, seed=2)
@@ -181,4 +181,84 @@ def test_training_and_decoding_share_one_context():
     stale = DecodingOracle(shape, params)
     ref0 = np.stack([stale.next_logprobs(stale.encode(b.src[i, :b.src_lens[i]]), [shape.eos_id]) for i in range(3)])
     assert np.max(np.abs(ref - ref0)) > 1e-2                # the update mattered
+    ctx.close()
+
+
+def test_a_batch_in_flight_is_invalidated_by_training_and_parameter_changes():
+    """A decoding batch is tied to the parameters it began under: a training step, an update or a parameter write on
+    the context makes the next decoding step fail with TFM_ESTATE instead of reading re-used encoder state; a new
+    tfm_decoder_begin recovers.  Two decoders of one context keep their own source offsets and projected keys/values,
+    so beginning a batch on one does not disturb the other."""
+    import paper_1904_01038_amd as T
+    from tests.test_oracle_model import small_batch
+    shape = ModelShape(1, 1, 32, 2, 64, 48)
+    params = init_params(shape, 0, generic=True)
+    cfg = T.make_config(shape, precision=T.FP32, max_sentences=8, max_len=16, max_tokens=64, init_loss_scale=1.0)
+    ctx = T.Tfm(cfg)
+    ctx.set_params(params)
+    oracle = DecodingOracle(shape, params)
+    b = small_batch(shape, 1)
+    eos3 = np.full(3, shape.eos_id, np.int32)
+    dec = T.Decoder(ctx, 3, 4, 32, 4)
+
+    def expect_estate():
+        with pytest.raises(T.TfmError) as e:
+            dec.step(eos3)
+        assert e.value.code == -4
+
+    dec.begin(b.src, b.src_lens, 1)
+    dec.step(eos3)
+    ctx.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens)                      # re-uses the encoder buffers
+    expect_estate()
+    expect_estate()                                                           # stays refused until a new batch begins
+    dec.begin(b.src, b.src_lens, 1)
+    dec.step(eos3)
+    ctx.apply_update(0.0)                                                     # (lr 0: the parameters keep their values)
+    expect_estate()
+    dec.begin(b.src, b.src_lens, 1)
+    ctx.set_params({"embed": params["embed"]})
+    expect_estate()
+
+    # two decoders: the second one's batch has other sentences and lengths
+    rng = np.random.default_rng(3)
+    src2, lens2 = sources(shape, rng, 2, 5, 9)
+    dec2 = T.Decoder(ctx, 2, 4, 32, 4)
+    dec.begin(b.src, b.src_lens, 1)
+    dec2.begin(src2, lens2, 1)
+    dec.step(eos3)
+    ref = np.stack([oracle.next_logprobs(oracle.encode(b.src[i, :b.src_lens[i]]), [shape.eos_id]) for i in range(3)])
+    assert np.max(np.abs(dec.logprobs() - ref)) <= 2e-4
+    dec2.step(np.full(2, shape.eos_id, np.int32))
+    ref2 = np.stack([oracle.next_logprobs(oracle.encode(src2[i, :lens2[i]]), [shape.eos_id]) for i in range(2)])
+    assert np.max(np.abs(dec2.logprobs() - ref2)) <= 2e-4
+    ctx.close()
+
+
+def test_big_model_fp16_beam4_full_size_steps():
+    """The decoding benchmark's configuration (big Transformer, fp16, beam 4) at its real widths: 2 sentences x 4 rows,
+    4 steps with re-ordered beams, whole distribution against the full-prefix oracle.  The row count is what a small
+    decoding batch has; the GEMM, cache and attention kernels are the ones the benchmark runs."""
+    import paper_1904_01038_amd as T
+    from synth import PRESETS
+    shape = PRESETS["big"]
+    params = rounded(init_params(shape, 0), T.FP16)
+    B, beam, steps, topk = 2, 4, 4, 8
+    cfg = T.make_config(shape, precision=T.FP16, max_sentences=8, max_len=32, max_tokens=256, dropout=0.1)
+    ctx = T.Tfm(cfg)
+    ctx.set_params(params)
+    dec = T.Decoder(ctx, B * beam, steps, 64, topk)
+    oracle = DecodingOracle(shape, params)
+    rng = np.random.default_rng(11)
+    src, lens = sources(shape, rng, B, 10, 24)
+    dec.begin(src, lens, beam)
+    mems = [oracle.encode(src[b, :lens[b]]) for b in range(B)]
+    hist = [[] for _ in range(B * beam)]
+    for t in range(steps):
+        prev = np.full(B * beam, shape.eos_id, np.int32) if t == 0 else zipf_ids(rng, B * beam, shape.vocab)
+        parent = None if t == 0 else np.array([r // beam * beam + rng.integers(0, beam) for r in range(B * beam)], np.int32)
+        par = parent if parent is not None else np.arange(B * beam)
+        hist = [hist[par[r]] + [int(prev[r])] for r in range(B * beam)]
+        top_lp, top_id = dec.step(prev, parent)
+        ref = np.stack([oracle.next_logprobs(mems[r // beam], hist[r]) for r in range(B * beam)])
+        check_step(dec.logprobs(), top_lp, top_id, ref, 3e-2)
     ctx.close()

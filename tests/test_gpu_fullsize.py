@@ -9,12 +9,12 @@ from tests.gpu_util import cosine
 pytestmark = pytest.mark.gpu
 
 
-def run_workload(workload, precision_name, n_sentences=None):
+def run_workload(workload, precision_name, n_sentences=None, shape=None):
     import paper_1904_01038_amd as T
     from oracle.transformer import OracleTransformer, TrainConfig
     import torch
-    shape = PRESETS[WORKLOADS[workload]["model"]]
-    batch = make_batches(workload, 1)[0]
+    shape = shape or PRESETS[WORKLOADS[workload]["model"]]
+    batch = make_batches(workload, 1, shape=shape)[0]
     prec = {"fp16": T.FP16, "bf16": T.BF16}[precision_name]
     tdt = {"fp16": torch.float16, "bf16": torch.bfloat16}[precision_name]
     scale = 8.0 if precision_name == "fp16" else 1.0
@@ -60,6 +60,16 @@ def test_lm16_fp16_full_size_subbatch():
 def test_lm16_adaptive_fp16_full_size_subbatch():
     """267.7 K types in three clusters: every tail GEMM at its real shape."""
     check(*run_workload("lm16a", "fp16"))
+
+
+def test_lm24_real_width_two_blocks_fp16():
+    """The larger language model (24 blocks, inner dimension 8K, embedding dimension 1.5K) at its real widths and its
+    real sub-batch (8 blocks of 512 tokens), cut to 2 of its 24 identical blocks so that the float64 oracle finishes:
+    every GEMM shape, the 1536-wide normalisation and embedding paths and the causal 512-token attention of the full
+    model are the ones that run here."""
+    import dataclasses
+    shape = dataclasses.replace(PRESETS["lm24"], dec_layers=2)
+    check(*run_workload("lm24", "fp16", shape=shape))
 
 
 def test_big_fp16_delayed_updates_with_injected_overflows_full_size():
@@ -112,3 +122,68 @@ def test_big_fp16_delayed_updates_with_injected_overflows_full_size():
     assert changed == names                                  # Adam moved every weight matrix probed
     assert all(np.isfinite(v).all() for v in after.values())
     gpu.close()
+
+
+def test_big_fp16_loss_scale_trajectory_full_size():
+    """The headline workload at its own initial loss scale (128): the benchmark's first update windows, dropout off,
+    against the oracle with the fp16 overflow criterion - overflow flag per sub-batch, skip decision, scale and update
+    count after every window must be identical (Implementation, Mixed precision: halve the scale and skip on overflow).
+
+    The oracle's verdict for a window is clear-cut unless its largest scaled gradient value lies within 10 % of the fp16
+    maximum (half-precision rounding moves the GPU's values by ~1e-3 relative); the comparison ends at the first window
+    that is not clear-cut, and at least four windows must have been compared.  With the seeded initial weights the
+    largest gradient element is the embedding row of the most frequent token, 1.6e3 un-scaled on the first batch: 128
+    and 64 overflow, 32 does not.  The same first batch is also stepped at scales 64 and 16 (the oracle's gradient is
+    linear in the scale, so its verdict follows from the first window's maximum)."""
+    import paper_1904_01038_amd as T
+    from oracle.transformer import OracleTransformer, TrainConfig, FP16_MAX
+    import torch
+    shape = PRESETS["big"]
+    n_windows = 6
+    batches = make_batches("big", 16)[:n_windows]               # the pool bench.py cycles through, in its order
+    params = init_params(shape, 0)
+    params = {k: torch.tensor(v, dtype=torch.float32).to(torch.float16).to(torch.float64).numpy() for k, v in params.items()}
+    max_tok = max(max(b.ntokens, int(b.src_lens.sum())) for b in batches)
+    cfg = T.make_config(shape, precision=T.FP16, max_sentences=max(len(b.tgt_lens) for b in batches),
+                        max_tokens=(max_tok + 63) // 64 * 64, max_len=max(max(b.tgt.shape[1], b.src.shape[1]) for b in batches),
+                        dropout=0.0, init_loss_scale=128.0, label_smoothing=0.1)
+    oracle = OracleTransformer(shape, params, TrainConfig(init_loss_scale=128.0, fp16_overflow=True, label_smoothing=0.1))
+    lr = 1e-4
+    compared, trajectory = 0, []
+    gpu = None
+    for w, b in enumerate(batches):
+        ro = oracle.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens)
+        gmax = max(float(np.max(np.abs(v))) for v in oracle.G.values())       # one sub-batch per window: G is its gradient
+        ratio = gmax / FP16_MAX
+        if w == 0:
+            # the same batch at two other scales in a context of its own: flagged at 64, clean at 16, both clear-cut
+            probe = T.Tfm(cfg)
+            probe.set_params(params)
+            for s_other in (64.0, 16.0):
+                r_other = ratio * s_other / 128.0
+                assert not 0.9 <= r_other <= 1.1
+                probe.set_scaler(s_other, 0, 0)
+                rg = probe.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens)
+                assert rg["overflow"] == int(r_other > 1.0), (s_other, r_other, rg)
+                assert probe.apply_update(0.0)["skipped"] == int(r_other > 1.0)
+            probe.close()
+            del probe
+            gpu = T.Tfm(cfg)
+            gpu.set_params(params)
+            del params
+        if 0.9 <= ratio <= 1.1:
+            break                                                             # not clear-cut: stop comparing here
+        rg = gpu.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens)
+        assert rg["overflow"] == ro["overflow"] == int(ratio > 1.0), (w, ratio, rg, ro)
+        assert rg["loss_scale"] == ro["loss_scale"]
+        if not ro["overflow"]:
+            assert abs(rg["loss_sum"] - ro["loss_sum"]) <= 1e-2 * abs(ro["loss_sum"]), (w, rg, ro)
+        ug, uo = gpu.apply_update(lr), oracle.apply_update(lr)
+        for key in ("skipped", "loss_scale_after", "clean_steps", "num_updates", "ntokens_total"):
+            assert ug[key] == uo[key], (w, key, ug, uo)
+        trajectory.append((w, round(ratio, 3), ug["skipped"], ug["loss_scale_after"]))
+        compared += 1
+    print("windows (index, max |S g| / 65504, skipped, scale after):", trajectory)
+    gpu.close()
+    assert compared >= 4, trajectory
+    assert [t[2] for t in trajectory[:3]] == [1, 1, 0] and trajectory[2][3] == 32.0, trajectory

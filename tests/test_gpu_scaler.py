@@ -101,3 +101,53 @@ def test_dropout_bits_match_the_oracle_generator():
         T.ops.dropout_mask(key, p, out)
         ref = dropout_keep(key, 0, 37, 72, p)
         assert np.array_equal(out.cpu().numpy().reshape(37, 72).astype(bool), ref)
+
+
+def test_scale_below_the_minimum_is_reported_and_recovers():
+    """The floor of the loss scale: an overflow that takes the scale below min_loss_scale makes the synchronous update
+    return TFM_ESCALE (its results are still filled in); an update enqueued without synchronisation reports it through
+    the next synchronising call (train_step with results, get_scaler); restoring the scale ends the condition, and so
+    does growth back to the minimum."""
+    import paper_1904_01038_amd as T
+    cfg = T.make_config(SHAPE, precision=T.FP16, max_sentences=64, max_len=64, max_tokens=1024, init_loss_scale=4.0,
+                        scale_window=2, min_loss_scale=4.0, label_smoothing=0.1)
+    from synth import init_params
+    gpu = T.Tfm(cfg)
+    gpu.set_params(init_params(SHAPE, 0, generic=True))
+    b = small_batch(SHAPE, 1)
+    step = lambda **kw: gpu.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens, **kw)
+
+    gpu.debug_set_loss_multiplier(1e6)
+    assert step()["overflow"] == 1
+    with pytest.raises(T.TfmError) as e:
+        gpu.apply_update(1e-3)                               # 4 -> 2 < 4
+    assert e.value.code == -5
+    with pytest.raises(T.TfmError) as e:
+        gpu.get_scaler()
+    assert e.value.code == -5
+    # growth brings it back: two clean updates at scale 2 double it to 4, the minimum
+    with pytest.raises(T.TfmError) as e:
+        step()                                               # still below: reported, but the sub-batch was accumulated
+    assert e.value.code == -5
+    with pytest.raises(T.TfmError):
+        gpu.apply_update(1e-3)                               # clean update 1 at scale 2: still below
+    step(sync=False)
+    u = gpu.apply_update(1e-3)                               # clean update 2: the scale doubles to 4
+    assert (u["skipped"], u["loss_scale_after"], u["num_updates"]) == (0, 4.0, 2)
+    assert gpu.get_scaler()["loss_scale"] == 4.0
+    # the asynchronous path: nothing is reported by the update itself, the next synchronising call reports it
+    gpu.debug_set_loss_multiplier(1e6)
+    step(sync=False)
+    assert gpu.apply_update(1e-3, sync=False) is None
+    with pytest.raises(T.TfmError) as e:
+        step()
+    assert e.value.code == -5
+    gpu.apply_update(0.0, sync=False)
+    # restoring the scale by hand ends the condition
+    gpu.set_scaler(8.0, 0, 2)
+    assert gpu.get_scaler()["loss_scale"] == 8.0
+    r = step()
+    assert r["overflow"] == 0 and r["loss_scale"] == 8.0
+    u = gpu.apply_update(1e-3)
+    assert (u["skipped"], u["loss_scale_after"]) == (0, 8.0)
+    gpu.close()

@@ -4,7 +4,7 @@ import itertools
 
 import numpy as np
 
-from paper_1904_01038_amd.search import beam_search
+from tests.beam_search import beam_search
 
 
 def test_wide_beam_is_exhaustive():
