@@ -259,6 +259,17 @@ int tfm_op_adam(float* w, float* m, float* v, const void* g, int32_t gdtype, voi
 int tfm_op_scan(int32_t dtype, const void* x, int64_t n, float* result, void* scratch, void* stream);
 size_t tfm_op_scan_scratch(int64_t n);
 
+/* tfm_op_scan for callers that cannot allocate device memory or pass a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same kernels and the same result, bit for bit, with the per-block
+ * partial results kept in a 16 KiB device array that the library holds on every GPU it runs on until the process ends.
+ * The call allocates and frees nothing.  x (device, `dtype`, n elements, n a multiple of 8) and result (device fp32 [2])
+ * are the caller's.  n above TFM_SCAN_NOALLOC_MAX_N returns TFM_EINVAL; tfm_last_error(NULL) then names the limit, or
+ * the HIP error for TFM_EHIP.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race on it and must be serialised by the caller.  Nothing needs clearing between calls: every
+ * launch overwrites the entries it later reads. */
+#define TFM_SCAN_NOALLOC_MAX_N ((int64_t)1 << 31)
+int tfm_op_scan_noalloc(int32_t dtype, const void* x, int64_t n, float* result, void* stream);
+
 /* Dropout keep bits of (key, p) for elements [0, n): out[i] = 1 or 0 (device uint8). */
 int tfm_op_dropout_mask(uint64_t key, float p, uint8_t* out, int64_t n, void* stream);
 /* Host helper: the 64-bit key of a dropout site (stream 0 encoder / 1 decoder; layer -1 = embedding;

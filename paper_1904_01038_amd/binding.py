@@ -116,6 +116,7 @@ def lib():
         L.tfm_op_scan_scratch.argtypes = [i64]
         L.tfm_op_scan_scratch.restype = C.c_size_t
         L.tfm_op_scan.argtypes = [i32, vp, i64, vp, vp, vp]
+        L.tfm_op_scan_noalloc.argtypes = [i32, vp, i64, vp, vp]
         L.tfm_op_dropout_mask.argtypes = [u64, f32, vp, i64, vp]
         L.tfm_dropout_key.argtypes = [u64, u64, i32, i32, i32]
         L.tfm_dropout_key.restype = u64

@@ -178,4 +178,7 @@ void launch_logprob_rows(hipStream_t s, int dt, const void* z, int ldz, const fl
 
 uint64_t dropout_site_key(uint64_t seed, uint64_t step, int stream, int layer, int sub);
 
+// message tfm_last_error(NULL) returns on this thread (entry points that have no context to hold it)
+void set_global_error(const char* msg);
+
 }  // namespace tfm

@@ -1,6 +1,9 @@
 // Inf/nan scan (+ optional accumulation into the fp32 window buffer), the loss-scale state machine, and the fp32
 // master-weight Adam update.  All HBM-bound streaming kernels with 16-byte accesses; reductions use per-block
 // partials added in a fixed order (no floating-point atomics), so every result is reproducible.
+#include <mutex>
+
+#include "../../include/tfm.h"
 #include "common.h"
 #include "kernels.h"
 
@@ -90,6 +93,32 @@ void launch_scan(hipStream_t s, int dt, const void* x, int64_t n, float* result,
   if (dt == F32) scan_dispatch<float>(s, x, n, result, st, acc, acc_mode, scratch);
   else if (dt == F16) scan_dispatch<half_t>(s, x, n, result, st, acc, acc_mode, scratch);
   else scan_dispatch<bf16_t>(s, x, n, result, st, acc, acc_mode, scratch);
+}
+
+// ---- the scan for callers that cannot allocate ------------------------------------------------------------------------------
+// Same kernels as launch_scan; the per-block partials live in a file-scope device array instead of caller memory.  Every
+// block writes its own two floats and the finishing kernel reads exactly the blocks of this launch, so nothing has to be
+// cleared between calls.  In host code the array's name is only a handle: its device address is looked up once per
+// device and kept.
+static __device__ __align__(256) float scan_static_scratch[2 * SCAN_MAX_BLOCKS];     // 16 KiB on every device the library runs on
+constexpr int SCAN_STATIC_DEVICES = 64;
+static float* g_scan_static_ptr[SCAN_STATIC_DEVICES];
+static std::mutex g_scan_static_mutex;
+
+// device address of scan_static_scratch on the current device, or null with *err set
+static float* scan_static_address(hipError_t* err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= SCAN_STATIC_DEVICES) { *err = hipErrorInvalidDevice; return nullptr; }
+  std::lock_guard<std::mutex> lock(g_scan_static_mutex);
+  if (!g_scan_static_ptr[dev]) {
+    float* p = nullptr;
+    *err = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scan_static_scratch));
+    if (*err != hipSuccess) return nullptr;
+    g_scan_static_ptr[dev] = p;
+  }
+  return g_scan_static_ptr[dev];
 }
 
 // ---- conversion ---------------------------------------------------------------------------------------------------------
@@ -202,3 +231,16 @@ void launch_adam(hipStream_t s, const AdamArgs& a) {
 }
 
 }  // namespace tfm
+
+extern "C" int tfm_op_scan_noalloc(int32_t dtype, const void* x, int64_t n, float* result, void* stream) {
+  using namespace tfm;
+  if (dtype < 0 || dtype > 2 || !x || !result || n < 0 || n % 8) { set_global_error("tfm_op_scan_noalloc: bad argument (dtype, null pointer, or n not a multiple of 8)"); return TFM_EINVAL; }
+  if (n > TFM_SCAN_NOALLOC_MAX_N) { set_global_error("tfm_op_scan_noalloc: n exceeds TFM_SCAN_NOALLOC_MAX_N"); return TFM_EINVAL; }
+  hipError_t e = hipSuccess;
+  float* scratch = scan_static_address(&e);
+  if (!scratch) { set_global_error(hipGetErrorString(e)); return TFM_EHIP; }
+  launch_scan((hipStream_t)stream, dtype, x, n, result, nullptr, nullptr, 0, scratch);
+  e = hipGetLastError();
+  if (e != hipSuccess) { set_global_error(hipGetErrorString(e)); return TFM_EHIP; }
+  return TFM_OK;
+}

@@ -186,6 +186,12 @@ int fail(tfm_ctx* c, int code, const char* fmt, ...) {
   return code;
 }
 
+}  // namespace
+namespace tfm {
+void set_global_error(const char* msg) { snprintf(g_create_error, sizeof(g_create_error), "%s", msg ? msg : ""); }
+}  // namespace tfm
+namespace {
+
 #define HIP_TRY(c, expr)                                                                          \
   do {                                                                                            \
     hipError_t e_ = (expr);                                                                       \

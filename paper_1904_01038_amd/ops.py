@@ -100,6 +100,15 @@ def scan(x, result):
     _check(lib().tfm_op_scan(_dt(x), _p(x), x.numel(), _p(result), _p(scratch), _stream()), "tfm_op_scan")
 
 
+def scan_noalloc(x, result):
+    """The scan through the entry point that allocates nothing (its partial results live in a static device array)."""
+    L = lib()
+    rc = L.tfm_op_scan_noalloc(_dt(x), _p(x), x.numel(), _p(result), _stream())
+    if rc:
+        from .binding import TfmError
+        raise TfmError(rc, "tfm_op_scan_noalloc: " + (L.tfm_last_error(None) or b"").decode())
+
+
 def dropout_mask(key, p, out):
     _check(lib().tfm_op_dropout_mask(key, p, _p(out), out.numel(), _stream()), "tfm_op_dropout_mask")
 
