@@ -569,18 +569,30 @@ void launch_wgrad_grouped(hipStream_t s, int dt, const WgradJob* jobs, int n) {
   }
 }
 
-// Configuration choice, from measurements on the projection shapes of the big and base Transformers (M ~ 3264-3700 tokens):
+// Configuration choice, from measurements on the projection shapes of the big and base Transformers (M ~ 3000-3700 tokens):
 //   id  tile     wavefronts  K-step  ring   resident blocks per CU
 //    1  128x128      4         32     3      3      more than 256 tiles and K < 3072: several blocks per CU keep it fed
 //   12  128x128     16         64     3      1      K >= 3072, or at most 256 tiles (one block per CU anyway): 16 wavefronts
 //                                                   of 32x32 hide the fetch latency that 4 of 64x64 exposed (10-15 % faster)
-//   13  256x256      8         64     2      1      >= 150 tiles of 256x256: half the bytes fetched per flop (16 wavefronts
-//                                                   are slower here: more LDS traffic per flop)
+//   13  256x256      8         64     2      1      half the bytes fetched per flop (16 wavefronts are slower here: more LDS
+//                                                   traffic per flop)
+//   14  192x256      8         64     2      1      X W^T and dY W only: where 256x256 leaves compute units idle (a 3072-wide
+//                                                   output of ~3200 rows has 156 tiles of 256x256 but 204 of 192x256 for
+//                                                   256 CUs: 31.5 -> 28.0 us; 3000 rows: 37.6 -> 27.3 us)
 //   20   64x64       4         64     4      2      fewer than 128 tiles of 128x128 (a decoding step's few rows)
+// A launch costs about rounds x (fixed + slope x K-steps), rounds = tiles over the 256 compute units rounded up (the last,
+// partly filled round takes as long as a full one); fixed / slope in us per round and 64-wide K-step, measured with
+// M = 3264: 11 / 1.45 for 256x256, 9.5 / 1.16 for 192x256, 4.4 / 0.48 for 128x128.
 static int choose_tile(const GemmArgs& a) {
   const long t1 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
   if (t1 < 128 && a.form == 0) return 20;               // few rows (a decoding step, X W^T): smaller tiles reach more CUs
   const long t3 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
+  const long t4 = (long)((a.M + 191) / 192) * ((a.N + 255) / 256);
+  const double ks = (double)((a.K + 63) / 64);
+  const double c128 = (double)((t1 + 255) / 256) * (4.4 + 0.48 * ks);
+  const double c256 = (double)((t3 + 255) / 256) * (11.0 + 1.45 * ks);
+  const double c192 = a.form == 2 ? 1e30 : (double)((t4 + 255) / 256) * (9.5 + 1.16 * ks);
+  if (c192 < c256 && c192 < c128) return 14;
   if (t3 >= 150) return 13;
   if (a.K >= 3072 || t1 <= 256) return 12;
   return 1;
@@ -591,6 +603,7 @@ static void gemm_mfma_dispatch(hipStream_t s, const GemmArgs& a) {
   switch (choose_tile(a)) {
     case 13: gemm_mfma_launch<T, 256, 256, 2, 4, 64, 2>(s, a); break;
     case 12: gemm_mfma_launch<T, 128, 128, 4, 4, 64, 3>(s, a); break;
+    case 14: gemm_mfma_launch<T, 192, 256, 2, 4, 64, 2>(s, a); break;   // (never chosen for A^T B: its A tile would be [k][192])
     case 20:                                            // (the [k][row] swizzle spans 16 vectors: NT form only)
       if (a.form == 0) gemm_mfma_launch<T, 64, 64, 2, 2, 64, 4>(s, a);
       else gemm_mfma_launch<T, 128, 128, 2, 2, 32, 3>(s, a);

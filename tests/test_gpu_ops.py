@@ -17,6 +17,9 @@ def _dtypes():
 
 GEMM_SHAPES = [  # M, N, K: several tiles plus ragged tails in every dimension
     (200, 136, 72), (128, 128, 64), (333, 264, 200), (1, 8, 8), (130, 8, 264), (257, 384, 1032),
+    # large outputs with short contractions: the 192x256 tiling (221 tiles, ragged in both directions) and the 256x256 tiling
+    # (221 tiles where 192x256 would need a second round)
+    (3200, 3080, 72), (3264, 4104, 40),
 ]
 
 
