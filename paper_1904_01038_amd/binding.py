@@ -104,9 +104,9 @@ def lib():
         L.tfm_probe_copy.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_double), vp]
         L.tfm_op_wgrad_grouped.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp]
         L.tfm_op_attention_fwd.argtypes = [i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, i32, i32, i32,
-                                           i32, i32, u64, f32, vp]
+                                           i32, i32, u64, f32, vp, i32, vp]
         L.tfm_op_attention_bwd.argtypes = [i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, i32, vp, i32, vp,
-                                           i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, u64, f32, vp]
+                                           i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, u64, f32, vp, i32, vp]
         L.tfm_op_residual_layernorm_fwd.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, u64, f32, vp]
         L.tfm_op_layernorm_bwd_scratch.argtypes = [i32, i32]
         L.tfm_op_layernorm_bwd_scratch.restype = C.c_size_t

@@ -74,6 +74,9 @@ struct AttnP {
   uint32_t drop_thr;
   float inv_keep;
   int H;
+  // Launches whose sentences all fit one 64-row chunk: consecutive sentences packed into one block (block g serves
+  // sentences groups[g] .. groups[g+1]-1, at most 64 query rows and 64 key rows in total); null: one sentence per block
+  const int* groups;
 };
 __device__ __forceinline__ uint64_t attn_drop_word(const AttnP& p, int qrow, int h, int j) {
   return drop_word(p.drop_key, ((((uint64_t)qrow * (uint64_t)p.H + (uint64_t)h) << 16) + (uint64_t)j) >> 2);
@@ -191,14 +194,25 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_
   __shared__ __attribute__((aligned(16))) uint16_t Vs[CH * PT];
   // Blocks are dispatched x fastest: x walks the (sentence, head) pairs and y the query chunks from the last one down, so
   // under a causal mask (chunk c loops over c + 1 key chunks) the longest blocks of the whole launch start first.
-  const int b = blockIdx.x / H, h = blockIdx.x - b * H;
-  const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;
+  // With a group table (one-chunk launches only) a block serves a run of consecutive sentences packed into one 64-row tile;
+  // a query then admits the keys klo .. khi-1 of the tile, those of its own sentence.
+  const int bi = blockIdx.x / H, h = blockIdx.x - bi * H;
+  const int b0 = p.groups ? p.groups[bi] : bi, b1 = p.groups ? p.groups[bi + 1] : bi + 1;
+  const int q0 = p.q_off[b0], lq = p.q_off[b1] - q0, k0 = p.k_off[b0], lk = p.k_off[b1] - k0;
   const int qstart = ((int)gridDim.y - 1 - (int)blockIdx.y) * 64;
   if (qstart >= lq) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int qi0 = qstart + wave * 32;
   const bool active = qi0 < lq;
   const int qi = qi0 + (lane & 31);
+  int klo = 0, khi = qi < lq ? lk : 0, qpos = qi;    // admissible keys of the tile; the query's position inside its sentence
+  if (p.groups) {
+    khi = 0;
+    for (int b = b0; b < b1; ++b) {
+      const int qs = p.q_off[b] - q0, qe = p.q_off[b + 1] - q0;
+      if (qi >= qs && qi < qe) { klo = p.k_off[b] - k0; khi = p.k_off[b + 1] - k0; qpos = qi - qs; }
+    }
+  }
   const uint16_t* Q = p.q + (size_t)q0 * p.ldq + h * DH;
   const uint16_t* K = p.k + (size_t)k0 * p.ldk + h * DH;
   const uint16_t* V = p.v + (size_t)k0 * p.ldv + h * DH;
@@ -235,13 +249,13 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int j = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const bool ok = j < lk && (!p.causal || j <= qi);
+        const bool ok = j >= klo && j < khi && (!p.causal || j - klo <= qpos);
         s[r] = ok ? s[r] * p.scale : -INFINITY;
         bm = fmaxf(bm, s[r]);
       }
       bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-      const float mn = fmaxf(m, bm);
-      // mn is finite from the first block on: key 0 is valid for every query
+      // (a query of a packed tile may admit no key of the first 32-key block: keep the running maximum out of exp then)
+      const float mn = fmaxf(fmaxf(m, bm), -3.0e38f);
       const float alpha = __expf(m - mn);
       float ps = 0.f;
 #pragma unroll
@@ -494,6 +508,10 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_BWD_MIN_WAVES) void attn_bwd_mfma_
 // bytes cover the 64 banks once) keep four blocks resident per CU.
 constexpr int PF = 72;
 
+// Short sentences are packed: a block serves a run of consecutive sentences whose query rows and key rows (contiguous in the
+// packed token layout) fill at most one 64-row tile each.  The products are formed over the whole tile; a weight counts
+// only where query and key belong to the same sentence, which each row looks up as the range of admissible partners
+// (QR: keys of a query's sentence, KR: queries of a key's sentence, both relative to the tile).
 template <typename T, bool DROP>
 __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[CH * PF];
@@ -502,8 +520,21 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p
   __shared__ __attribute__((aligned(16))) uint16_t Gs[CH * PF];
   __shared__ __attribute__((aligned(16))) float Ls[CH];
   __shared__ __attribute__((aligned(16))) float Ds[CH];
-  const int b = blockIdx.z, h = blockIdx.y;
-  const int q0 = p.q_off[b], lq = p.q_off[b + 1] - q0, k0 = p.k_off[b], lk = p.k_off[b + 1] - k0;   // both in [1, 64]
+  __shared__ int QR[CH], KR[CH];                     // partner range lo | hi << 8, own sentence's first row << 16
+  const int h = blockIdx.y;
+  const int b0 = p.groups ? p.groups[blockIdx.z] : (int)blockIdx.z, b1 = p.groups ? p.groups[blockIdx.z + 1] : b0 + 1;
+  const int q0 = p.q_off[b0], lq = p.q_off[b1] - q0, k0 = p.k_off[b0], lk = p.k_off[b1] - k0;   // both in [1, 64]
+  if (threadIdx.x < CH) {
+    const int r = threadIdx.x;
+    int qr = 0, kr = 0;                              // empty ranges for rows beyond the tile's sentences
+    for (int b = b0; b < b1; ++b) {
+      const int qs = p.q_off[b] - q0, qe = p.q_off[b + 1] - q0, ks = p.k_off[b] - k0, ke = p.k_off[b + 1] - k0;
+      if (r >= qs && r < qe) qr = ks | (ke << 8) | (qs << 16);
+      if (r >= ks && r < ke) kr = qs | (qe << 8) | (ks << 16);
+    }
+    QR[r] = qr;
+    KR[r] = kr;
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int own0 = wave * 32;                        // first own row of this wavefront (a query for dQ, a key for dK/dV)
   const int own = own0 + (lane & 31);
@@ -541,6 +572,7 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p
   if (own0 < lq) {
     // dQ^T[d][query] = K^T dS^T with S^T[key][query]: a lane owns one query, 16 keys in registers
     const float delta = Ds[own], L = Ls[own];
+    const int klo = QR[own] & 0xff, khi = (QR[own] >> 8) & 0xff, qpos = own - (QR[own] >> 16);   // position inside the sentence
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       const int j0 = kb * 32;
@@ -555,12 +587,13 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p
       }
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
+        // (with dropout a block serves one sentence, so tile keys are sentence keys and a word covers 4 of them)
         const uint64_t w = DROP ? attn_drop_word(p, q0 + own, h, j0 + 8 * g + 4 * half) : 0;
 #pragma unroll
         for (int f = 0; f < 4; ++f) {
           const int r = g * 4 + f;
           const int jj = j0 + 8 * g + 4 * half + f;
-          const bool ok = jj < lk && own < lq && (!p.causal || jj <= own);
+          const bool ok = jj >= klo && jj < khi && (!p.causal || jj - klo <= qpos);
           const float pr = ok ? __expf(s[r] * p.scale - L) : 0.f;
           const float dpd = !DROP ? dp[r] : (drop_keep(w, f, p.drop_thr) ? dp[r] * p.inv_keep : 0.f);
           s[r] = pr * (dpd - delta);
@@ -579,11 +612,12 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p
   }
   if (own0 < lk) {
     // dK^T[d][key] = Q^T dS, dV^T[d][key] = dO^T P with S[query][key]: a lane owns one key, 16 queries in registers
+    const int qlo = KR[own] & 0xff, qhi = (KR[own] >> 8) & 0xff, kpos = own - (KR[own] >> 16);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       const int i0 = qb * 32;
       if (i0 >= lq) break;
-      if (p.causal && i0 + 31 < own0) continue;      // every query of this block precedes every key of this wavefront
+      if (p.causal && !p.groups && i0 + 31 < own0) continue;   // (one sentence) every query of this block precedes every key of this wavefront
       f32x16 s, dp;
 #pragma unroll
       for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
@@ -603,7 +637,7 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = il + e;
-          const bool ok = i < lq && own < lk && (!p.causal || own <= i);
+          const bool ok = i >= qlo && i < qhi && (!p.causal || kpos <= i - qlo);
           pr[e] = ok ? __expf(s[rg * 4 + e] * p.scale - lv[e]) : 0.f;
           float dpd = dp[rg * 4 + e];
           if (DROP) {
@@ -664,13 +698,16 @@ static AttnP make_params(const AttnArgs& a) {
   p.drop_thr = a.drop_p > 0.f ? drop_threshold(a.drop_p) : 0u;
   p.inv_keep = 1.f / (1.f - a.drop_p);
   p.H = a.H;
+  p.groups = nullptr;
   return p;
 }
 
 void launch_attention_fwd_mfma(hipStream_t s, const AttnArgs& a) {
-  const AttnP p = make_params(a);
-  dim3 grid(a.H * a.B, (a.max_lq + 63) / 64), block(ATT_THREADS);
+  AttnP p = make_params(a);
   const bool drop = p.drop_thr != 0;
+  const bool packed = a.groups != nullptr && a.n_groups > 0 && !drop && a.max_lq <= 64 && a.max_lk <= 64;
+  p.groups = packed ? a.groups : nullptr;
+  dim3 grid(a.H * (packed ? a.n_groups : a.B), (a.max_lq + 63) / 64), block(ATT_THREADS);
   if (a.dt == F16) {
     if (drop) hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t, true>), grid, block, 0, s, p, a.H);
     else hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t, false>), grid, block, 0, s, p, a.H);
@@ -681,11 +718,13 @@ void launch_attention_fwd_mfma(hipStream_t s, const AttnArgs& a) {
 }
 
 void launch_attention_bwd_mfma(hipStream_t s, const AttnArgs& a) {
-  const AttnP p = make_params(a);
+  AttnP p = make_params(a);
   const int nq = (a.max_lq + 63) / 64, nk = (a.max_lk + 63) / 64;
   const bool drop = p.drop_thr != 0;
-  if (nq == 1 && nk == 1) {                              // every sentence fits one chunk: one block per (sentence, head)
-    dim3 grid(1, a.H, a.B), block(ATT_THREADS);
+  if (nq == 1 && nk == 1) {                              // every sentence fits one chunk: one block per (group of sentences, head)
+    const bool packed = a.groups != nullptr && a.n_groups > 0 && !drop;
+    p.groups = packed ? a.groups : nullptr;
+    dim3 grid(1, a.H, packed ? a.n_groups : a.B), block(ATT_THREADS);
     if (a.dt == F16) {
       if (drop) hipLaunchKernelGGL((attn_bwd_single_kernel<half_t, true>), grid, block, 0, s, p);
       else hipLaunchKernelGGL((attn_bwd_single_kernel<half_t, false>), grid, block, 0, s, p);

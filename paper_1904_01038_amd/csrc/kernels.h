@@ -81,6 +81,11 @@ struct AttnArgs {
   // backward regenerate the same bits from the key.
   uint64_t drop_key = 0;
   float drop_p = 0.f;
+  // Optional packing of short sentences (device int32 [n_groups + 1], ascending, groups[0] = 0, groups[n_groups] = B): group g
+  // is the run of consecutive sentences groups[g] .. groups[g+1]-1, whose query rows and whose key rows each number at most
+  // 64.  Used by the one-chunk kernels when every sentence fits 64 rows and the attention weights have no dropout; null: off.
+  const int* groups = nullptr;
+  int n_groups = 0;
 };
 void launch_attention_fwd(hipStream_t s, const AttnArgs& a);
 void launch_attention_bwd(hipStream_t s, const AttnArgs& a);

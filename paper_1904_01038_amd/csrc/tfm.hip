@@ -149,6 +149,7 @@ struct tfm_ctx {
   size_t splitk_bytes;
   int *labels, *uentries, *ibase;                   // device ints (ibase = start of the int block)
   int *seg_tok, *seg_beg, *seg_end, *seg_dst, *mt_tok, *mt_row0, *mt_n;
+  int* grp[3];                                      // sentence groups for the packed attention kernels: encoder self, decoder self, cross
   float* emb_partial;
   size_t int_block_ints;
   Adaptive ad;
@@ -403,7 +404,7 @@ size_t carve(tfm_ctx* c, char* base) {
   const size_t Bc = (size_t)cf.max_sentences + 1;
   const size_t NS = 2 * R + 2 * R / EMB_SEG + 2, NM = 2 * R / EMB_SEG + 2;
   c->emb_partial = (float*)a.take((2 * NM) * d * sizeof(float));
-  c->int_block_ints = 2 * (2 * R + Bc) + R + 2 * R + 4 * NS + 3 * NM + (c->ad.n ? 8 * R : 0);
+  c->int_block_ints = 2 * (2 * R + Bc) + R + 2 * R + 4 * NS + 3 * NM + (c->ad.n ? 8 * R : 0) + 3 * Bc;
   c->ibase = (int*)a.take(c->int_block_ints * 4);
   int* p = c->ibase;
   auto nxt = [&](size_t n) { int* r = base ? p : nullptr; p += n; return r; };
@@ -418,6 +419,7 @@ size_t carve(tfm_ctx* c, char* base) {
     ad.in_idx = nxt(R); ad.in_tok = nxt(R); ad.out_idx = nxt(R); ad.out_lab = nxt(R);
     ad.sg_tok = nxt(R); ad.sg_beg = nxt(R); ad.sg_end = nxt(R); ad.sg_ent = nxt(R);
   }
+  for (int k = 0; k < 3; ++k) c->grp[k] = nxt(Bc);   // (the last 3 * Bc ints of the block)
   return (a.off + 255) & ~(size_t)255;
 }
 
@@ -822,6 +824,7 @@ struct StepCtx {
   std::vector<int> slen, tlen;
   int B, Ts, Tt;
   uint64_t step;
+  int n_grp[3] = {0, 0, 0};                          // groups of this step per attention kind (0: none, one sentence per block)
 };
 
 uint64_t site_key(const StepCtx& s, int stream, int layer, int sub) {
@@ -844,6 +847,8 @@ void attention(const StepCtx& s, bool bwd, const Stream& qs, const Stream& ks, c
   a.total_q = qs.rows; a.total_k = ks.rows; a.causal = causal ? 1 : 0;
   a.d_o = d_o; a.lddo = d; a.dq = dq; a.dk = dk; a.dv = dv; a.lddq = lddq; a.lddk = lddk; a.lddv = lddv;
   a.drop_key = drop_key; a.drop_p = c->cfg.attn_dropout;          // dropout on the attention weights (0: off)
+  const int kind = qs.id == 0 ? 0 : (ks.id == 1 ? 1 : 2);
+  if (s.n_grp[kind] > 0) { a.groups = c->grp[kind]; a.n_groups = s.n_grp[kind]; }
   const double f = attn_flops(lq, lk, d, causal);
   const double bytes = (double)c->esz * d * (bwd ? (4.0 * qs.rows + 4.0 * ks.rows) : (2.0 * qs.rows + 2.0 * ks.rows));
   if (!bwd) run(c, TFM_PROF_ATTENTION, f, bytes, [&] { launch_attention_fwd(c->stream, a); });
@@ -1239,6 +1244,27 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
       if (!pairs.empty()) a_sg_end[nseg - 1] = ad.in_off[k] + (int)pairs.size();
       ad.sg_cnt[k] = nseg - ad.sg_off[k];
     }
+  }
+  // Short sentences share attention blocks: runs of consecutive sentences whose query rows and key rows each fill at most
+  // one 64-row tile (the one-chunk attention kernels take the table; with longer sentences in the batch it is not used).
+  {
+    int* grp = hb + (c->int_block_ints - 3 * Bc);
+    auto build = [&](const int32_t* lq, const int32_t* lk, int maxq, int maxk, int* out) {
+      if (maxq > 64 || maxk > 64) return 0;
+      int n = 0, sq = 0, sk = 0;
+      out[0] = 0;
+      for (int b = 0; b < B; ++b) {
+        if (b > out[n] && (sq + lq[b] > 64 || sk + lk[b] > 64)) { out[++n] = b; sq = sk = 0; }
+        sq += lq[b]; sk += lk[b];
+      }
+      out[++n] = B;
+      return n;
+    };
+    if (has_enc) {
+      s.n_grp[0] = build(src_lens, src_lens, maxs, maxs, grp);
+      s.n_grp[2] = build(tgt_lens, src_lens, maxt, maxs, grp + 2 * Bc);
+    }
+    s.n_grp[1] = build(tgt_lens, tgt_lens, maxt, maxt, grp + Bc);
   }
   HIP_TRY(c, hipMemcpyAsync(c->ibase, hb, c->int_block_ints * 4, hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipEventRecord(c->stage_ev[slot], c->stream));
@@ -1714,13 +1740,14 @@ int tfm_op_wgrad_grouped(int32_t dtype, int32_t n, const int32_t* dims, const vo
 int tfm_op_attention_fwd(int32_t dtype, const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v, int32_t ldv,
                          void* o, int32_t ldo, float* lse, const int32_t* q_off, const int32_t* k_off, int32_t B, int32_t H,
                          int32_t dh, int32_t max_lq, int32_t max_lk, int32_t total_q, int32_t causal, uint64_t drop_key, float drop_p,
-                         void* stream) {
+                         const int32_t* groups, int32_t n_groups, void* stream) {
   if (dtype < 0 || dtype > 2 || !q || !k || !v || !o || !lse || !q_off || !k_off || B < 1 || H < 1 || dh < 1 || dh > 128) return TFM_EINVAL;
   if (max_lq < 1 || max_lk < 1 || max_lq > 4096 || max_lk > 4096 || !(drop_p >= 0.f && drop_p < 1.f)) return TFM_EINVAL;
+  if (n_groups < 0 || n_groups > B || (groups == nullptr) != (n_groups == 0)) return TFM_EINVAL;
   AttnArgs a{};
   a.dt = dtype; a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.o = o; a.ldo = ldo; a.lse = lse;
   a.q_off = q_off; a.k_off = k_off; a.B = B; a.H = H; a.dh = dh; a.max_lq = max_lq; a.max_lk = max_lk; a.total_q = total_q;
-  a.causal = causal; a.drop_key = drop_key; a.drop_p = drop_p;
+  a.causal = causal; a.drop_key = drop_key; a.drop_p = drop_p; a.groups = groups; a.n_groups = n_groups;
   launch_attention_fwd((hipStream_t)stream, a);
   return op_done();
 }
@@ -1729,15 +1756,17 @@ int tfm_op_attention_bwd(int32_t dtype, const void* q, int32_t ldq, const void* 
                          const void* o, int32_t ldo, const void* d_o, int32_t lddo, const float* lse, void* dq, int32_t lddq,
                          void* dk, int32_t lddk, void* dv, int32_t lddv, const int32_t* q_off, const int32_t* k_off, int32_t B,
                          int32_t H, int32_t dh, int32_t max_lq, int32_t max_lk, int32_t total_q, int32_t total_k, int32_t causal,
-                         uint64_t drop_key, float drop_p, void* stream) {
+                         uint64_t drop_key, float drop_p, const int32_t* groups, int32_t n_groups, void* stream) {
   if (dtype < 0 || dtype > 2 || !q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !q_off || !k_off) return TFM_EINVAL;
   if (B < 1 || H < 1 || dh < 1 || dh > 128 || max_lq < 1 || max_lk < 1 || max_lq > 4096 || max_lk > 4096) return TFM_EINVAL;
   if (!(drop_p >= 0.f && drop_p < 1.f)) return TFM_EINVAL;
+  if (n_groups < 0 || n_groups > B || (groups == nullptr) != (n_groups == 0)) return TFM_EINVAL;
   AttnArgs a{};
   a.dt = dtype; a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldk = ldk; a.ldv = ldv; a.o = const_cast<void*>(o); a.ldo = ldo;
   a.lse = const_cast<float*>(lse); a.q_off = q_off; a.k_off = k_off; a.B = B; a.H = H; a.dh = dh; a.max_lq = max_lq;
   a.max_lk = max_lk; a.total_q = total_q; a.total_k = total_k; a.causal = causal; a.d_o = d_o; a.lddo = lddo; a.dq = dq;
   a.dk = dk; a.dv = dv; a.lddq = lddq; a.lddk = lddk; a.lddv = lddv; a.drop_key = drop_key; a.drop_p = drop_p;
+  a.groups = groups; a.n_groups = n_groups;
   launch_attention_bwd((hipStream_t)stream, a);
   return op_done();
 }

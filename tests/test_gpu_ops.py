@@ -233,21 +233,41 @@ ATTN_CASES = [  # (query lengths, key lengths or None for self-attention, causal
     ([10, 60, 64], [70, 128, 1], False),
     ([70, 128, 3], [10, 64, 64], False),
     ([128, 127, 66, 2], None, True),
+    # many short sentences (several per 64-row tile when a group table is passed)
+    ([10, 12, 11, 30, 2, 1, 64, 5, 5, 5, 5, 40, 20, 3, 1, 1, 62], None, True),
+    ([10, 12, 11, 30, 2, 1, 64, 5, 5, 5, 5, 40, 20, 3, 1, 1, 62], None, False),
+    ([10, 12, 3, 30, 20, 7, 9, 9, 33], [12, 9, 40, 1, 33, 16, 8, 8, 31], False),
 ]
 
 
+def sentence_groups(lq, lk):
+    """Runs of consecutive sentences whose query rows and key rows each number at most 64 (greedy, as the library's ingest)."""
+    out, sq, sk = [0], 0, 0
+    for b in range(len(lq)):
+        if b > out[-1] and (sq + lq[b] > 64 or sk + lk[b] > 64):
+            out.append(b)
+            sq = sk = 0
+        sq, sk = sq + lq[b], sk + lk[b]
+    out.append(len(lq))
+    return out
+
+
+@pytest.mark.parametrize("packed", [False, True])
 @pytest.mark.parametrize("p_drop", [0.0, 0.25])
 @pytest.mark.parametrize("prec,dh", [("fp32", 16), ("fp32", 64), ("fp16", 64), ("bf16", 64), ("fp16", 32)])
 @pytest.mark.parametrize("case", ATTN_CASES)
-def test_attention_forward_backward(prec, dh, case, p_drop):
+def test_attention_forward_backward(prec, dh, case, p_drop, packed):
     """p_drop > 0: dropout on the attention weights; both sides derive the keep bits from the same key, query row, head and
-    key index, each with its own implementation of the generator."""
+    key index, each with its own implementation of the generator.  packed: the call also gets a table of sentence groups
+    (several short sentences per 64-row tile); the results must not depend on it."""
     import torch
     import paper_1904_01038_amd as T
     from oracle.transformer import attention_fwd, attention_bwd, attention_keep, dropout_key, site_id
     lq, lk, causal = case
     dkey = int(dropout_key(17, 4, site_id(1, 2, 3)))
     lk = lq if lk is None else lk
+    if packed and (max(lq) > 64 or max(lk) > 64 or dh != 64 or prec == "fp32"):
+        pytest.skip("the group table only matters to the one-chunk matrix-core kernels")
     H = 3
     d = H * dh
     dt = _dtypes()[prec]
@@ -262,9 +282,10 @@ def test_attention_forward_backward(prec, dh, case, p_drop):
     k_off = torch.tensor(np.concatenate([[0], np.cumsum(lk)]), dtype=torch.int32).cuda()
     o = torch.zeros(Tq, d, dtype=dt, device="cuda")
     lse = torch.zeros(H, Tq, dtype=torch.float32, device="cuda")
-    T.ops.attention_fwd(q, k, v, o, lse, q_off, k_off, H, dh, max(lq), max(lk), causal, dkey, p_drop)
+    groups = torch.tensor(sentence_groups(lq, lk), dtype=torch.int32).cuda() if packed else None
+    T.ops.attention_fwd(q, k, v, o, lse, q_off, k_off, H, dh, max(lq), max(lk), causal, dkey, p_drop, groups)
     dq, dk, dv = (torch.zeros_like(x) for x in (q, k, v))
-    T.ops.attention_bwd(q, k, v, o, do, lse, dq, dk, dv, q_off, k_off, H, dh, max(lq), max(lk), Tk, causal, dkey, p_drop)
+    T.ops.attention_bwd(q, k, v, o, do, lse, dq, dk, dv, q_off, k_off, H, dh, max(lq), max(lk), Tk, causal, dkey, p_drop, groups)
     qd, kd, vd, dod = (x.double().cpu().numpy() for x in (q, k, v, do))
     # With dropout the kept weights, and with them the outputs and their rounding, grow by 1 / (1 - p_drop); and where a
     # sentence has a single key, dS = P (dP - dO.O) vanishes only in exact arithmetic: the backward pass forms dO.O from the
