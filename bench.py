@@ -294,7 +294,11 @@ def main():
     del ctx
     torch.cuda.empty_cache()
     if prec != T.FP32:
+        l2_cu, l2_all = T.ops.probe_fetch(64 << 10)
+        fab_cu, fab_all = T.ops.probe_fetch(512 << 10)
         roofline["measured_ceilings"] = {"mfma_only_loop_tflops": T.ops.probe_mfma(prec), "copy_kernel_gbs": T.ops.probe_copy(1 << 30),
+                                         "operand_fetch_gbs_per_cu": {"from_l2": l2_cu, "through_fabric": fab_cu},
+                                         "operand_fetch_gbs_total": {"from_l2": l2_all, "through_fabric": fab_all},
                                          "published": {"mfma_tflops": MFMA_PEAK_TFLOPS, "hbm_gbs": HBM_PEAK_GBS}}
 
     out = {"metric": "target tokens/sec per training step on 1 MI355X", "value": tokens / dt, "unit": "tokens/s",

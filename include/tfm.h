@@ -178,6 +178,12 @@ int tfm_profile_read(tfm_ctx* ctx, tfm_prof_entry out[TFM_PROF_CLASSES], int32_t
  * bytes written) per second.  Both block until the measurement is done. */
 int tfm_probe_mfma(int32_t dtype, void* scratch, size_t scratch_bytes, double* tflops, void* stream);
 int tfm_probe_copy(void* dst, const void* src, size_t bytes, double* gbs, void* stream);
+/* tfm_probe_fetch: the rate at which compute units pull data in: one 16-wavefront block per compute unit re-reads its own
+ * region of region_bytes (a multiple of 16 KiB) with 16-byte loads.  64 KiB regions stay in the XCDs' L2 caches (the GEMMs'
+ * operand-tile path when panels are shared inside an XCD); 512 KiB regions (128 MiB in all) are served by the memory side
+ * through the fabric (the path of every panel's first touch in an XCD).  buf: device memory (contents irrelevant, read only
+ * except for 16 KiB at its end), at least compute units x region_bytes + 16 KiB, else TFM_ENOMEM.  Blocks until done. */
+int tfm_probe_fetch(const void* buf, size_t bytes, size_t region_bytes, double* gbs_per_cu, double* gbs_total, void* stream);
 
 /* ---- single operations on caller-owned device buffers (used by the kernel-level parity tests) ---------------
  * dtype: TFM_FP32 / TFM_FP16 / TFM_BF16 for every tensor argument unless stated.  stream: hipStream_t or NULL.  */

@@ -102,6 +102,7 @@ def lib():
                                      f32, vp]
         L.tfm_probe_mfma.argtypes = [i32, vp, C.c_size_t, C.POINTER(C.c_double), vp]
         L.tfm_probe_copy.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_double), vp]
+        L.tfm_probe_fetch.argtypes = [vp, C.c_size_t, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
         L.tfm_op_wgrad_grouped.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp]
         L.tfm_op_attention_fwd.argtypes = [i32, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, i32, i32, i32,
                                            i32, i32, u64, f32, vp, i32, vp]

@@ -51,6 +51,24 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(uint4* __restrict__ dst
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
+// Re-reads a private region per block with 16-byte loads, 8 in flight per lane: the rate at which a compute unit can pull
+// operand tiles in.  Regions of 64 KiB per block stay in the L2 of the block's XCD (16 MiB in all), regions of 512 KiB
+// (128 MiB in all) exceed the L2s and are served by the memory side (infinity cache / HBM) through the fabric.
+typedef unsigned int fetch_vec __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(1024) void fetch_probe_kernel(const fetch_vec* __restrict__ buf, unsigned region_vecs, int iters, fetch_vec* out) {
+  const fetch_vec* base = buf + (size_t)blockIdx.x * region_vecs;
+  fetch_vec acc = {0u, 0u, 0u, 0u};
+  unsigned idx = threadIdx.x;                              // < 1024 <= region_vecs
+  for (int it = 0; it < iters; ++it) {
+    fetch_vec v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { v[u] = base[idx]; idx += 1024; if (idx >= region_vecs) idx -= region_vecs; }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  if (acc[0] == 0x12345678u && acc[1] == 0x9abcdef0u) out[threadIdx.x] = acc;   // (keeps the loads; practically never taken)
+}
+
 }  // namespace tfm
 
 using namespace tfm;
@@ -100,6 +118,32 @@ int tfm_probe_copy(void* dst, const void* src, size_t bytes, double* gbs, void* 
   hipEventDestroy(e0); hipEventDestroy(e1);
   if (!ok || hipGetLastError() != hipSuccess) return TFM_EHIP;
   *gbs = 2.0 * (double)bytes * reps / (ms * 1e-3) / 1e9;   // bytes read plus bytes written
+  return TFM_OK;
+}
+
+int tfm_probe_fetch(const void* buf, size_t bytes, size_t region_bytes, double* gbs_per_cu, double* gbs_total, void* stream) {
+  if (!buf || !gbs_per_cu || !gbs_total || ((uintptr_t)buf & 15)) return TFM_EINVAL;
+  if (region_bytes < 16384 || region_bytes % 16384 || region_bytes > ((size_t)1 << 30)) return TFM_EINVAL;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return TFM_EHIP;
+  if (bytes < (size_t)cus * region_bytes + 16384) return TFM_ENOMEM;        // every block's region, plus the result slot
+  hipStream_t s = (hipStream_t)stream;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return TFM_EHIP;
+  const fetch_vec* b = (const fetch_vec*)buf;
+  fetch_vec* out = (fetch_vec*)((char*)buf + (size_t)cus * region_bytes);
+  const unsigned vecs = (unsigned)(region_bytes / 16);
+  const int iters = 400;
+  hipLaunchKernelGGL(fetch_probe_kernel, dim3(cus), dim3(1024), 0, s, b, vecs, iters, out);
+  hipEventRecord(e0, s);
+  hipLaunchKernelGGL(fetch_probe_kernel, dim3(cus), dim3(1024), 0, s, b, vecs, iters, out);
+  hipEventRecord(e1, s);
+  float ms = 0.f;
+  const bool ok = hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms > 0.f;
+  hipEventDestroy(e0); hipEventDestroy(e1);
+  if (!ok || hipGetLastError() != hipSuccess) return TFM_EHIP;
+  *gbs_total = (double)cus * 1024.0 * 16.0 * 8.0 * iters / (ms * 1e-3) / 1e9;
+  *gbs_per_cu = *gbs_total / cus;
   return TFM_OK;
 }
 

@@ -139,3 +139,14 @@ def probe_copy(nbytes=1 << 30):
     out = C.c_double()
     _check(lib().tfm_probe_copy(_p(a), _p(b), nbytes, C.byref(out), _stream()), "tfm_probe_copy")
     return out.value
+
+
+def probe_fetch(region_bytes=64 << 10):
+    """(GB/s per compute unit, GB/s in total) at which one block per compute unit re-reads a private region of region_bytes:
+    64 KiB regions stay in the L2 caches, 512 KiB regions are served through the fabric by the memory side."""
+    import torch
+    n = 256 * region_bytes + (1 << 20)
+    buf = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    per_cu, total = C.c_double(), C.c_double()
+    _check(lib().tfm_probe_fetch(_p(buf), n, region_bytes, C.byref(per_cu), C.byref(total), _stream()), "tfm_probe_fetch")
+    return per_cu.value, total.value

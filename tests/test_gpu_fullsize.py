@@ -72,6 +72,40 @@ def test_lm24_real_width_two_blocks_fp16():
     check(*run_workload("lm24", "fp16", shape=shape))
 
 
+def test_big_fp16_two_accumulated_subbatches_full_size_values():
+    """The delayed-update workload's values at full size: two sub-batches of sentences of 10-120 tokens (the attention
+    kernels for more than one 64-row chunk, the fp32 window accumulator) accumulated without an update in between, losses
+    and every accumulated gradient tensor against the float64 oracle."""
+    import paper_1904_01038_amd as T
+    from oracle.transformer import OracleTransformer, TrainConfig
+    import torch
+    shape = PRESETS["big"]
+    batches = make_batches("big_accum", 32)
+    # one batch of long sentences and one of short ones, so that both attention paths contribute to the same window
+    by_len = sorted(batches, key=lambda b: b.tgt.shape[1])
+    pick = [by_len[-1], by_len[0]]
+    assert pick[0].tgt.shape[1] > 64 and pick[1].tgt.shape[1] <= 32
+    params = init_params(shape, 0)
+    params = {k: torch.tensor(v, dtype=torch.float32).to(torch.float16).to(torch.float64).numpy() for k, v in params.items()}
+    max_tok = max(max(b.ntokens, int(b.src_lens.sum())) for b in pick)
+    cfg = T.make_config(shape, precision=T.FP16, max_sentences=max(len(b.tgt_lens) for b in pick),
+                        max_tokens=(max_tok + 63) // 64 * 64, max_len=max(max(b.tgt.shape[1], b.src.shape[1]) for b in pick),
+                        dropout=0.0, init_loss_scale=8.0, label_smoothing=0.1)
+    gpu = T.Tfm(cfg)
+    gpu.set_params(params)
+    oracle = OracleTransformer(shape, params, TrainConfig(init_loss_scale=8.0, fp16_overflow=False, label_smoothing=0.1))
+    del params
+    for b in pick:
+        rg = gpu.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens)
+        ro = oracle.train_step(b.src, b.tgt, b.src_lens, b.tgt_lens)
+        assert rg["overflow"] == 0 and rg["ntokens"] == ro["ntokens"]
+        assert abs(rg["loss_sum"] - ro["loss_sum"]) <= 1e-2 * abs(ro["loss_sum"])
+    gg = gpu.get_grads()
+    gpu.close()
+    worst = min((cosine(gg[k], v), k) for k, v in oracle.G.items())
+    assert worst[0] >= 0.999, worst
+
+
 def test_big_fp16_delayed_updates_with_injected_overflows_full_size():
     """The delayed-update workload at full size (big model, 16 sub-batches of sentences of 10-120 tokens per update, two
     windows): sub-batches 5 and 11 of the first window run with the loss multiplied by 1e6, which must flag exactly those

@@ -129,3 +129,8 @@ def test_measured_ceilings_are_plausible():
         assert 1000.0 < tf <= 2500.0 * 1.02, tf
     gbs = T.ops.probe_copy(1 << 28)
     assert 2000.0 < gbs <= 8000.0 * 1.02, gbs
+    # operand fetch: an L2-resident region comes in faster than one served through the fabric, and no faster than 64 bytes
+    # per clock and compute unit (2.4 GHz)
+    l2_cu, l2_all = T.ops.probe_fetch(64 << 10)
+    fab_cu, fab_all = T.ops.probe_fetch(512 << 10)
+    assert 40.0 < l2_cu <= 64 * 2.4 * 1.02 and fab_cu < l2_cu and fab_all > 2000.0, (l2_cu, fab_cu, fab_all)
