@@ -10,6 +10,10 @@ path; the parameters and sub-layers are those of oracle/transformer.py.
   DecodingOracle.encode(src)                    encoder output for one source sentence (None for a decoder-only model)
   DecodingOracle.logprobs(mem, dec_in)          log-softmax over the vocabulary at every position of dec_in
   DecodingOracle.next_logprobs(mem, history)    the last row of the above: the step's prediction
+  DecodingOracle.vocabulary_logprobs(y)         final states -> log-probabilities of every token; for a model with an
+                                                adaptive softmax (Applications, language modeling) a head token has
+                                                log p_head(w), a token of tail cluster c has log p_head(entry of c) +
+                                                log p_c(w), the definition the training criterion uses per target
   top_k(logp, k)                                the k best (log-probability, id) pairs, best first; equal values in
                                                 ascending id order (the rule the library documents)
 """
@@ -51,13 +55,31 @@ class DecodingOracle:
             y, _ = m._block_fwd(pre + ".ln_ffn", y, lambda u, pre=pre: m._ffn_fwd(pre + ".ffn", u), (1, i, 2, 0))
         if sh.pre_norm:
             y, _ = layer_norm_fwd(y, P["dec.ln_final.g"], P["dec.ln_final.b"])
-        z = y @ P["embed"].T
-        z = z - z.max(axis=1, keepdims=True)
-        return z - np.log(np.exp(z).sum(axis=1, keepdims=True))
+        return self.vocabulary_logprobs(y)
+
+    def vocabulary_logprobs(self, y):
+        sh, P = self.shape, self.model.p
+        head = _log_softmax(y @ P["embed"].T)
+        if not sh.cutoffs:
+            return head
+        bounds = sh.cluster_bounds()
+        c0 = bounds[0][1]
+        out = np.empty((y.shape[0], sh.vocab))
+        out[:, :c0] = head[:, :c0]                                # the head's own tokens
+        for c in range(1, len(bounds)):
+            lo, hi = bounds[c]
+            u = y @ P[f"embed.{c}.proj"]                          # state projected down to the cluster's width
+            out[:, lo:hi] = head[:, c0 + c - 1:c0 + c] + _log_softmax(u @ P[f"embed.{c}"].T)
+        return out
 
     def next_logprobs(self, mem, history):
         """history: the tokens fed to the decoder so far (the first one is eos)."""
         return self.logprobs(mem, history)[-1]
+
+
+def _log_softmax(z):
+    z = z - z.max(axis=1, keepdims=True)
+    return z - np.log(np.exp(z).sum(axis=1, keepdims=True))
 
 
 def top_k(logp, k):

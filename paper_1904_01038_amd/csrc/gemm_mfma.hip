@@ -572,8 +572,9 @@ void launch_wgrad_grouped(hipStream_t s, int dt, const WgradJob* jobs, int n) {
 // Configuration choice, from measurements on the projection shapes of the big and base Transformers (M ~ 3000-3700 tokens):
 //   id  tile     wavefronts  K-step  ring   resident blocks per CU
 //    1  128x128      4         32     3      3      more than 256 tiles and K < 3072: several blocks per CU keep it fed
-//   12  128x128     16         64     3      1      K >= 3072, or at most 256 tiles (one block per CU anyway): 16 wavefronts
-//                                                   of 32x32 hide the fetch latency that 4 of 64x64 exposed (10-15 % faster)
+//   12  128x128     16         64     4      1      K >= 3072, or at most 256 tiles (one block per CU anyway): 16 wavefronts
+//                                                   of 32x32 hide the fetch latency that 4 of 64x64 exposed (10-15 % faster);
+//                                                   a 4-slot ring is 2-4 % faster than 3 slots, 5 slots are slower again
 //   13  256x256      8         64     2      1      half the bytes fetched per flop (16 wavefronts are slower here: more LDS
 //                                                   traffic per flop)
 //   14  192x256      8         64     2      1      X W^T and dY W only: where 256x256 leaves compute units idle (a 3072-wide
@@ -602,7 +603,7 @@ template <typename T>
 static void gemm_mfma_dispatch(hipStream_t s, const GemmArgs& a) {
   switch (choose_tile(a)) {
     case 13: gemm_mfma_launch<T, 256, 256, 2, 4, 64, 2>(s, a); break;
-    case 12: gemm_mfma_launch<T, 128, 128, 4, 4, 64, 3>(s, a); break;
+    case 12: gemm_mfma_launch<T, 128, 128, 4, 4, 64, 4>(s, a); break;
     case 14: gemm_mfma_launch<T, 192, 256, 2, 4, 64, 2>(s, a); break;   // (never chosen for A^T B: its A tile would be [k][192])
     case 20:                                            // (the [k][row] swizzle spans 16 vectors: NT form only)
       if (a.form == 0) gemm_mfma_launch<T, 64, 64, 2, 2, 64, 4>(s, a);
