@@ -296,7 +296,9 @@ uint64_t tfm_dropout_key(uint64_t seed, uint64_t step, int32_t stream, int32_t l
  * stays valid only while the context's parameters do: after any tfm_train_step, tfm_apply_update or tfm_set_param on
  * the context, tfm_decoder_step returns TFM_ESTATE until tfm_decoder_begin starts a batch again.  Dropout is off.
  * The search itself (which beams continue, length penalty, stopping) is the caller's: it passes, per row, the token to
- * feed and the row whose history this row continues. */
+ * feed and the row whose history this row continues.  Models with adaptive inputs / an adaptive softmax (n_cutoffs > 0) are
+ * decoded the same way: the returned log-probabilities are log p_head(token) for a head token and log p_head(cluster entry) +
+ * log p_cluster(token) for a token of a tail cluster (Applications, language modeling). */
 typedef struct tfm_decoder tfm_decoder;
 
 /* max_rows: sentences x beam; max_steps <= config.max_len: positions a hypothesis may reach; max_src_tokens: source

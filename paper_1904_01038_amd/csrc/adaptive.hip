@@ -63,6 +63,19 @@ __global__ __launch_bounds__(256) void segsum_add_rows_kernel(T* __restrict__ ds
   }
 }
 
+// Decoding with an adaptive softmax: the scores of one cluster's tokens join the row of "virtual logits" over the whole
+// vocabulary, virt[r][col0 + j] = z[r][j] + offset[r]; for a tail cluster offset = (head score of the cluster's entry) - (the
+// cluster's own log-sum-exp), for the head's tokens 0.  The log-sum-exp of a finished row is then the head's, and a row's
+// log-softmax gives log p_head(cluster) + log p_cluster(token) for every tail token.
+template <typename T>
+__global__ __launch_bounds__(256) void adaptive_virtual_kernel(const T* __restrict__ z, int ldz, int width, T* __restrict__ virt, int ldv, int col0,
+                                                               const T* __restrict__ head, int ldh, int entry, const float* __restrict__ lse) {
+  const int r = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= width) return;
+  const float off = entry >= 0 ? to_f<T>(head[(size_t)r * ldh + entry]) - lse[r] : 0.f;
+  virt[(size_t)r * ldv + col0 + j] = from_f<T>(to_f<T>(z[(size_t)r * ldz + j]) + off);
+}
+
 #define BY_DTYPE(CALL)                                  \
   do {                                                  \
     if (dt == F32) { typedef float T; CALL; }           \
@@ -92,6 +105,12 @@ void launch_scatter_add_rows(hipStream_t s, int dt, void* dst, int ld_dst, const
 void launch_scatter_add_f32(hipStream_t s, float* a, float* b, const int* idx, const float* sa, const float* sb, int n) {
   if (n <= 0) return;
   hipLaunchKernelGGL(scatter_add_f32_kernel, dim3(blocks_for(n)), dim3(256), 0, s, a, b, idx, sa, sb, n);
+}
+void launch_adaptive_virtual(hipStream_t s, int dt, const void* z, int ldz, int width, void* virt, int ldv, int col0, const void* head, int ldh,
+                             int entry, const float* lse, int rows) {
+  if (rows <= 0 || width <= 0) return;
+  BY_DTYPE(hipLaunchKernelGGL((adaptive_virtual_kernel<T>), dim3(blocks_for(width), rows), dim3(256), 0, s, (const T*)z, ldz, width, (T*)virt, ldv,
+                              col0, (const T*)head, ldh, entry, lse));
 }
 void launch_segsum_add_rows(hipStream_t s, int dt, void* dst, const void* src, int width, const int* tok, const int* beg, const int* end,
                             const int* entries, int n_seg) {

@@ -127,6 +127,9 @@ void launch_gather_rows(hipStream_t s, int dt, const void* src, int ld_src, cons
 void launch_gather_dx(hipStream_t s, int dt, const void* dx, const int* idx, void* dst, int d, int n, float scale, uint64_t key, float p);
 void launch_scatter_add_rows(hipStream_t s, int dt, void* dst, int ld_dst, const int* idx, const void* src, int width, int n);
 void launch_scatter_add_f32(hipStream_t s, float* a, float* b, const int* idx, const float* sa, const float* sb, int n);
+// virt[r][col0 + j] = z[r][j] + (entry >= 0 ? head[r][entry] - lse[r] : 0), j < width, r < rows (decoding with an adaptive softmax)
+void launch_adaptive_virtual(hipStream_t s, int dt, const void* z, int ldz, int width, void* virt, int ldv, int col0, const void* head, int ldh,
+                             int entry, const float* lse, int rows);
 void launch_segsum_add_rows(hipStream_t s, int dt, void* dst, const void* src, int width, const int* tok, const int* beg, const int* end,
                             const int* entries, int n_seg);
 // Adds sqrt(d) * dropout-backward(dx) of every occurrence of a token to its row of the embedding gradient.

@@ -1424,6 +1424,11 @@ struct tfm_decoder {
   float *mean, *rstd, *lse, *top_logp, *lp_stage;
   int *top_id, *anc[2], *ibuf;
   int* src_off;                                    // [max_sentences + 1]: this batch's source offsets (the context's are re-used by training)
+  // adaptive inputs / adaptive softmax (null without clusters)
+  void *a_head, *a_tail, *a_u, *a_xc, *a_y;        // head scores [R, v0]; one tail cluster's scores [R, vmax]; projected state [R, wmax];
+                                                   // gathered narrow input rows [R, wmax]; projected input vectors [R, d]
+  float *a_lse, *a_lp1;                            // [R]: a cluster's log-sum-exp; throw-away best value of that pass
+  int* a_id1;                                      // [R]: throw-away best id
   std::vector<void*> Kc, Vc, xkv;                  // per decoder layer
   // pinned host staging
   int* h_in;                                       // prev, parent, pos [3 * max_rows]; also source ids / pos / offsets
@@ -1457,8 +1462,21 @@ size_t decoder_carve(tfm_decoder* D, char* base) {
   D->lp_stage = (float*)a.take((size_t)16 * cf.vocab * 4);
   D->anc[0] = (int*)a.take(R * D->max_steps * 4);
   D->anc[1] = (int*)a.take(R * D->max_steps * 4);
-  D->ibuf = (int*)a.take(3 * R * 4);
+  D->ibuf = (int*)a.take(4 * R * 4);              // token, parent, position, index into a tail cluster's table
   D->src_off = (int*)a.take(((size_t)cf.max_sentences + 1) * 4);
+  if (c->ad.n) {
+    const Adaptive& ad = c->ad;
+    size_t wmax = 0;
+    for (int k = 1; k <= ad.n; ++k) wmax = std::max(wmax, (size_t)ad.width[k]);
+    D->a_head = a.take(R * (size_t)ad.v0 * esz);
+    D->a_tail = a.take(R * (size_t)ad.vmax * esz);
+    D->a_u = a.take(R * wmax * esz);
+    D->a_xc = a.take(R * wmax * esz);
+    D->a_y = a.take(R * d * esz);
+    D->a_lse = (float*)a.take(R * 4);
+    D->a_lp1 = (float*)a.take(R * 4);
+    D->a_id1 = (int*)a.take(R * 4);
+  }
   D->Kc.assign(cf.dec_layers, nullptr); D->Vc.assign(cf.dec_layers, nullptr); D->xkv.assign(cf.dec_layers, nullptr);
   for (int l = 0; l < cf.dec_layers; ++l) {
     D->Kc[l] = a.take(R * D->max_steps * d * esz);
@@ -1471,7 +1489,6 @@ size_t decoder_carve(tfm_decoder* D, char* base) {
 int decoder_check(const tfm_ctx* c, int max_rows, int max_steps, int max_src, int topk) {
   if (!c) return TFM_EINVAL;
   const tfm_config& cf = c->cfg;
-  if (cf.n_cutoffs) return TFM_EINVAL;             // decoding with an adaptive softmax is not built
   if (max_rows < 1 || max_steps < 1 || max_steps > cf.max_len || topk < 1 || topk > 16 || topk > cf.vocab) return TFM_EINVAL;
   if (cf.enc_layers && (max_src < 1 || max_src > cf.max_tokens)) return TFM_EINVAL;
   // the attention kernel keeps element offsets into one cache in 32 bits
@@ -1541,7 +1558,7 @@ int tfm_decoder_create(tfm_ctx* c, void* ws, size_t bytes, int32_t max_rows, int
   const size_t need = decoder_carve(D, nullptr);
   if (bytes < need) { delete D; return fail(c, TFM_ENOMEM, "decoder workspace has %zu bytes, %zu needed", bytes, need); }
   decoder_carve(D, (char*)ws);
-  D->h_in_ints = std::max<size_t>(3 * (size_t)max_rows, 2 * (size_t)c->cfg.max_tokens + c->cfg.max_sentences + 1);
+  D->h_in_ints = std::max<size_t>(4 * (size_t)max_rows, 2 * (size_t)c->cfg.max_tokens + c->cfg.max_sentences + 1);
   hipError_t e = hipHostMalloc((void**)&D->h_in, D->h_in_ints * 4, hipHostMallocDefault);
   if (e == hipSuccess) e = hipHostMalloc((void**)&D->h_out, (size_t)max_rows * topk * 8, hipHostMallocDefault);
   if (e != hipSuccess) {
@@ -1640,8 +1657,24 @@ int tfm_decoder_step(tfm_decoder* D, const int32_t* prev, const int32_t* parent,
   }
   // the previous step's call synchronised, so the staging buffer is free
   for (int r = 0; r < R; ++r) { D->h_in[r] = prev[r]; D->h_in[R + r] = parent ? parent[r] : r; D->h_in[2 * R + r] = D->t; }
-  HIP_TRY(c, hipMemcpyAsync(D->ibuf, D->h_in, (size_t)3 * R * 4, hipMemcpyHostToDevice, c->stream));
-  const int* d_prev = D->ibuf; const int* d_parent = D->ibuf + R; const int* d_pos = D->ibuf + 2 * R;
+  // Adaptive inputs: a row fed with a token of tail cluster k gets the id -1 - (its row in the compact list of projected vectors);
+  // the lists are ordered by cluster, rows ascending
+  const Adaptive& ad = c->ad;
+  int in_cnt[4] = {0, 0, 0, 0}, in_off[4] = {0, 0, 0, 0};
+  if (ad.n) {
+    for (int r = 0; r < R; ++r) in_cnt[ad.cluster_of(prev[r])]++;
+    for (int k = 2; k <= ad.n; ++k) in_off[k] = in_off[k - 1] + in_cnt[k - 1];
+    int fill[4] = {0, 0, 0, 0};
+    for (int r = 0; r < R; ++r) {
+      const int k = ad.cluster_of(prev[r]);
+      if (!k) continue;
+      const int row = in_off[k] + fill[k]++;
+      D->h_in[3 * R + row] = prev[r] - ad.lo[k];
+      D->h_in[r] = -1 - row;
+    }
+  }
+  HIP_TRY(c, hipMemcpyAsync(D->ibuf, D->h_in, (size_t)4 * R * 4, hipMemcpyHostToDevice, c->stream));
+  const int* d_prev = D->ibuf; const int* d_parent = D->ibuf + R; const int* d_pos = D->ibuf + 2 * R; const int* d_in_tok = D->ibuf + 3 * R;
   run(c, TFM_PROF_EMBED, 0.0, 4.0 * R * (D->t + 1) * 2.0,
       [&] { launch_ancestry(c->stream, D->anc[D->cur], D->anc[D->cur ^ 1], d_parent, R, D->max_steps, D->t); });
   D->cur ^= 1;
@@ -1649,8 +1682,15 @@ int tfm_decoder_step(tfm_decoder* D, const int32_t* prev, const int32_t* parent,
   const std::vector<Block>& blocks = c->dec.blocks;
   const int K = (int)blocks.size();
   void* emb = pre ? D->resid[0] : D->norm[0];
+  for (int k = 1; k <= ad.n; ++k) {                  // tail tokens: narrow table rows, projected up to the model width
+    const int n = in_cnt[k], w = ad.width[k];
+    if (n == 0) continue;
+    run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * n * w * 2.0,
+        [&] { launch_gather_rows(c->stream, c->dt, wh(c, ad.E[k]), w, d_in_tok + in_off[k], D->a_xc, w, n); });
+    gemm(c, 0, n, d, w, D->a_xc, w, wh(c, ad.P[k]), w, (char*)D->a_y + (size_t)in_off[k] * d * c->esz, d);
+  }
   run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * R * d * 2.0,
-      [&] { launch_embed_fwd(c->stream, c->dt, c->Wh, d_prev, d_pos, c->pe, emb, R, d, 0, 0.f); });
+      [&] { launch_embed_fwd(c->stream, c->dt, c->Wh, d_prev, d_pos, c->pe, emb, R, d, 0, 0.f, ad.n ? D->a_y : nullptr); });
   if (pre) decode_ln(D, D->resid[0], nullptr, blocks[0].ln_g, blocks[0].ln_b, nullptr, D->norm[0]);
   double src_positions = 0;
   if (cf.enc_layers) src_positions = (double)D->src_rows * D->beam;
@@ -1665,7 +1705,26 @@ int tfm_decoder_step(tfm_decoder* D, const int32_t* prev, const int32_t* parent,
     }
   }
   const void* top = D->norm[K & 1];
-  gemm(c, 0, R, V, d, top, d, c->Wh, d, D->logits, V);
+  if (!ad.n) {
+    gemm(c, 0, R, V, d, top, d, c->Wh, d, D->logits, V);
+  } else {
+    // Adaptive softmax: the head scores its tokens and one entry per tail cluster; a tail cluster projects the state down
+    // and scores its own tokens.  All scores are assembled into one row of virtual logits over the vocabulary (see
+    // launch_adaptive_virtual), which the ordinary top-k / log-softmax pass then reads.
+    const int v0 = ad.v0, c0 = ad.hi[0];
+    gemm(c, 0, R, v0, d, top, d, c->Wh, d, D->a_head, v0);
+    run(c, TFM_PROF_LOSS, 0.0, (double)c->esz * R * c0 * 2.0,
+        [&] { launch_adaptive_virtual(c->stream, c->dt, D->a_head, v0, c0, D->logits, V, 0, nullptr, 0, -1, nullptr, R); });
+    for (int k = 1; k <= ad.n; ++k) {
+      const int w = ad.width[k], Vk = ad.hi[k] - ad.lo[k];
+      gemm(c, 1, R, w, d, top, d, wh(c, ad.P[k]), w, D->a_u, w);                      // u = P^T h
+      gemm(c, 0, R, Vk, w, D->a_u, w, wh(c, ad.E[k]), w, D->a_tail, Vk);              // z = E u
+      run(c, TFM_PROF_LOSS, 0.0, (double)c->esz * R * Vk * 3.0, [&] {
+        launch_row_topk(c->stream, c->dt, D->a_tail, Vk, R, Vk, 1, D->a_lp1, D->a_id1, D->a_lse);   // (for its log-sum-exp)
+        launch_adaptive_virtual(c->stream, c->dt, D->a_tail, Vk, Vk, D->logits, V, ad.lo[k], D->a_head, v0, c0 + k - 1, D->a_lse, R);
+      });
+    }
+  }
   run(c, TFM_PROF_LOSS, 0.0, (double)c->esz * R * V,
       [&] { launch_row_topk(c->stream, c->dt, D->logits, V, R, V, D->topk, D->top_logp, D->top_id, D->lse); });
   const size_t n = (size_t)R * D->topk;

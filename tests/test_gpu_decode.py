@@ -13,6 +13,10 @@ SHAPES = {
     "pre": ModelShape(1, 2, 32, 4, 48, 80, pre_norm=1),
     "lm": ModelShape(0, 2, 32, 2, 64, 96, pre_norm=1),
     "half": ModelShape(2, 2, 128, 2, 256, 512),         # head width 64: the MFMA GEMMs serve rows that are a multiple of 8
+    # adaptive inputs + adaptive softmax: clusters of 24 / 32 / 40 tokens (generic kernels) and of 126 (+2 entries) / 128 / 256
+    # tokens, every table a multiple of 8 rows (matrix-core GEMMs)
+    "adaptive": ModelShape(0, 2, 32, 2, 64, 96, pre_norm=1, cutoffs=(24, 56), factor=2),
+    "adaptive_half": ModelShape(0, 2, 128, 2, 256, 510, pre_norm=1, cutoffs=(126, 254)),
 }
 
 
@@ -26,7 +30,8 @@ def rounded(params, prec):
 def make(shape, prec, max_rows, max_steps, max_src, topk, seed=0):
     import paper_1904_01038_amd as T
     params = rounded(init_params(shape, seed, generic=True), prec)
-    cfg = T.make_config(shape, precision=prec, max_sentences=16, max_len=max(max_steps, 24), max_tokens=256, dropout=0.3)
+    cfg = T.make_config(shape, precision=prec, max_sentences=16, max_len=max(max_steps, 24), max_tokens=256, dropout=0.3,
+                        label_smoothing=0.0 if shape.cutoffs else 0.1)
     ctx = T.Tfm(cfg)
     ctx.set_params(params)
     return ctx, T.Decoder(ctx, max_rows, max_steps, max_src, topk), DecodingOracle(shape, params)
@@ -59,7 +64,8 @@ def check_step(lp_gpu, top_lp, top_id, lp_ref, tol):
 
 
 @pytest.mark.parametrize("name,prec,tol", [("post", "fp32", 2e-4), ("pre", "fp32", 2e-4), ("lm", "fp32", 2e-4),
-                                           ("half", "fp16", 3e-2), ("half", "bf16", 2e-1)])
+                                           ("half", "fp16", 3e-2), ("half", "bf16", 2e-1),
+                                           ("adaptive", "fp32", 2e-4), ("adaptive_half", "fp16", 3e-2), ("adaptive_half", "bf16", 2e-1)])
 def test_steps_with_reordered_beams_match_the_full_decoder(name, prec, tol):
     import paper_1904_01038_amd as T
     shape = SHAPES[name]
@@ -74,6 +80,8 @@ def test_steps_with_reordered_beams_match_the_full_decoder(name, prec, tol):
         hist = [[] for _ in range(B * beam)]
         for t in range(steps):
             prev = np.full(B * beam, shape.eos_id, np.int32) if t == 0 else rng.integers(4, shape.vocab, B * beam).astype(np.int32)
+            if t == 2 and shape.cutoffs:
+                prev[:] = rng.integers(4, shape.cutoffs[0], B * beam)     # a step that feeds head tokens only
             parent = None
             if t:
                 parent = np.array([r // beam * beam + rng.integers(0, beam) for r in range(B * beam)], np.int32)
