@@ -223,11 +223,12 @@ int tfm_op_wgrad_grouped(int32_t dtype, int32_t n, const int32_t* dims, const vo
  * drop_p > 0: inverted dropout on the attention weights; weight (packed query row i, head h, key j of the sentence)
  * uses element ((i * H + h) << 16) + j of the counter-based generator with key drop_key.  The backward call must be
  * given the same key and probability.
- * groups (device int32 [n_groups + 1], or NULL with n_groups = 0): optional packing of short sentences.  Ascending,
- * groups[0] = 0, groups[n_groups] = B; group g is the run of consecutive sentences groups[g] .. groups[g+1]-1, and the
- * query rows of a group as well as its key rows must number at most 64.  When max_lq and max_lk are both at most 64 and
- * drop_p = 0, one block then serves a whole group (the products run over the group's 64-row tiles and a weight counts only
- * inside a sentence); otherwise the table is ignored.  The results do not depend on it. */
+ * groups (device int32 [(n_groups + 1) * 4], 16-byte aligned, or NULL with n_groups = 0): optional packing of short
+ * sentences.  Entry g is {first sentence, first query row, first key row, 0} of group g, the closing entry {B, total_q,
+ * total_k, 0}; a group is a run of at most 16 consecutive sentences whose query rows and whose key rows each number at most
+ * 64.  When max_lq and max_lk are both at most 64 and drop_p = 0, one block then serves a whole group (the products run
+ * over the group's 64-row tiles and a weight counts only inside a sentence); otherwise the table is ignored.  The results
+ * do not depend on it. */
 int tfm_op_attention_fwd(int32_t dtype, const void* q, int32_t ldq, const void* k, int32_t ldk, const void* v,
                          int32_t ldv, void* o, int32_t ldo, float* lse, const int32_t* q_off, const int32_t* k_off,
                          int32_t B, int32_t H, int32_t dh, int32_t max_lq, int32_t max_lk, int32_t total_q,

@@ -74,9 +74,10 @@ struct AttnP {
   uint32_t drop_thr;
   float inv_keep;
   int H;
-  // Launches whose sentences all fit one 64-row chunk: consecutive sentences packed into one block (block g serves
-  // sentences groups[g] .. groups[g+1]-1, at most 64 query rows and 64 key rows in total); null: one sentence per block
-  const int* groups;
+  // Launches whose sentences all fit one 64-row chunk: consecutive sentences packed into one block.  Entry g of the
+  // table is {first sentence, first query row, first key row, 0}; block g serves the sentences from its entry up to the
+  // next entry's (at most 16 of them, at most 64 query rows and 64 key rows in total); null: one sentence per block
+  const int4* groups;
 };
 __device__ __forceinline__ uint64_t attn_drop_word(const AttnP& p, int qrow, int h, int j) {
   return drop_word(p.drop_key, ((((uint64_t)qrow * (uint64_t)p.H + (uint64_t)h) << 16) + (uint64_t)j) >> 2);
@@ -188,7 +189,7 @@ __device__ __forceinline__ void store_rows(uint16_t* __restrict__ G, int ld, int
 }
 
 // ---- forward ------------------------------------------------------------------------------------------------------------
-template <typename T, bool DROP>
+template <typename T, bool DROP, bool PACK>
 __global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_kernel(AttnP p, int H) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[CH * PT];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[CH * PT];
@@ -197,20 +198,30 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_
   // With a group table (one-chunk launches only) a block serves a run of consecutive sentences packed into one 64-row tile;
   // a query then admits the keys klo .. khi-1 of the tile, those of its own sentence.
   const int bi = blockIdx.x / H, h = blockIdx.x - bi * H;
-  const int b0 = p.groups ? p.groups[bi] : bi, b1 = p.groups ? p.groups[bi + 1] : bi + 1;
-  const int q0 = p.q_off[b0], lq = p.q_off[b1] - q0, k0 = p.k_off[b0], lk = p.k_off[b1] - k0;
+  int b0, b1, q0, lq, k0, lk;
+  if (PACK) {                                        // (two independent 16-byte loads: no deeper than the offsets' own)
+    const int4 g0 = p.groups[bi], g1 = p.groups[bi + 1];
+    b0 = g0.x; b1 = g1.x; q0 = g0.y; lq = g1.y - q0; k0 = g0.z; lk = g1.z - k0;
+  } else {
+    b0 = bi; b1 = bi + 1;
+    q0 = p.q_off[b0]; lq = p.q_off[b1] - q0; k0 = p.k_off[b0]; lk = p.k_off[b1] - k0;
+  }
   const int qstart = ((int)gridDim.y - 1 - (int)blockIdx.y) * 64;
   if (qstart >= lq) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int qi0 = qstart + wave * 32;
   const bool active = qi0 < lq;
   const int qi = qi0 + (lane & 31);
-  int klo = 0, khi = qi < lq ? lk : 0, qpos = qi;    // admissible keys of the tile; the query's position inside its sentence
-  if (p.groups) {
+  int klo = 0, khi = lk, qpos = qi;                  // admissible keys of the tile; the query's position inside its sentence
+  if (PACK) {
+    // lanes 0 .. 16 fetch the tile-relative offsets of the group's sentences (one load each, in flight together with the
+    // Q, K and V rows); every lane then finds its own sentence among them by exchange, without touching memory again
+    const int bb = min(b0 + (lane & 31), b1);
+    const int qo = p.q_off[bb] - q0, ko = p.k_off[bb] - k0;
     khi = 0;
-    for (int b = b0; b < b1; ++b) {
-      const int qs = p.q_off[b] - q0, qe = p.q_off[b + 1] - q0;
-      if (qi >= qs && qi < qe) { klo = p.k_off[b] - k0; khi = p.k_off[b + 1] - k0; qpos = qi - qs; }
+    for (int j = 0; j < b1 - b0; ++j) {
+      const int qs = __shfl(qo, j, 64), qe = __shfl(qo, j + 1, 64), ks = __shfl(ko, j, 64), ke = __shfl(ko, j + 1, 64);
+      if (qi >= qs && qi < qe) { klo = ks; khi = ke; qpos = qi - qs; }
     }
   }
   const uint16_t* Q = p.q + (size_t)q0 * p.ldq + h * DH;
@@ -249,13 +260,14 @@ __global__ __launch_bounds__(ATT_THREADS, ATT_FWD_MIN_WAVES) void attn_fwd_mfma_
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int j = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const bool ok = j >= klo && j < khi && (!p.causal || j - klo <= qpos);
+        const bool ok = PACK ? (j >= klo && j < khi && (!p.causal || j - klo <= qpos)) : (j < lk && (!p.causal || j <= qi));
         s[r] = ok ? s[r] * p.scale : -INFINITY;
         bm = fmaxf(bm, s[r]);
       }
       bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-      // (a query of a packed tile may admit no key of the first 32-key block: keep the running maximum out of exp then)
-      const float mn = fmaxf(fmaxf(m, bm), -3.0e38f);
+      // One sentence per tile: mn is finite from the first block on (key 0 is valid for every query).  A query of a packed
+      // tile may admit no key of the first 32-key block: the running maximum is kept out of exp then.
+      const float mn = PACK ? fmaxf(fmaxf(m, bm), -3.0e38f) : fmaxf(m, bm);
       const float alpha = __expf(m - mn);
       float ps = 0.f;
 #pragma unroll
@@ -512,7 +524,7 @@ constexpr int PF = 72;
 // packed token layout) fill at most one 64-row tile each.  The products are formed over the whole tile; a weight counts
 // only where query and key belong to the same sentence, which each row looks up as the range of admissible partners
 // (QR: keys of a query's sentence, KR: queries of a key's sentence, both relative to the tile).
-template <typename T, bool DROP>
+template <typename T, bool DROP, bool PACK>
 __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[CH * PF];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[CH * PF];
@@ -522,15 +534,28 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p
   __shared__ __attribute__((aligned(16))) float Ds[CH];
   __shared__ int QR[CH], KR[CH];                     // partner range lo | hi << 8, own sentence's first row << 16
   const int h = blockIdx.y;
-  const int b0 = p.groups ? p.groups[blockIdx.z] : (int)blockIdx.z, b1 = p.groups ? p.groups[blockIdx.z + 1] : b0 + 1;
-  const int q0 = p.q_off[b0], lq = p.q_off[b1] - q0, k0 = p.k_off[b0], lk = p.k_off[b1] - k0;   // both in [1, 64]
-  if (threadIdx.x < CH) {
+  int b0, b1, q0, lq, k0, lk;                        // lq, lk in [1, 64]
+  if (PACK) {
+    const int4 g0 = p.groups[blockIdx.z], g1 = p.groups[blockIdx.z + 1];
+    b0 = g0.x; b1 = g1.x; q0 = g0.y; lq = g1.y - q0; k0 = g0.z; lk = g1.z - k0;
+  } else {
+    b0 = blockIdx.z; b1 = b0 + 1;
+    q0 = p.q_off[b0]; lq = p.q_off[b1] - q0; k0 = p.k_off[b0]; lk = p.k_off[b1] - k0;
+  }
+  if (threadIdx.x < CH) {                            // (the first wavefront: one lane per tile row)
     const int r = threadIdx.x;
     int qr = 0, kr = 0;                              // empty ranges for rows beyond the tile's sentences
-    for (int b = b0; b < b1; ++b) {
-      const int qs = p.q_off[b] - q0, qe = p.q_off[b + 1] - q0, ks = p.k_off[b] - k0, ke = p.k_off[b + 1] - k0;
-      if (r >= qs && r < qe) qr = ks | (ke << 8) | (qs << 16);
-      if (r >= ks && r < ke) kr = qs | (qe << 8) | (ks << 16);
+    if (PACK) {
+      const int bb = min(b0 + (r & 31), b1);         // lanes 0 .. 16 hold the sentences' tile-relative offsets
+      const int qo = p.q_off[bb] - q0, ko = p.k_off[bb] - k0;
+      for (int j = 0; j < b1 - b0; ++j) {
+        const int qs = __shfl(qo, j, 64), qe = __shfl(qo, j + 1, 64), ks = __shfl(ko, j, 64), ke = __shfl(ko, j + 1, 64);
+        if (r >= qs && r < qe) qr = ks | (ke << 8) | (qs << 16);
+        if (r >= ks && r < ke) kr = qs | (qe << 8) | (ks << 16);
+      }
+    } else {
+      if (r < lq) qr = lk << 8;
+      if (r < lk) kr = lq << 8;
     }
     QR[r] = qr;
     KR[r] = kr;
@@ -617,7 +642,7 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attn_bwd_single_kernel(AttnP p
     for (int qb = 0; qb < 2; ++qb) {
       const int i0 = qb * 32;
       if (i0 >= lq) break;
-      if (p.causal && !p.groups && i0 + 31 < own0) continue;   // (one sentence) every query of this block precedes every key of this wavefront
+      if (p.causal && !PACK && i0 + 31 < own0) continue;      // (one sentence) every query of this block precedes every key of this wavefront
       f32x16 s, dp;
 #pragma unroll
       for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
@@ -705,15 +730,19 @@ static AttnP make_params(const AttnArgs& a) {
 void launch_attention_fwd_mfma(hipStream_t s, const AttnArgs& a) {
   AttnP p = make_params(a);
   const bool drop = p.drop_thr != 0;
-  const bool packed = a.groups != nullptr && a.n_groups > 0 && !drop && a.max_lq <= 64 && a.max_lk <= 64;
-  p.groups = packed ? a.groups : nullptr;
+  // (measured over sentence lengths 11 .. 64 at ~3500 tokens: the forward kernel gains from sharing tiles only from about
+  // three sentences per tile on; below that the group lookup costs what the saved blocks bring)
+  const bool packed = a.groups != nullptr && a.n_groups > 0 && !drop && a.max_lq <= 64 && a.max_lk <= 64 && 3 * a.n_groups <= a.B;
+  p.groups = packed ? (const int4*)a.groups : nullptr;
   dim3 grid(a.H * (packed ? a.n_groups : a.B), (a.max_lq + 63) / 64), block(ATT_THREADS);
   if (a.dt == F16) {
-    if (drop) hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t, true>), grid, block, 0, s, p, a.H);
-    else hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t, false>), grid, block, 0, s, p, a.H);
+    if (drop) hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t, true, false>), grid, block, 0, s, p, a.H);
+    else if (packed) hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t, false, true>), grid, block, 0, s, p, a.H);
+    else hipLaunchKernelGGL((attn_fwd_mfma_kernel<half_t, false, false>), grid, block, 0, s, p, a.H);
   } else {
-    if (drop) hipLaunchKernelGGL((attn_fwd_mfma_kernel<bf16_t, true>), grid, block, 0, s, p, a.H);
-    else hipLaunchKernelGGL((attn_fwd_mfma_kernel<bf16_t, false>), grid, block, 0, s, p, a.H);
+    if (drop) hipLaunchKernelGGL((attn_fwd_mfma_kernel<bf16_t, true, false>), grid, block, 0, s, p, a.H);
+    else if (packed) hipLaunchKernelGGL((attn_fwd_mfma_kernel<bf16_t, false, true>), grid, block, 0, s, p, a.H);
+    else hipLaunchKernelGGL((attn_fwd_mfma_kernel<bf16_t, false, false>), grid, block, 0, s, p, a.H);
   }
 }
 
@@ -722,15 +751,18 @@ void launch_attention_bwd_mfma(hipStream_t s, const AttnArgs& a) {
   const int nq = (a.max_lq + 63) / 64, nk = (a.max_lk + 63) / 64;
   const bool drop = p.drop_thr != 0;
   if (nq == 1 && nk == 1) {                              // every sentence fits one chunk: one block per (group of sentences, head)
-    const bool packed = a.groups != nullptr && a.n_groups > 0 && !drop;
-    p.groups = packed ? a.groups : nullptr;
+    // (the backward kernel gains from 1.5 sentences per tile on: 41 -> 20 us at 11-token sentences, 27 -> 19 us at 21 tokens)
+    const bool packed = a.groups != nullptr && a.n_groups > 0 && !drop && 3 * a.n_groups <= 2 * a.B;
+    p.groups = packed ? (const int4*)a.groups : nullptr;
     dim3 grid(1, a.H, packed ? a.n_groups : a.B), block(ATT_THREADS);
     if (a.dt == F16) {
-      if (drop) hipLaunchKernelGGL((attn_bwd_single_kernel<half_t, true>), grid, block, 0, s, p);
-      else hipLaunchKernelGGL((attn_bwd_single_kernel<half_t, false>), grid, block, 0, s, p);
+      if (drop) hipLaunchKernelGGL((attn_bwd_single_kernel<half_t, true, false>), grid, block, 0, s, p);
+      else if (packed) hipLaunchKernelGGL((attn_bwd_single_kernel<half_t, false, true>), grid, block, 0, s, p);
+      else hipLaunchKernelGGL((attn_bwd_single_kernel<half_t, false, false>), grid, block, 0, s, p);
     } else {
-      if (drop) hipLaunchKernelGGL((attn_bwd_single_kernel<bf16_t, true>), grid, block, 0, s, p);
-      else hipLaunchKernelGGL((attn_bwd_single_kernel<bf16_t, false>), grid, block, 0, s, p);
+      if (drop) hipLaunchKernelGGL((attn_bwd_single_kernel<bf16_t, true, false>), grid, block, 0, s, p);
+      else if (packed) hipLaunchKernelGGL((attn_bwd_single_kernel<bf16_t, false, true>), grid, block, 0, s, p);
+      else hipLaunchKernelGGL((attn_bwd_single_kernel<bf16_t, false, false>), grid, block, 0, s, p);
     }
     return;
   }

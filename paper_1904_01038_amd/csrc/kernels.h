@@ -81,9 +81,10 @@ struct AttnArgs {
   // backward regenerate the same bits from the key.
   uint64_t drop_key = 0;
   float drop_p = 0.f;
-  // Optional packing of short sentences (device int32 [n_groups + 1], ascending, groups[0] = 0, groups[n_groups] = B): group g
-  // is the run of consecutive sentences groups[g] .. groups[g+1]-1, whose query rows and whose key rows each number at most
-  // 64.  Used by the one-chunk kernels when every sentence fits 64 rows and the attention weights have no dropout; null: off.
+  // Optional packing of short sentences: device int32 [(n_groups + 1) * 4], 16-byte aligned, entry g = {first sentence, first
+  // query row, first key row, 0} of group g and a closing entry {B, total query rows, total key rows, 0}.  A group is a run of
+  // at most 16 consecutive sentences whose query rows and whose key rows each number at most 64.  Used by the one-chunk kernels
+  // when every sentence fits 64 rows and the attention weights have no dropout; null: off.
   const int* groups = nullptr;
   int n_groups = 0;
 };

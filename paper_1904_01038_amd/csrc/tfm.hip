@@ -149,7 +149,7 @@ struct tfm_ctx {
   size_t splitk_bytes;
   int *labels, *uentries, *ibase;                   // device ints (ibase = start of the int block)
   int *seg_tok, *seg_beg, *seg_end, *seg_dst, *mt_tok, *mt_row0, *mt_n;
-  int* grp[3];                                      // sentence groups for the packed attention kernels: encoder self, decoder self, cross
+  int* grp[3];                                      // sentence groups for the packed attention kernels (4 ints per entry): encoder self, decoder self, cross
   float* emb_partial;
   size_t int_block_ints;
   Adaptive ad;
@@ -404,7 +404,7 @@ size_t carve(tfm_ctx* c, char* base) {
   const size_t Bc = (size_t)cf.max_sentences + 1;
   const size_t NS = 2 * R + 2 * R / EMB_SEG + 2, NM = 2 * R / EMB_SEG + 2;
   c->emb_partial = (float*)a.take((2 * NM) * d * sizeof(float));
-  c->int_block_ints = 2 * (2 * R + Bc) + R + 2 * R + 4 * NS + 3 * NM + (c->ad.n ? 8 * R : 0) + 3 * Bc;
+  c->int_block_ints = 2 * (2 * R + Bc) + R + 2 * R + 4 * NS + 3 * NM + (c->ad.n ? 8 * R : 0) + 12 * Bc + 4;
   c->ibase = (int*)a.take(c->int_block_ints * 4);
   int* p = c->ibase;
   auto nxt = [&](size_t n) { int* r = base ? p : nullptr; p += n; return r; };
@@ -419,7 +419,9 @@ size_t carve(tfm_ctx* c, char* base) {
     ad.in_idx = nxt(R); ad.in_tok = nxt(R); ad.out_idx = nxt(R); ad.out_lab = nxt(R);
     ad.sg_tok = nxt(R); ad.sg_beg = nxt(R); ad.sg_end = nxt(R); ad.sg_ent = nxt(R);
   }
-  for (int k = 0; k < 3; ++k) c->grp[k] = nxt(Bc);   // (the last 3 * Bc ints of the block)
+  // (the last 12 * Bc ints of the block, moved up to a 16-byte boundary: the kernels read whole entries)
+  p += (4 - ((p - c->ibase) & 3)) & 3;
+  for (int k = 0; k < 3; ++k) c->grp[k] = nxt(4 * Bc);
   return (a.off + 255) & ~(size_t)255;
 }
 
@@ -1245,26 +1247,32 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
       ad.sg_cnt[k] = nseg - ad.sg_off[k];
     }
   }
-  // Short sentences share attention blocks: runs of consecutive sentences whose query rows and key rows each fill at most
-  // one 64-row tile (the one-chunk attention kernels take the table; with longer sentences in the batch it is not used).
+  // Short sentences share attention blocks: runs of at most 16 consecutive sentences whose query rows and key rows each fill
+  // at most one 64-row tile (the one-chunk attention kernels take the table; not used with longer sentences in the batch, nor
+  // when no two sentences fit together).
   {
-    int* grp = hb + (c->int_block_ints - 3 * Bc);
+    int* grp = hb + (c->grp[0] - c->ibase);
     auto build = [&](const int32_t* lq, const int32_t* lk, int maxq, int maxk, int* out) {
       if (maxq > 64 || maxk > 64) return 0;
-      int n = 0, sq = 0, sk = 0;
-      out[0] = 0;
+      int n = 0, first = 0, sq = 0, sk = 0, rq = 0, rk = 0;            // rq, rk: rows before sentence b
+      out[0] = 0; out[1] = 0; out[2] = 0; out[3] = 0;
       for (int b = 0; b < B; ++b) {
-        if (b > out[n] && (sq + lq[b] > 64 || sk + lk[b] > 64)) { out[++n] = b; sq = sk = 0; }
-        sq += lq[b]; sk += lk[b];
+        if (b > first && (sq + lq[b] > 64 || sk + lk[b] > 64 || b - first >= 16)) {
+          ++n;
+          out[4 * n] = b; out[4 * n + 1] = rq; out[4 * n + 2] = rk; out[4 * n + 3] = 0;
+          first = b; sq = sk = 0;
+        }
+        sq += lq[b]; sk += lk[b]; rq += lq[b]; rk += lk[b];
       }
-      out[++n] = B;
-      return n;
+      ++n;
+      out[4 * n] = B; out[4 * n + 1] = rq; out[4 * n + 2] = rk; out[4 * n + 3] = 0;
+      return n < B ? n : 0;                                            // one sentence per group everywhere: nothing to pack
     };
     if (has_enc) {
       s.n_grp[0] = build(src_lens, src_lens, maxs, maxs, grp);
-      s.n_grp[2] = build(tgt_lens, src_lens, maxt, maxs, grp + 2 * Bc);
+      s.n_grp[2] = build(tgt_lens, src_lens, maxt, maxs, grp + 8 * Bc);
     }
-    s.n_grp[1] = build(tgt_lens, tgt_lens, maxt, maxt, grp + Bc);
+    s.n_grp[1] = build(tgt_lens, tgt_lens, maxt, maxt, grp + 4 * Bc);
   }
   HIP_TRY(c, hipMemcpyAsync(c->ibase, hb, c->int_block_ints * 4, hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipEventRecord(c->stage_ev[slot], c->stream));

@@ -50,9 +50,9 @@ def wgrad_grouped(jobs):
 
 
 def attention_fwd(q, k, v, o, lse, q_off, k_off, H, dh, max_lq, max_lk, causal, drop_key=0, drop_p=0.0, groups=None):
-    """groups: optional device int32 tensor [n_groups + 1] (see tfm_op_attention_fwd)."""
+    """groups: optional device int32 tensor [n_groups + 1, 4] (see tfm_op_attention_fwd)."""
     B = q_off.numel() - 1
-    ng = 0 if groups is None else groups.numel() - 1
+    ng = 0 if groups is None else groups.shape[0] - 1
     _check(lib().tfm_op_attention_fwd(_dt(q), _p(q), q.stride(0), _p(k), k.stride(0), _p(v), v.stride(0), _p(o),
                                       o.stride(0), _p(lse), _p(q_off), _p(k_off), B, H, dh, max_lq, max_lk,
                                       lse.shape[1], int(causal), int(drop_key), float(drop_p), _p(groups), ng, _stream()),
@@ -62,7 +62,7 @@ def attention_fwd(q, k, v, o, lse, q_off, k_off, H, dh, max_lq, max_lk, causal, 
 def attention_bwd(q, k, v, o, d_o, lse, dq, dk, dv, q_off, k_off, H, dh, max_lq, max_lk, total_k, causal, drop_key=0,
                   drop_p=0.0, groups=None):
     B = q_off.numel() - 1
-    ng = 0 if groups is None else groups.numel() - 1
+    ng = 0 if groups is None else groups.shape[0] - 1
     _check(lib().tfm_op_attention_bwd(_dt(q), _p(q), q.stride(0), _p(k), k.stride(0), _p(v), v.stride(0), _p(o),
                                       o.stride(0), _p(d_o), d_o.stride(0), _p(lse), _p(dq), dq.stride(0), _p(dk),
                                       dk.stride(0), _p(dv), dv.stride(0), _p(q_off), _p(k_off), B, H, dh, max_lq,

@@ -237,18 +237,20 @@ ATTN_CASES = [  # (query lengths, key lengths or None for self-attention, causal
     ([10, 12, 11, 30, 2, 1, 64, 5, 5, 5, 5, 40, 20, 3, 1, 1, 62], None, True),
     ([10, 12, 11, 30, 2, 1, 64, 5, 5, 5, 5, 40, 20, 3, 1, 1, 62], None, False),
     ([10, 12, 3, 30, 20, 7, 9, 9, 33], [12, 9, 40, 1, 33, 16, 8, 8, 31], False),
+    ([1] * 40 + [3, 2] * 9, None, True),                 # more than 16 sentences would fit a tile: groups are cut at 16
 ]
 
 
 def sentence_groups(lq, lk):
-    """Runs of consecutive sentences whose query rows and key rows each number at most 64 (greedy, as the library's ingest)."""
-    out, sq, sk = [0], 0, 0
+    """Runs of at most 16 consecutive sentences whose query rows and key rows each number at most 64 (greedy, as the library's
+    ingest): one entry {first sentence, first query row, first key row, 0} per group and a closing entry."""
+    out, first, sq, sk, rq, rk = [[0, 0, 0, 0]], 0, 0, 0, 0, 0
     for b in range(len(lq)):
-        if b > out[-1] and (sq + lq[b] > 64 or sk + lk[b] > 64):
-            out.append(b)
-            sq = sk = 0
-        sq, sk = sq + lq[b], sk + lk[b]
-    out.append(len(lq))
+        if b > first and (sq + lq[b] > 64 or sk + lk[b] > 64 or b - first >= 16):
+            out.append([b, rq, rk, 0])
+            first, sq, sk = b, 0, 0
+        sq, sk, rq, rk = sq + lq[b], sk + lk[b], rq + lq[b], rk + lk[b]
+    out.append([len(lq), rq, rk, 0])
     return out
 
 
