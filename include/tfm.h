@@ -111,7 +111,10 @@ int tfm_create(const tfm_config* cfg, void* dev_workspace, size_t bytes, void* h
 void tfm_destroy(tfm_ctx* ctx);                      /* does not free the workspace */
 const char* tfm_last_error(const tfm_ctx* ctx);      /* ctx may be NULL: message of the last failed tfm_create */
 
-/* Parameters: canonical order and names; matrices are row-major W[out, in] (y = x W^T + b). */
+/* Parameters: addressed by index, identified by name (tfm_param_info); the index order is the library's memory order and
+ * carries no meaning of its own (the key/value projections "dec.<l>.cross.wkv" / ".bkv" of all decoder layers are stored
+ * back to back, ahead of the decoder's other parameters, so that one product serves every layer).  Matrices are
+ * row-major W[out, in] (y = x W^T + b). */
 int tfm_num_params(const tfm_ctx* ctx, int32_t* n);
 int tfm_param_info(const tfm_ctx* ctx, int32_t i, char name[64], int64_t shape[2]);   /* shape[1] = 0 for vectors */
 int tfm_set_param(tfm_ctx* ctx, int32_t i, const float* host, int64_t n);  /* sets the fp32 master and the half copy */

@@ -119,8 +119,12 @@ struct tfm_ctx {
   char* ln_pool;
   size_t ln_slice;
   int ln_slices, ln_next;
-  hipEvent_t kv_ready;                              // side-stream mark after the cross-attention K/V projections (null: none)
-  bool kv_done;                                     // they were projected ahead and the main stream already waited
+  // Cross-attention keys and values of all decoder layers: one [rows, layers * 2d] activation (layer l's keys at column
+  // l * 2d, its values at l * 2d + d) written by one product with the stacked weights, and its gradient likewise.
+  int kv_w0, kv_b0;                                 // first stacked weight / bias parameter (-1: no encoder)
+  void *kv_all, *dkv_all;
+  int ld_kv;                                        // layers * 2d
+  hipEvent_t kv_ready;                              // side-stream mark after that product (null: it ran on the main stream)
   // The Adam step also runs on the side stream, cut into chunks in the order the forward pass first touches the
   // parameters (the flat order), so the next sub-batch's forward pass starts while later layers are still being
   // updated: it waits chunk by chunk.  Every other entry point first waits for the whole update.
@@ -142,7 +146,7 @@ struct tfm_ctx {
   int R;                   // row capacity
   // scratch
   void *demb[2];           // gradient w.r.t. the embedding output of the encoder / decoder stream
-  void *y, *dcur, *dsA, *dsB, *dctx, *dmemA, *dmemB, *logits;
+  void *y, *dcur, *dsA, *dsB, *dctx, *dmem, *logits;
   float *loss_rows, *nll_rows, *pe;
   void *red_scratch, *scan_scratch, *splitk_ws;
   void *red_scratch_side, *splitk_ws_side;          // the side stream's own reduction scratch
@@ -199,14 +203,14 @@ namespace {
     if (e_ != hipSuccess) return fail(c, TFM_EHIP, "%s: %s", #expr, hipGetErrorString(e_));        \
   } while (0)
 
-int add_param(std::vector<Param>& ps, int64_t& off, const std::string& name, int64_t rows, int64_t cols) {
+int add_param(std::vector<Param>& ps, int64_t& off, const std::string& name, int64_t rows, int64_t cols, bool pad = true) {
   Param p{name, rows, cols, off};
-  off += (p.numel() + 255) / 256 * 256;
+  off += pad ? (p.numel() + 255) / 256 * 256 : p.numel();
   ps.push_back(p);
   return (int)ps.size() - 1;
 }
 
-void build_params(const tfm_config& c, std::vector<Param>& ps, int64_t& P, Stream& enc, Stream& dec) {
+void build_params(const tfm_config& c, std::vector<Param>& ps, int64_t& P, Stream& enc, Stream& dec, int* kv_w0, int* kv_b0) {
   const int d = c.d_model, F = c.d_ffn;
   int64_t off = 0;
   add_param(ps, off, "embed", c.n_cutoffs ? c.cutoffs[0] + c.n_cutoffs : c.vocab, d);
@@ -238,8 +242,8 @@ void build_params(const tfm_config& c, std::vector<Param>& ps, int64_t& P, Strea
     b.kind = CROSS; b.layer = layer;
     b.w_a = add_param(ps, off, pre + ".cross.wq", d, d);
     b.b_a = add_param(ps, off, pre + ".cross.bq", d, 0);
-    b.w_kv = add_param(ps, off, pre + ".cross.wkv", 2 * d, d);
-    b.b_kv = add_param(ps, off, pre + ".cross.bkv", 2 * d, 0);
+    b.w_kv = *kv_w0 + layer;
+    b.b_kv = *kv_b0 + layer;
     b.w_o = add_param(ps, off, pre + ".cross.wo", d, d);
     b.b_o = add_param(ps, off, pre + ".cross.bo", d, 0);
     ln(pre + ".ln_cross", b.ln_g, b.ln_b);
@@ -262,6 +266,22 @@ void build_params(const tfm_config& c, std::vector<Param>& ps, int64_t& P, Strea
     enc.blocks.push_back(ffn_block(pre, i));
   }
   if (c.enc_layers && c.pre_norm) ln("enc.ln_final", enc.lnf_g, enc.lnf_b);
+  *kv_w0 = *kv_b0 = -1;
+  if (c.enc_layers) {
+    // The key/value projections of every decoder layer's cross-attention read the same encoder output: their weights lie
+    // back to back (no padding between them) as one [layers * 2d, d] matrix, their biases as one vector, so that one
+    // product serves all layers.  (2 d d and 2 d elements keep every slice 32-byte aligned since d is a multiple of 8.)
+    for (int i = 0; i < c.dec_layers; ++i) {
+      const int p = add_param(ps, off, "dec." + std::to_string(i) + ".cross.wkv", 2 * d, d, false);
+      if (i == 0) *kv_w0 = p;
+    }
+    off = (off + 255) / 256 * 256;
+    for (int i = 0; i < c.dec_layers; ++i) {
+      const int p = add_param(ps, off, "dec." + std::to_string(i) + ".cross.bkv", 2 * d, 0, false);
+      if (i == 0) *kv_b0 = p;
+    }
+    off = (off + 255) / 256 * 256;
+  }
   for (int i = 0; i < c.dec_layers; ++i) {
     const std::string pre = "dec." + std::to_string(i);
     dec.blocks.push_back(self_block(pre, i));
@@ -328,6 +348,9 @@ size_t carve(tfm_ctx* c, char* base) {
   c->g = a.take(c->P * esz);
   c->Wh = c->dt == F32 ? (void*)c->W : a.take(c->P * esz);
   c->st = (DevState*)a.take(sizeof(DevState));
+  c->ld_kv = cf.enc_layers ? cf.dec_layers * 2 * (int)d : 0;
+  c->kv_all = cf.enc_layers ? a.take(R * c->ld_kv * esz) : nullptr;
+  c->dkv_all = cf.enc_layers ? a.take(R * c->ld_kv * esz) : nullptr;
   for (Stream* s : {&c->enc, &c->dec}) {
     const size_t K = s->blocks.size();
     if (K == 0) continue;
@@ -342,8 +365,10 @@ size_t carve(tfm_ctx* c, char* base) {
     for (Block& b : s->blocks) {
       if (b.kind == SELF) { b.inter = a.take(R * 3 * d * esz); b.ctx = a.take(R * d * esz); b.lse = (float*)a.take(H * R * 4); b.dint = a.take(R * 3 * d * esz); }
       else if (b.kind == CROSS) {
-        b.inter = a.take(R * d * esz); b.kv = a.take(R * 2 * d * esz); b.ctx = a.take(R * d * esz); b.lse = (float*)a.take(H * R * 4);
-        b.dint = a.take(R * d * esz); b.dkv = a.take(R * 2 * d * esz);
+        b.inter = a.take(R * d * esz); b.ctx = a.take(R * d * esz); b.lse = (float*)a.take(H * R * 4);
+        b.dint = a.take(R * d * esz);
+        b.kv = c->kv_all ? (char*)c->kv_all + (size_t)b.layer * 2 * d * esz : nullptr;
+        b.dkv = c->dkv_all ? (char*)c->dkv_all + (size_t)b.layer * 2 * d * esz : nullptr;
       } else { b.inter = a.take(R * F * esz); b.dint = a.take(R * F * esz); }
       b.dy = a.take(R * d * esz);
     }
@@ -356,8 +381,7 @@ size_t carve(tfm_ctx* c, char* base) {
   c->dsA = a.take(R * d * esz);
   c->dsB = a.take(R * d * esz);
   c->dctx = a.take(R * d * esz);
-  c->dmemA = a.take(R * d * esz);
-  c->dmemB = a.take(R * d * esz);
+  c->dmem = a.take(R * d * esz);
   {
     Adaptive& ad = c->ad;
     ad.n = cf.n_cutoffs;
@@ -572,7 +596,7 @@ int tfm_workspace_bytes(const tfm_config* cfg, size_t* bytes) {
   tmp.cfg = *cfg;
   tmp.dt = cfg->precision;
   tmp.esz = dtype_size(tmp.dt);
-  build_params(*cfg, tmp.params, tmp.P, tmp.enc, tmp.dec);
+  build_params(*cfg, tmp.params, tmp.P, tmp.enc, tmp.dec, &tmp.kv_w0, &tmp.kv_b0);
   *bytes = carve(&tmp, nullptr);
   return TFM_OK;
 }
@@ -589,7 +613,7 @@ int tfm_create(const tfm_config* cfg, void* ws, size_t bytes, void* hip_stream, 
   c->dt = cfg->precision;
   c->esz = dtype_size(c->dt);
   c->R = cfg->max_tokens;
-  build_params(*cfg, c->params, c->P, c->enc, c->dec);
+  build_params(*cfg, c->params, c->P, c->enc, c->dec, &c->kv_w0, &c->kv_b0);
   const size_t need = carve(c, nullptr);
   if (bytes < need) {
     delete c;
@@ -608,12 +632,14 @@ int tfm_create(const tfm_config* cfg, void* ws, size_t bytes, void* hip_stream, 
   c->wq_tiles = 0;
   c->wq_flush_tiles = 4096;
   {
-    // chunk boundaries: the embedding, then one chunk per block (its parameters are contiguous), final norms with
+    // chunk boundaries: the embedding, then one chunk per block (its parameters are contiguous; the cross-attention blocks'
+    // stacked key/value projections are a chunk of their own between the two streams' blocks), final norms with
     // the block before them
     std::vector<int> first;                         // first parameter of each chunk
     first.push_back(0);
     for (Stream* st : {&c->enc, &c->dec})
       for (Block& b : st->blocks) first.push_back(b.w_a);
+    if (c->kv_w0 >= 0) first.push_back(c->kv_w0);    // the stacked key/value projections of the cross-attention blocks
     std::sort(first.begin(), first.end());
     c->chunk_of.assign(c->params.size(), 0);
     for (size_t k = 0; k < first.size(); ++k) {
@@ -874,10 +900,9 @@ void sublayer_fwd(const StepCtx& s, Stream& st, int k, const void* fin, void* y)
     Stream& en = c->enc;
     const void* mem = en.norm[en.blocks.size()];
     gemm(c, 0, T, d, d, fin, d, wh(c, b.w_a), d, b.inter, d, wh(c, b.b_a));
-    if (c->kv_ready) { main_wait(c, c->kv_ready); c->kv_done = true; }   // projected ahead on the side stream (see tfm_train_step) ...
-    else if (!c->kv_done) gemm(c, 0, en.rows, 2 * d, d, mem, d, wh(c, b.w_kv), d, b.kv, 2 * d, wh(c, b.b_kv));   // ... or here
+    if (c->kv_ready) { main_wait(c, c->kv_ready); c->kv_ready = nullptr; }   // the keys and values of all layers (see tfm_train_step)
     const char* kv = (const char*)b.kv;
-    attention(s, false, st, en, s.tlen, s.slen, b.inter, d, kv, 2 * d, kv + d * c->esz, 2 * d, b.ctx, b.lse, false,
+    attention(s, false, st, en, s.tlen, s.slen, b.inter, d, kv, c->ld_kv, kv + d * c->esz, c->ld_kv, b.ctx, b.lse, false,
               site_key(s, st.id, b.layer, 4));
     gemm(c, 0, T, d, d, b.ctx, d, wh(c, b.w_o), d, y, d, wh(c, b.b_o));
   } else {
@@ -930,8 +955,7 @@ void stream_fwd(const StepCtx& s, Stream& st) {
 
 // backward of sub-layer k given dy (which lives in the block's own b.dy); writes the gradient w.r.t. its input (plus
 // `residual` if given) to dout.  Weight and bias gradients are queued (see wgrad).
-void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const void* fin, const void* residual, void* dout,
-                  void** dmem_cur, void** dmem_other, bool* dmem_valid) {
+void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const void* fin, const void* residual, void* dout) {
   tfm_ctx* c = s.c;
   Block& b = st.blocks[k];
   const int d = c->cfg.d_model, F = c->cfg.d_ffn, T = st.rows;
@@ -947,19 +971,16 @@ void sublayer_bwd(const StepCtx& s, Stream& st, int k, const void* dy, const voi
     wgrad(c, 3 * d, d, T, dqkv, 3 * d, fin, d, gr(c, b.w_a), d, gr(c, b.b_a));
   } else if (b.kind == CROSS) {
     Stream& en = c->enc;
-    const void* mem = en.norm[en.blocks.size()];
     wgrad(c, d, d, T, dy, d, b.ctx, d, gr(c, b.w_o), d, gr(c, b.b_o));
     gemm(c, 1, T, d, d, dy, d, wh(c, b.w_o), d, c->dctx, d);
     const char* kv = (const char*)b.kv;
     char* dkv = (char*)b.dkv;
-    attention(s, true, st, en, s.tlen, s.slen, b.inter, d, kv, 2 * d, kv + d * c->esz, 2 * d, b.ctx, b.lse, false,
-              site_key(s, st.id, b.layer, 4), c->dctx, b.dint, d, dkv, 2 * d, dkv + d * c->esz, 2 * d);
+    // the gradients w.r.t. this layer's keys and values land in its columns of dkv_all; the encoder output's gradient and the
+    // stacked weights' are formed from all layers at once after the decoder's backward pass (see tfm_train_step)
+    attention(s, true, st, en, s.tlen, s.slen, b.inter, d, kv, c->ld_kv, kv + d * c->esz, c->ld_kv, b.ctx, b.lse, false,
+              site_key(s, st.id, b.layer, 4), c->dctx, b.dint, d, dkv, c->ld_kv, dkv + d * c->esz, c->ld_kv);
     gemm(c, 1, T, d, d, b.dint, d, wh(c, b.w_a), d, dout, d, nullptr, 0, nullptr, residual);
-    gemm(c, 1, en.rows, d, 2 * d, dkv, 2 * d, wh(c, b.w_kv), d, *dmem_other, d, nullptr, 0, nullptr, *dmem_valid ? *dmem_cur : nullptr);
-    std::swap(*dmem_cur, *dmem_other);
-    *dmem_valid = true;
     wgrad(c, d, d, T, b.dint, d, fin, d, gr(c, b.w_a), d, gr(c, b.b_a));
-    wgrad(c, 2 * d, d, en.rows, dkv, 2 * d, mem, d, gr(c, b.w_kv), d, gr(c, b.b_kv));
   } else {
     wgrad(c, d, F, T, dy, d, b.inter, F, gr(c, b.w_o), F, gr(c, b.b_o));
     // the saved hidden activations are positive exactly where the ReLU passed AND the unit was kept: the mask, times the
@@ -989,7 +1010,7 @@ void ln_bwd(tfm_ctx* c, const void* dn, const void* add, const void* sres, const
 
 // Backward through a stream.  On entry c->dcur holds the gradient w.r.t. the stream output norm[K]; returns the buffer
 // holding the gradient w.r.t. the embedding output.
-void* stream_bwd(const StepCtx& s, Stream& st, void** dmem_cur, void** dmem_other, bool* dmem_valid, void* dn_in) {
+void* stream_bwd(const StepCtx& s, Stream& st, void* dn_in) {
   tfm_ctx* c = s.c;
   const int K = (int)st.blocks.size(), T = st.rows;
   const bool pre = c->cfg.pre_norm != 0;
@@ -1005,7 +1026,7 @@ void* stream_bwd(const StepCtx& s, Stream& st, void** dmem_cur, void** dmem_othe
       void* ds = drop ? c->dsA : b.dy;
       ln_bwd(c, dn, nullptr, st.resid[k + 1], st.mean[k + 1], st.rstd[k + 1], b.ln_g, b.ln_b, ds, b.dy, -1, T, block_key(s, st, k));
       void* out = k == 0 ? c->demb[st.id] : c->dcur;
-      sublayer_bwd(s, st, k, b.dy, st.norm[k], ds, out, dmem_cur, dmem_other, dmem_valid);
+      sublayer_bwd(s, st, k, b.dy, st.norm[k], ds, out);
       dn = out;
     }
     return dn;
@@ -1022,7 +1043,7 @@ void* stream_bwd(const StepCtx& s, Stream& st, void** dmem_cur, void** dmem_othe
     void* ds = idx == 0 ? c->demb[st.id] : (drop ? pp : bdy);
     ln_bwd(c, dn, dR, st.resid[idx], st.mean[idx], st.rstd[idx], g, b, ds, bdy, -1, T, idx >= 1 ? block_key(s, st, idx - 1) : 0);
     if (idx == 0) return ds;
-    sublayer_bwd(s, st, idx - 1, bdy, st.norm[idx - 1], nullptr, c->dcur, dmem_cur, dmem_other, dmem_valid);
+    sublayer_bwd(s, st, idx - 1, bdy, st.norm[idx - 1], nullptr, c->dcur);
     dn = c->dcur;
     dR = ds;
     std::swap(pp, pp_alt);
@@ -1292,19 +1313,16 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   c->lnq.clear();
   c->ln_next = 0;
   c->kv_ready = nullptr;
-  c->kv_done = false;
   if (has_enc) {
     stream_fwd(s, c->enc);
-    if (c->overlap) {
-      // Every decoder layer's cross-attention keys and values depend on the encoder output alone: project them on the
-      // side stream while the decoder's first blocks run; the first cross-attention block waits for all of them.
-      side_begin(c);
-      const void* mem = c->enc.norm[c->enc.blocks.size()];
-      for (Block& b : c->dec.blocks)
-        if (b.kind == CROSS)
-          gemm(c, 0, c->enc.rows, 2 * d, d, mem, d, wh(c, b.w_kv), d, b.kv, 2 * d, wh(c, b.b_kv), 0, nullptr, nullptr, true);
-      c->kv_ready = mark(c, c->side);
-    }
+    // Every decoder layer's cross-attention keys and values depend on the encoder output alone: one product with the
+    // stacked weights projects them all.  With the side stream on it runs there beside the decoder's first block, and
+    // the first cross-attention block waits for it.
+    const void* mem = c->enc.norm[c->enc.blocks.size()];
+    need(c, c->kv_b0 + cf.dec_layers - 1);
+    if (c->overlap) side_begin(c);
+    gemm(c, 0, c->enc.rows, c->ld_kv, d, mem, d, wh(c, c->kv_w0), d, c->kv_all, c->ld_kv, wh(c, c->kv_b0), 0, nullptr, nullptr, true);
+    if (c->overlap) c->kv_ready = mark(c, c->side);
   }
   stream_fwd(s, c->dec);
   Stream& de = c->dec;
@@ -1326,13 +1344,17 @@ int tfm_train_step(tfm_ctx* c, const int32_t* src, const int32_t* tgt, const int
   gemm(c, 1, (int)Tt, d, V0, c->logits, V0, c->Wh, d, c->dcur, d);
   if (ad.n) adaptive_tails(s, top, mult);          // tail clusters: their losses, gradients, and their share of dcur
   run(c, TFM_PROF_LOSS, 0.0, 8.0 * (double)Tt, [&] { launch_sum_rows(c->stream, c->loss_rows, c->nll_rows, (int)Tt, &c->st->loss_sum); });
-  void* dmem_cur = c->dmemA;
-  void* dmem_other = c->dmemB;
-  bool dmem_valid = false;
-  void* ddec = stream_bwd(s, de, &dmem_cur, &dmem_other, &dmem_valid, c->dcur);
-  flush_wgrads(c);                                 // the decoder's weight gradients run beside the encoder's backward pass
+  void* ddec = stream_bwd(s, de, c->dcur);
   void* denc = nullptr;
-  if (has_enc) denc = stream_bwd(s, c->enc, &dmem_cur, &dmem_other, &dmem_valid, dmem_cur);
+  if (has_enc) {
+    // all layers' key/value gradients at once: the encoder output's gradient (one product over the layers * 2d columns) and
+    // the stacked projection weights' and biases'
+    const void* mem = c->enc.norm[c->enc.blocks.size()];
+    gemm(c, 1, c->enc.rows, d, c->ld_kv, c->dkv_all, c->ld_kv, wh(c, c->kv_w0), d, c->dmem, d);
+    wgrad(c, c->ld_kv, d, c->enc.rows, c->dkv_all, c->ld_kv, mem, d, gr(c, c->kv_w0), d, gr(c, c->kv_b0));
+  }
+  flush_wgrads(c);                                 // the decoder's weight gradients run beside the encoder's backward pass
+  if (has_enc) denc = stream_bwd(s, c->enc, c->dmem);
   flush_wgrads(c);
   if (c->overlap) order(c, c->side, c->stream);                            // join: every weight gradient is in g
   if (ad.n) adaptive_embed_bwd(s, ddec);

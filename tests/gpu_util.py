@@ -20,7 +20,7 @@ def make_pair(shape, precision, *, dropout=0.0, seed_params=0, max_sentences=64,
                         scale_window=scale_window, clip_norm=clip_norm, seed=seed, attn_dropout=attn_dropout,
                         relu_dropout=relu_dropout, weight_decay=weight_decay)
     gpu = T.Tfm(cfg)
-    assert gpu.param_names == list(params.keys())
+    assert sorted(gpu.param_names) == sorted(params.keys())          # same names; the library orders them by its own memory layout
     gpu.set_params(params)
     ocfg = TrainConfig(weight_decay=weight_decay, dropout=dropout, attn_dropout=attn_dropout, relu_dropout=relu_dropout, label_smoothing=label_smoothing, init_loss_scale=init_loss_scale,
                        scale_window=scale_window, clip_norm=clip_norm, fp16_overflow=(precision == T.FP16),
