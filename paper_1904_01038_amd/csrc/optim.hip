@@ -26,23 +26,38 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(const T* __restrict_
                                                             float* __restrict__ partial) {
   __shared__ float sh[16];
   float bad = 0.f, sq = 0.f;
+  // two vectors in flight per lane, non-temporal: the data is on its way through, nothing here reads it twice
   const int64_t stride = (int64_t)gridDim.x * SCAN_THREADS * SCAN_VEC;
-  for (int64_t i = ((int64_t)blockIdx.x * SCAN_THREADS + threadIdx.x) * SCAN_VEC; i < n; i += stride) {
-    float v[SCAN_VEC];
-    load_f<T, SCAN_VEC>(x + i, v);
+  for (int64_t i = ((int64_t)blockIdx.x * SCAN_THREADS + threadIdx.x) * SCAN_VEC; i < n; i += 2 * stride) {
+    const int64_t i1 = i + stride;
+    const bool two = i1 < n;
+    float v[2][SCAN_VEC];
+    load_f_nt<T, SCAN_VEC>(x + i, v[0]);
+    if (two) load_f_nt<T, SCAN_VEC>(x + i1, v[1]);
+    else {
 #pragma unroll
-    for (int k = 0; k < SCAN_VEC; ++k) {
-      if (!(fabsf(v[k]) <= 3.402823466e38f)) bad = 1.f;
-      sq += v[k] * v[k];
+      for (int k = 0; k < SCAN_VEC; ++k) v[1][k] = 0.f;
     }
-    if (ACC == 1) {
-      store_f<float, SCAN_VEC>(acc + i, v);
-    } else if (ACC == 2) {
-      float a[SCAN_VEC];
-      load_f<float, SCAN_VEC>(acc + i, a);
+    float a[2][SCAN_VEC] = {};
+    if (ACC == 2) {
+      load_f_nt<float, SCAN_VEC>(acc + i, a[0]);
+      if (two) load_f_nt<float, SCAN_VEC>(acc + i1, a[1]);
+    }
 #pragma unroll
-      for (int k = 0; k < SCAN_VEC; ++k) a[k] += v[k];
-      store_f<float, SCAN_VEC>(acc + i, a);
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int k = 0; k < SCAN_VEC; ++k) {
+        if (!(fabsf(v[u][k]) <= 3.402823466e38f)) bad = 1.f;
+        sq += v[u][k] * v[u][k];
+      }
+    if (ACC == 1) {
+      store_f_nt<float, SCAN_VEC>(acc + i, v[0]);
+      if (two) store_f_nt<float, SCAN_VEC>(acc + i1, v[1]);
+    } else if (ACC == 2) {
+#pragma unroll
+      for (int k = 0; k < SCAN_VEC; ++k) { a[0][k] += v[0][k]; a[1][k] += v[1][k]; }
+      store_f_nt<float, SCAN_VEC>(acc + i, a[0]);
+      if (two) store_f_nt<float, SCAN_VEC>(acc + i1, a[1]);
     }
   }
   bad = block_max(bad, sh);
@@ -180,43 +195,56 @@ void launch_scaler_update(hipStream_t s, DevState* st, long long ntokens, float 
 
 // ---- Adam -------------------------------------------------------------------------------------------------------------------
 // Per parameter: read w, m, v (12 B) and the gradient (2 or 4 B), write w, m, v (12 B) and the half model copy (2 B).
-constexpr int ADAM_VEC = 4;
+// One pass, no loop: a thread owns ADAM_UN groups of ADAM_VEC consecutive parameters, a block's width apart, issues all their
+// loads before the first result is needed, and touches everything with non-temporal accesses (nothing here is read again
+// before the next forward pass has gone through hundreds of megabytes).  Measured on the big model's 210 M parameters
+// against a grid-stride loop over plain accesses: 1.27 -> 1.01 ms (4.6 -> 5.8 TB/s).
+constexpr int ADAM_VEC = 4, ADAM_UN = 4, ADAM_THREADS = 256;
 template <typename GT, typename HT>
-__global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ w, float* __restrict__ m, float* __restrict__ v,
-                                                   const GT* __restrict__ g, HT* __restrict__ hcopy, int64_t n, float lr, float beta1,
-                                                   float beta2, float eps, const DevState* __restrict__ st, float grad_mult,
-                                                   float bc1, float bc2, float wd) {
+__global__ __launch_bounds__(ADAM_THREADS) void adam_kernel(float* __restrict__ w, float* __restrict__ m, float* __restrict__ v,
+                                                            const GT* __restrict__ g, HT* __restrict__ hcopy, int64_t n, float lr,
+                                                            float beta1, float beta2, float eps, const DevState* __restrict__ st,
+                                                            float grad_mult, float bc1, float bc2, float wd) {
   if (st) {
     if (st->skipped) return;
     grad_mult = st->grad_mult; bc1 = st->bc1; bc2 = st->bc2;
   }
   const float step = lr / bc1, rbc2 = 1.f / bc2;
-  const int64_t stride = (int64_t)gridDim.x * 256 * ADAM_VEC;
-  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * ADAM_VEC; i < n; i += stride) {
-    float wv[ADAM_VEC], mv[ADAM_VEC], vv[ADAM_VEC], gv[ADAM_VEC];
-    load_f<float, ADAM_VEC>(w + i, wv);
-    load_f<float, ADAM_VEC>(m + i, mv);
-    load_f<float, ADAM_VEC>(v + i, vv);
-    load_f<GT, ADAM_VEC>(g + i, gv);
+  const int64_t i0 = ((int64_t)blockIdx.x * ADAM_UN * ADAM_THREADS + threadIdx.x) * ADAM_VEC;
+  float wv[ADAM_UN][ADAM_VEC], mv[ADAM_UN][ADAM_VEC], vv[ADAM_UN][ADAM_VEC], gv[ADAM_UN][ADAM_VEC];
 #pragma unroll
-    for (int k = 0; k < ADAM_VEC; ++k) {
-      const float gg = gv[k] * grad_mult + wd * wv[k];
-      mv[k] = beta1 * mv[k] + (1.f - beta1) * gg;
-      vv[k] = beta2 * vv[k] + (1.f - beta2) * gg * gg;
-      wv[k] -= step * mv[k] / (sqrtf(vv[k] * rbc2) + eps);
+  for (int u = 0; u < ADAM_UN; ++u) {
+    const int64_t i = i0 + (int64_t)u * ADAM_THREADS * ADAM_VEC;
+    if (i < n) {
+      load_f_nt<float, ADAM_VEC>(w + i, wv[u]);
+      load_f_nt<float, ADAM_VEC>(m + i, mv[u]);
+      load_f_nt<float, ADAM_VEC>(v + i, vv[u]);
+      load_f_nt<GT, ADAM_VEC>(g + i, gv[u]);
     }
-    store_f<float, ADAM_VEC>(w + i, wv);
-    store_f<float, ADAM_VEC>(m + i, mv);
-    store_f<float, ADAM_VEC>(v + i, vv);
-    if (hcopy) store_f<HT, ADAM_VEC>(hcopy + i, wv);
+  }
+#pragma unroll
+  for (int u = 0; u < ADAM_UN; ++u) {
+    const int64_t i = i0 + (int64_t)u * ADAM_THREADS * ADAM_VEC;
+    if (i < n) {
+#pragma unroll
+      for (int k = 0; k < ADAM_VEC; ++k) {
+        const float gg = gv[u][k] * grad_mult + wd * wv[u][k];
+        mv[u][k] = beta1 * mv[u][k] + (1.f - beta1) * gg;
+        vv[u][k] = beta2 * vv[u][k] + (1.f - beta2) * gg * gg;
+        wv[u][k] -= step * mv[u][k] / (sqrtf(vv[u][k] * rbc2) + eps);
+      }
+      store_f_nt<float, ADAM_VEC>(w + i, wv[u]);
+      store_f_nt<float, ADAM_VEC>(m + i, mv[u]);
+      store_f_nt<float, ADAM_VEC>(v + i, vv[u]);
+      if (hcopy) store_f_nt<HT, ADAM_VEC>(hcopy + i, wv[u]);
+    }
   }
 }
 
 template <typename GT>
 static void adam_dispatch(hipStream_t s, const AdamArgs& a) {
-  int64_t b = (a.n + 256 * ADAM_VEC - 1) / (256 * ADAM_VEC);
-  if (b > 8192) b = 8192;
-  dim3 grid((unsigned)(b < 1 ? 1 : b)), block(256);
+  const int64_t per_block = (int64_t)ADAM_THREADS * ADAM_VEC * ADAM_UN;
+  dim3 grid((unsigned)((a.n + per_block - 1) / per_block)), block(ADAM_THREADS);      // n < 2^31 * 4096: the grid fits
 #define ADAM(HT)                                                                                                       \
   hipLaunchKernelGGL((adam_kernel<GT, HT>), grid, block, 0, s, a.w, a.m, a.v, (const GT*)a.g, (HT*)a.half_copy, a.n, a.lr, \
                      a.beta1, a.beta2, a.eps, a.st, a.grad_mult, a.bc1, a.bc2, a.weight_decay)

@@ -45,10 +45,12 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(float* out, int iters) 
   out[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
 }
 
-// Plain streaming copy, 16 bytes per lane and access, grid-stride.
-__global__ __launch_bounds__(256) void copy_probe_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
-  const size_t stride = (size_t)gridDim.x * 256;
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+// Plain streaming copy: 16 bytes per lane, one access each way per thread, non-temporal (the fastest form of a copy found
+// on this device: 6.4-6.5 TB/s read + written over 1 GiB, against 4.8 TB/s for a grid-stride loop over plain accesses).
+typedef unsigned int copy_vec __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void copy_probe_kernel(copy_vec* __restrict__ dst, const copy_vec* __restrict__ src, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 // Re-reads a private region per block with 16-byte loads, 8 in flight per lane: the rate at which a compute unit can pull
@@ -107,11 +109,12 @@ int tfm_probe_copy(void* dst, const void* src, size_t bytes, double* gbs, void* 
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return TFM_EHIP;
   const size_t n = bytes / 16;
-  const unsigned grid = (unsigned)std::min<size_t>((n + 255) / 256, 16384);
+  if ((n + 255) / 256 > 0x7fffffffull) return TFM_EINVAL;
+  const unsigned grid = (unsigned)((n + 255) / 256);
   const int reps = 10;
-  hipLaunchKernelGGL(copy_probe_kernel, dim3(grid), dim3(256), 0, s, (uint4*)dst, (const uint4*)src, n);
+  hipLaunchKernelGGL(copy_probe_kernel, dim3(grid), dim3(256), 0, s, (copy_vec*)dst, (const copy_vec*)src, n);
   hipEventRecord(e0, s);
-  for (int r = 0; r < reps; ++r) hipLaunchKernelGGL(copy_probe_kernel, dim3(grid), dim3(256), 0, s, (uint4*)dst, (const uint4*)src, n);
+  for (int r = 0; r < reps; ++r) hipLaunchKernelGGL(copy_probe_kernel, dim3(grid), dim3(256), 0, s, (copy_vec*)dst, (const copy_vec*)src, n);
   hipEventRecord(e1, s);
   float ms = 0.f;
   const bool ok = hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms > 0.f;
