@@ -106,10 +106,112 @@ __global__ __launch_bounds__(64) void decode_attention_kernel(DecodeAttnArgs p) 
   }
 }
 
+// The same for head width 64 and 2-byte elements, arranged so that no phase waits for more than one round trip to memory:
+//   phase 1  lane = position: the 8 loads of a key row are issued together
+//   phase 3  lane = (position group g = lane / 8, feature vector f = lane % 8): a lane reads 16 bytes of V for the positions
+//            s = g, g + 8, ... (four of them in flight), and the eight groups are added up with three lane exchanges
+template <typename T>
+__global__ __launch_bounds__(64) void decode_attention64_kernel(DecodeAttnArgs p) {
+  extern __shared__ float smem[];
+  constexpr int dh = 64;
+  const int r = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+  int n, base = 0;
+  if (p.anc) n = p.t + 1;
+  else { const int s = r / p.beam; base = p.src_off[s]; n = p.src_off[s + 1] - base; }
+  float* sc = smem;
+  int* rowi = reinterpret_cast<int*>(smem + p.n_max);
+  float* qs = smem + 2 * p.n_max;
+  const T* q = reinterpret_cast<const T*>(p.q) + (size_t)r * p.ldq + h * dh;
+  qs[lane] = to_f<T>(q[lane]);
+  const T* K = reinterpret_cast<const T*>(p.k);
+  const T* V = reinterpret_cast<const T*>(p.v);
+  // position t of a self-attention step may still be outside the caches: it is read from the new rows, and 16 lanes copy
+  // this head's 128 + 128 bytes into the row's own cache lines for the steps to come (nobody reads them during this launch)
+  const T* knew = nullptr;
+  const T* vnew = nullptr;
+  if (p.anc && p.k_new) {
+    knew = reinterpret_cast<const T*>(p.k_new) + (size_t)r * p.ld_new + h * dh;
+    vnew = reinterpret_cast<const T*>(p.v_new) + (size_t)r * p.ld_new + h * dh;
+    if (lane < 16) {
+      const size_t dst = ((size_t)r * p.max_steps + p.t) * p.row_stride + h * dh + (lane & 7) * 8;
+      typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+      const T* src = (lane < 8 ? knew : vnew) + (lane & 7) * 8;
+      T* cache = const_cast<T*>(lane < 8 ? K : V);
+      *reinterpret_cast<u4*>(cache + dst) = *reinterpret_cast<const u4*>(src);
+    }
+  }
+  __syncthreads();
+  const float scale = 0.125f;
+  float lmax = -INFINITY;
+  for (int s = lane; s < n; s += 64) {
+    const long long off = p.anc ? ((long long)p.anc[(size_t)r * p.max_steps + s] * p.max_steps + s) * p.row_stride + h * dh
+                                : (long long)(base + s) * p.row_stride + h * dh;
+    const T* kr = (knew && s == p.t) ? knew : K + off;
+    float kv[8][8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) load_f<T, 8>(kr + j * 8, kv[j]);
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc += qs[j * 8 + i] * kv[j][i];
+    acc *= scale;
+    sc[s] = acc;
+    rowi[s] = (int)off;
+    lmax = fmaxf(lmax, acc);
+  }
+  const float m = wave_max(lmax);
+  float lsum = 0.f;
+  for (int s = lane; s < n; s += 64) {
+    const float e = __expf(sc[s] - m);
+    sc[s] = e;
+    lsum += e;
+  }
+  const float inv = 1.f / wave_sum(lsum);
+  __syncthreads();
+  const int g = lane >> 3, f = lane & 7;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  for (int s0 = g; s0 < n; s0 += 32) {
+    float v[4][8], w[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int s = s0 + 8 * u;
+      w[u] = s < n ? sc[s] : 0.f;
+      const int sv = s < n ? s : s0;                                // (a position past the end re-reads a valid row, weight 0)
+      load_f<T, 8>(((vnew && sv == p.t) ? vnew : V + rowi[sv]) + f * 8, v[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += w[u] * v[u][i];
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    acc[i] += __shfl_xor(acc[i], 8, 64);
+    acc[i] += __shfl_xor(acc[i], 16, 64);
+    acc[i] += __shfl_xor(acc[i], 32, 64);
+    acc[i] *= inv;
+  }
+  if (g == 0) store_f<T, 8>(reinterpret_cast<T*>(p.o) + (size_t)r * p.ldo + h * dh + f * 8, acc);
+}
+
+// (16-byte accesses: the host side lays q, the caches and the output out with head slices at multiples of 128 bytes)
+static bool decode_attention_fast(const DecodeAttnArgs& a) {
+  return a.dh == 64 && a.dt != F32 && a.ldq % 8 == 0 && a.row_stride % 8 == 0 && a.ldo % 8 == 0 && (!a.k_new || a.ld_new % 8 == 0);
+}
+bool decode_attention_appends(const DecodeAttnArgs& a) { return a.anc && a.k_new && a.v_new && decode_attention_fast(a); }
+
 void launch_decode_attention(hipStream_t s, const DecodeAttnArgs& a) {
   if (a.rows <= 0) return;
   dim3 grid(a.rows, a.H), block(64);
   const size_t smem = (size_t)(2 * a.n_max + a.dh) * sizeof(float);
+  if (decode_attention_fast(a)) {
+    if (a.dt == F16) hipLaunchKernelGGL((decode_attention64_kernel<half_t>), grid, block, smem, s, a);
+    else hipLaunchKernelGGL((decode_attention64_kernel<bf16_t>), grid, block, smem, s, a);
+    return;
+  }
   const bool vec = a.dh % 8 == 0;
 #define DA(T, VEC) hipLaunchKernelGGL((decode_attention_kernel<T, VEC>), grid, block, smem, s, a)
   if (a.dt == F32) { if (vec) DA(float, 8); else DA(float, 1); }

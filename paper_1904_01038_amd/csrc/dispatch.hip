@@ -5,6 +5,7 @@
 namespace tfm {
 
 void launch_gemm(hipStream_t s, const GemmArgs& a) {
+  if (a.deferred_splits) *a.deferred_splits = 0;       // (only a split-K launch of the matrix-core kernels sets it)
   if (gemm_mfma_supported(a)) launch_gemm_mfma(s, a);
   else launch_gemm_naive(s, a);
 }

@@ -515,7 +515,8 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
     if (a.form == 1) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, false, true>), grid, block, 0, s, p);
     else hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, true, true>), grid, block, 0, s, p);
   }
-  if (splits > 1) {
+  if (a.deferred_splits) *a.deferred_splits = splits > 1 ? splits : 0;
+  if (splits > 1 && !a.deferred_splits) {
     const size_t quads = ((size_t)a.M * a.N + 3) / 4;
     hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, (const float*)a.splitk_ws, splits,
                        a.M, a.N, (T*)a.C, a.ldc, (const T*)a.bias, a.relu);

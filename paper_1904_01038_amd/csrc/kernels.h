@@ -47,6 +47,10 @@ struct GemmArgs {
   uint64_t drop_key = 0;
   float drop_p = 0.f;
   float mask_scale = 1.f;    // with mask: the kept elements are also multiplied by this (the dropout scale of the masked layer)
+  // Deferred split-K reduction (host pointer or null).  If given and the launch splits the contraction, the fp32 partial
+  // results [splits][M][N] stay in splitk_ws, nothing is written to C, bias is NOT applied, and *deferred_splits = splits:
+  // the caller's next kernel adds them up (see launch_splitk_layernorm_fwd).  Otherwise *deferred_splits = 0 and C is complete.
+  int* deferred_splits = nullptr;
 };
 void launch_gemm(hipStream_t s, const GemmArgs& a);
 bool gemm_mfma_supported(const GemmArgs& a);
@@ -96,6 +100,10 @@ void launch_attention_bwd_mfma(hipStream_t s, const AttnArgs& a);
 void launch_attention_fwd_naive(hipStream_t s, const AttnArgs& a);
 void launch_attention_bwd_naive(hipStream_t s, const AttnArgs& a);
 
+// The same as launch_residual_layernorm_fwd with y = bias + sum over `splits` fp32 slices partial[s][rows][d] (in that order)
+// and no dropout: the reduction of a split-K product fused with the residual connection and LayerNorm that follow it.
+void launch_splitk_layernorm_fwd(hipStream_t s, int dt, const void* x, const float* partial, int splits, const void* bias,
+                                 const void* gamma, const void* beta, void* s_out, void* n_out, int rows, int d);
 void launch_residual_layernorm_fwd(hipStream_t s, int dt, const void* x, const void* y, const void* gamma,
                                    const void* beta, void* s_out, void* n_out, float* mean, float* rstd, int rows,
                                    int d, uint64_t key, float p);
@@ -178,8 +186,14 @@ struct DecodeAttnArgs {
   const int* src_off;                    // cross-attention: [sentences + 1] row offsets into k / v
   int rows, H, dh, beam, t, max_steps;
   int n_max;                             // upper bound on the positions any row attends to (sizes the LDS buffers)
+  // Self-attention only, optional: the step's new keys and values [rows, ld_new] (head h at column h * dh), not yet in the
+  // caches.  The kernel then takes position t from here and stores it at position t of the row's own cache lines (k and v
+  // must be writable), which saves the separate append.  Honoured only where decode_attention_appends() says so.
+  const void *k_new = nullptr, *v_new = nullptr;
+  int ld_new = 0;
 };
 void launch_decode_attention(hipStream_t s, const DecodeAttnArgs& a);
+bool decode_attention_appends(const DecodeAttnArgs& a);   // would this launch append k_new / v_new to the caches itself?
 // per row: log-sum-exp and the k (<= 16) largest logits as log-probabilities, best first, ties by ascending id
 void launch_row_topk(hipStream_t s, int dt, const void* z, int ldz, int rows, int V, int k, float* top_logp, int* top_id,
                      float* lse);

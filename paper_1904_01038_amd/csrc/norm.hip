@@ -69,6 +69,96 @@ __global__ __launch_bounds__(256) void residual_layernorm_fwd_kernel(
   }
 }
 
+// s = x + (bias + sum of the fp32 slices); n = gamma * (s - mean) * rstd + beta.  One wavefront per row as above.
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void splitk_layernorm_fwd_kernel(
+    const T* __restrict__ x, const float* __restrict__ partial, int splits, const T* __restrict__ bias,
+    const T* __restrict__ gamma, const T* __restrict__ beta, T* __restrict__ s_out, T* __restrict__ n_out, int rows, int d) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const size_t base = (size_t)row * d, slice = (size_t)rows * d;
+  float v[NCH][LN_VEC];
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (lane + 64 * c) * LN_VEC;
+    if (col < d) {
+      load_f<T, LN_VEC>(x + base + col, v[c]);
+      // all slices' loads are issued together (at most 8 slices: the split-K launch's own limit), then added in order
+      float t[8][LN_VEC], y[LN_VEC];
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (k < splits) load_f<float, LN_VEC>(partial + k * slice + base + col, t[k]);
+#pragma unroll
+      for (int i = 0; i < LN_VEC; ++i) y[i] = t[0][i];
+#pragma unroll
+      for (int k = 1; k < 8; ++k)
+        if (k < splits) {
+#pragma unroll
+          for (int i = 0; i < LN_VEC; ++i) y[i] += t[k][i];
+        }
+      if (bias) {
+        float t[LN_VEC];
+        load_f<T, LN_VEC>(bias + col, t);
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i) y[i] += t[i];
+      }
+#pragma unroll
+      for (int i = 0; i < LN_VEC; ++i) v[c][i] += y[i];
+      if (s_out) {
+        store_f<T, LN_VEC>(s_out + base + col, v[c]);
+#pragma unroll
+        for (int i = 0; i < LN_VEC; ++i) v[c][i] = to_f<T>(from_f<T>(v[c][i]));     // normalise what was stored, as above
+      }
+#pragma unroll
+      for (int i = 0; i < LN_VEC; ++i) sum += v[c][i];
+    }
+  }
+  const float mu = wave_sum(sum) / (float)d;
+  float sq = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (lane + 64 * c) * LN_VEC;
+    if (col < d) {
+#pragma unroll
+      for (int i = 0; i < LN_VEC; ++i) { const float t = v[c][i] - mu; sq += t * t; }
+    }
+  }
+  const float rs = rsqrtf(wave_sum(sq) / (float)d + LN_EPS);
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (lane + 64 * c) * LN_VEC;
+    if (col < d) {
+      float g[LN_VEC], b[LN_VEC], o[LN_VEC];
+      load_f<T, LN_VEC>(gamma + col, g);
+      load_f<T, LN_VEC>(beta + col, b);
+#pragma unroll
+      for (int i = 0; i < LN_VEC; ++i) o[i] = g[i] * ((v[c][i] - mu) * rs) + b[i];
+      store_f<T, LN_VEC>(n_out + base + col, o);
+    }
+  }
+}
+
+template <typename T>
+static void splitk_ln_dispatch(hipStream_t s, const void* x, const float* partial, int splits, const void* bias, const void* gamma,
+                               const void* beta, void* s_out, void* n_out, int rows, int d) {
+  dim3 grid((rows + 3) / 4), block(256);
+  const int nch = (d + 511) / 512;
+#define SLN(N)                                                                                                             \
+  hipLaunchKernelGGL((splitk_layernorm_fwd_kernel<T, N>), grid, block, 0, s, (const T*)x, partial, splits, (const T*)bias, \
+                     (const T*)gamma, (const T*)beta, (T*)s_out, (T*)n_out, rows, d)
+  if (nch <= 1) SLN(1); else if (nch == 2) SLN(2); else if (nch == 3) SLN(3); else SLN(4);
+#undef SLN
+}
+void launch_splitk_layernorm_fwd(hipStream_t s, int dt, const void* x, const float* partial, int splits, const void* bias,
+                                 const void* gamma, const void* beta, void* s_out, void* n_out, int rows, int d) {
+  if (rows <= 0) return;
+  if (dt == F16) splitk_ln_dispatch<half_t>(s, x, partial, splits, bias, gamma, beta, s_out, n_out, rows, d);
+  else if (dt == BF16) splitk_ln_dispatch<bf16_t>(s, x, partial, splits, bias, gamma, beta, s_out, n_out, rows, d);
+  // (split-K launches exist for the 2-byte types only)
+}
+
 template <typename T>
 static void ln_fwd_dispatch(hipStream_t s, const void* x, const void* y, const void* gamma, const void* beta, void* s_out,
                             void* n_out, float* mean, float* rstd, int rows, int d, uint64_t key, float p) {

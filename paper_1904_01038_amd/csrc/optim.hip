@@ -137,19 +137,39 @@ static float* scan_static_address(hipError_t* err) {
 }
 
 // ---- conversion ---------------------------------------------------------------------------------------------------------
+// 8 elements per thread in one pass with non-temporal accesses (the whole-buffer conversions move hundreds of megabytes
+// that nothing reads again soon); the last n % 8 elements, and buffers that are not 16-byte aligned, go one by one.
+template <typename S, typename D>
+__global__ __launch_bounds__(256) void convert_vec_kernel(const S* __restrict__ src, D* __restrict__ dst, int64_t n8) {
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= n8) return;
+  float v[8];
+  load_f_nt<S, 8>(src + i, v);
+  store_f_nt<D, 8>(dst + i, v);
+}
 template <typename S, typename D>
 __global__ void convert_kernel(const S* __restrict__ src, D* __restrict__ dst, int64_t n) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = from_f<D>(to_f<S>(src[i]));
 }
+template <typename S, typename D>
+static void convert_typed(hipStream_t s, const S* src, D* dst, int64_t n) {
+  int64_t n8 = 0;
+  if ((((uintptr_t)src | (uintptr_t)dst) & 31) == 0) {
+    n8 = n / 8 * 8;
+    if (n8) hipLaunchKernelGGL((convert_vec_kernel<S, D>), dim3((unsigned)((n8 / 8 + 255) / 256)), dim3(256), 0, s, src, dst, n8);
+  }
+  if (n > n8) {
+    int64_t b = (n - n8 + 255) / 256;
+    if (b > 4096) b = 4096;
+    hipLaunchKernelGGL((convert_kernel<S, D>), dim3((unsigned)b), dim3(256), 0, s, src + n8, dst + n8, n - n8);
+  }
+}
 template <typename S>
 static void convert_from(hipStream_t s, const void* src, int dst_dt, void* dst, int64_t n) {
-  int64_t b = (n + 255) / 256;
-  if (b > 4096) b = 4096;
-  dim3 grid((unsigned)b), block(256);
-  if (dst_dt == F32) hipLaunchKernelGGL((convert_kernel<S, float>), grid, block, 0, s, (const S*)src, (float*)dst, n);
-  else if (dst_dt == F16) hipLaunchKernelGGL((convert_kernel<S, half_t>), grid, block, 0, s, (const S*)src, (half_t*)dst, n);
-  else hipLaunchKernelGGL((convert_kernel<S, bf16_t>), grid, block, 0, s, (const S*)src, (bf16_t*)dst, n);
+  if (dst_dt == F32) convert_typed<S, float>(s, (const S*)src, (float*)dst, n);
+  else if (dst_dt == F16) convert_typed<S, half_t>(s, (const S*)src, (half_t*)dst, n);
+  else convert_typed<S, bf16_t>(s, (const S*)src, (bf16_t*)dst, n);
 }
 void launch_convert(hipStream_t s, int src_dt, const void* src, int dst_dt, void* dst, int64_t n) {
   if (n <= 0) return;

@@ -521,10 +521,11 @@ inline void* gr(tfm_ctx* c, int i) { return (char*)c->g + c->params[i].off * c->
 
 void gemm(tfm_ctx* c, int form, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C, int ldc,
           const void* bias = nullptr, int relu = 0, const void* mask = nullptr, const void* residual = nullptr, bool side = false,
-          uint64_t drop_key = 0, float drop_p = 0.f, float mask_scale = 1.f) {
+          uint64_t drop_key = 0, float drop_p = 0.f, float mask_scale = 1.f, int* deferred_splits = nullptr) {
+  if (deferred_splits) *deferred_splits = 0;
   if (M <= 0 || N <= 0) return;
   GemmArgs a{c->dt, form, M, N, K, A, lda, B, ldb, C, ldc, bias, relu, mask, residual};
-  a.drop_key = drop_key; a.drop_p = drop_p; a.mask_scale = mask_scale;
+  a.drop_key = drop_key; a.drop_p = drop_p; a.mask_scale = mask_scale; a.deferred_splits = deferred_splits;
   side = side && c->overlap;
   hipStream_t stream = side ? c->side : c->stream;
   a.splitk_ws = side ? c->splitk_ws_side : c->splitk_ws;
@@ -1526,46 +1527,68 @@ int decoder_check(const tfm_ctx* c, int max_rows, int max_steps, int max_src, in
   return TFM_OK;
 }
 
-void decode_ln(tfm_decoder* D, const void* x, const void* y, int g, int b, void* s_out, void* n_out) {
+// bias_param: the bias the deferred slices still lack (used only with splits > 0)
+void decode_ln(tfm_decoder* D, const void* x, const void* y, int g, int b, void* s_out, void* n_out, int splits = 0, int bias_param = -1) {
   tfm_ctx* c = D->c;
   const int d = c->cfg.d_model;
+  if (splits > 0) {
+    run(c, TFM_PROF_NORM, 0.0, (double)D->rows * d * (4.0 * splits + c->esz * (2.0 + (s_out ? 1.0 : 0.0))), [&] {
+      launch_splitk_layernorm_fwd(c->stream, c->dt, x, (const float*)c->splitk_ws, splits, bias_param >= 0 ? wh(c, bias_param) : nullptr,
+                                  wh(c, g), wh(c, b), s_out, n_out, D->rows, d);
+    });
+    return;
+  }
   run(c, TFM_PROF_NORM, 0.0, (double)c->esz * D->rows * d * (2.0 + (y ? 1.0 : 0.0) + (s_out ? 1.0 : 0.0)), [&] {
     launch_residual_layernorm_fwd(c->stream, c->dt, x, y, wh(c, g), wh(c, b), s_out, n_out, D->mean, D->rstd, D->rows, d, 0, 0.f);
   });
 }
 
+// qkv_new (self-attention): the step's fused [rows, 3d] projection, whose keys and values are to be appended to the caches k
+// and v at position t: by the attention kernel itself where it can, else by a copy kernel first
 void decode_attention(tfm_decoder* D, const void* q, int ldq, const void* k, const void* v, int row_stride, const int* anc, int n_max,
-                      double positions) {
+                      double positions, const void* qkv_new = nullptr) {
   tfm_ctx* c = D->c;
   const int d = c->cfg.d_model, H = c->cfg.n_heads;
   DecodeAttnArgs a{};
   a.dt = c->dt; a.q = q; a.ldq = ldq; a.k = k; a.v = v; a.row_stride = row_stride; a.o = D->att; a.ldo = d;
   a.anc = anc; a.src_off = D->src_off; a.rows = D->rows; a.H = H; a.dh = d / H; a.beam = D->beam; a.t = D->t;
   a.max_steps = D->max_steps; a.n_max = n_max;
+  if (qkv_new) {
+    a.k_new = (const char*)qkv_new + (size_t)d * c->esz; a.v_new = (const char*)qkv_new + (size_t)2 * d * c->esz; a.ld_new = 3 * d;
+    if (!decode_attention_appends(a)) {
+      run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * D->rows * d * 4.0, [&] {
+        launch_cache_append(c->stream, c->dt, qkv_new, const_cast<void*>(k), const_cast<void*>(v), D->rows, d, D->max_steps, D->t);
+      });
+      a.k_new = a.v_new = nullptr;
+    }
+  }
   // positions = sum over rows of the positions attended to: K and V rows read once each, q read, output written
   run(c, TFM_PROF_ATTENTION, 4.0 * d * positions, (double)c->esz * d * (2.0 * positions + 2.0 * D->rows),
       [&] { launch_decode_attention(c->stream, a); });
 }
 
 // y = f_k(fin) for the single new position of every row
-void decode_sublayer(tfm_decoder* D, const Block& b, int layer, const void* fin, double src_positions) {
+// y = f_k(fin) for the step's rows.  The sub-layer's last product has few tiles and usually runs split along K: its fp32
+// slices are then left in the split-K workspace, without the bias, and their count is returned for the kernel that fuses
+// their sum with the residual connection and LayerNorm (0: D->y is complete).
+int decode_sublayer(tfm_decoder* D, const Block& b, int layer, const void* fin, double src_positions) {
   tfm_ctx* c = D->c;
   const int d = c->cfg.d_model, F = c->cfg.d_ffn, R = D->rows;
+  int deferred = 0;
   if (b.kind == SELF) {
     gemm(c, 0, R, 3 * d, d, fin, d, wh(c, b.w_a), d, D->qkv, 3 * d, wh(c, b.b_a));
-    run(c, TFM_PROF_EMBED, 0.0, (double)c->esz * R * d * 4.0,
-        [&] { launch_cache_append(c->stream, c->dt, D->qkv, D->Kc[layer], D->Vc[layer], R, d, D->max_steps, D->t); });
-    decode_attention(D, D->qkv, 3 * d, D->Kc[layer], D->Vc[layer], d, D->anc[D->cur], D->t + 1, (double)R * (D->t + 1));
-    gemm(c, 0, R, d, d, D->att, d, wh(c, b.w_o), d, D->y, d, wh(c, b.b_o));
+    decode_attention(D, D->qkv, 3 * d, D->Kc[layer], D->Vc[layer], d, D->anc[D->cur], D->t + 1, (double)R * (D->t + 1), D->qkv);
+    gemm(c, 0, R, d, d, D->att, d, wh(c, b.w_o), d, D->y, d, wh(c, b.b_o), 0, nullptr, nullptr, false, 0, 0.f, 1.f, &deferred);
   } else if (b.kind == CROSS) {
     gemm(c, 0, R, d, d, fin, d, wh(c, b.w_a), d, D->q, d, wh(c, b.b_a));
     const char* kv = (const char*)D->xkv[layer];
     decode_attention(D, D->q, d, kv, kv + d * c->esz, 2 * d, nullptr, D->n_src_max, src_positions);
-    gemm(c, 0, R, d, d, D->att, d, wh(c, b.w_o), d, D->y, d, wh(c, b.b_o));
+    gemm(c, 0, R, d, d, D->att, d, wh(c, b.w_o), d, D->y, d, wh(c, b.b_o), 0, nullptr, nullptr, false, 0, 0.f, 1.f, &deferred);
   } else {
     gemm(c, 0, R, F, d, fin, d, wh(c, b.w_a), d, D->inter, F, wh(c, b.b_a), 1);
-    gemm(c, 0, R, d, F, D->inter, F, wh(c, b.w_o), F, D->y, d, wh(c, b.b_o));
+    gemm(c, 0, R, d, F, D->inter, F, wh(c, b.w_o), F, D->y, d, wh(c, b.b_o), 0, nullptr, nullptr, false, 0, 0.f, 1.f, &deferred);
   }
+  return deferred;
 }
 
 }  // namespace
@@ -1726,12 +1749,12 @@ int tfm_decoder_step(tfm_decoder* D, const int32_t* prev, const int32_t* parent,
   if (cf.enc_layers) src_positions = (double)D->src_rows * D->beam;
   for (int k = 0; k < K; ++k) {
     const int i = k & 1, j = i ^ 1;
-    decode_sublayer(D, blocks[k], blocks[k].layer, D->norm[i], src_positions);
+    const int splits = decode_sublayer(D, blocks[k], blocks[k].layer, D->norm[i], src_positions);
     if (pre) {
       const int g = k + 1 < K ? blocks[k + 1].ln_g : c->dec.lnf_g, b = k + 1 < K ? blocks[k + 1].ln_b : c->dec.lnf_b;
-      decode_ln(D, D->resid[i], D->y, g, b, D->resid[j], D->norm[j]);
+      decode_ln(D, D->resid[i], D->y, g, b, D->resid[j], D->norm[j], splits, blocks[k].b_o);
     } else {
-      decode_ln(D, D->norm[i], D->y, blocks[k].ln_g, blocks[k].ln_b, nullptr, D->norm[j]);
+      decode_ln(D, D->norm[i], D->y, blocks[k].ln_g, blocks[k].ln_b, nullptr, D->norm[j], splits, blocks[k].b_o);
     }
   }
   const void* top = D->norm[K & 1];
