@@ -121,8 +121,20 @@ __global__ __launch_bounds__(64) void decode_attention64_kernel(DecodeAttnArgs p
   float* sc = smem;
   int* rowi = reinterpret_cast<int*>(smem + p.n_max);
   float* qs = smem + 2 * p.n_max;
-  const T* q = reinterpret_cast<const T*>(p.q) + (size_t)r * p.ldq + h * dh;
-  qs[lane] = to_f<T>(q[lane]);
+  if (p.q_partial) {                                   // the query arrives as the slices of a split-K product (at most 8)
+    const size_t at = (size_t)r * p.H * dh + h * dh + lane, slice = (size_t)p.rows * p.H * dh;
+    float part[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) part[k] = k < p.q_splits ? p.q_partial[k * slice + at] : 0.f;
+    float qv = part[0];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) qv += part[k];
+    if (p.q_bias) qv += to_f<T>(reinterpret_cast<const T*>(p.q_bias)[h * dh + lane]);
+    qs[lane] = to_f<T>(from_f<T>(qv));                 // rounded as the stored projection would be
+  } else {
+    const T* q = reinterpret_cast<const T*>(p.q) + (size_t)r * p.ldq + h * dh;
+    qs[lane] = to_f<T>(q[lane]);
+  }
   const T* K = reinterpret_cast<const T*>(p.k);
   const T* V = reinterpret_cast<const T*>(p.v);
   // position t of a self-attention step may still be outside the caches: it is read from the new rows, and 16 lanes copy
@@ -207,11 +219,13 @@ void launch_decode_attention(hipStream_t s, const DecodeAttnArgs& a) {
   if (a.rows <= 0) return;
   dim3 grid(a.rows, a.H), block(64);
   const size_t smem = (size_t)(2 * a.n_max + a.dh) * sizeof(float);
-  if (decode_attention_fast(a)) {
+  if (decode_attention_fast(a) && a.q_splits <= 8) {
     if (a.dt == F16) hipLaunchKernelGGL((decode_attention64_kernel<half_t>), grid, block, smem, s, a);
     else hipLaunchKernelGGL((decode_attention64_kernel<bf16_t>), grid, block, smem, s, a);
     return;
   }
+  if (a.q_partial)                                     // the general kernel reads a finished query: finish it into q first
+    launch_splitk_reduce(s, a.dt, a.q_partial, a.q_splits, a.rows, a.H * a.dh, const_cast<void*>(a.q), a.ldq, a.q_bias);
   const bool vec = a.dh % 8 == 0;
 #define DA(T, VEC) hipLaunchKernelGGL((decode_attention_kernel<T, VEC>), grid, block, smem, s, a)
   if (a.dt == F32) { if (vec) DA(float, 8); else DA(float, 1); }

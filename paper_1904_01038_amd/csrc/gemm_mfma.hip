@@ -455,6 +455,13 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   store_f<T, 4>(C + (size_t)m * ldc + n, v);
 }
 
+void launch_splitk_reduce(hipStream_t s, int dt, const float* partial, int splits, int M, int N, void* C, int ldc, const void* bias) {
+  const size_t quads = ((size_t)M * N + 3) / 4;
+  dim3 grid((unsigned)((quads + 255) / 256)), block(256);
+  if (dt == F16) hipLaunchKernelGGL((splitk_reduce_kernel<half_t>), grid, block, 0, s, partial, splits, M, N, (half_t*)C, ldc, (const half_t*)bias, 0);
+  else if (dt == BF16) hipLaunchKernelGGL((splitk_reduce_kernel<bf16_t>), grid, block, 0, s, partial, splits, M, N, (bf16_t*)C, ldc, (const bf16_t*)bias, 0);
+}
+
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 // bytes spanned by a [rows, width] view with row stride ld (elements of 2 bytes)

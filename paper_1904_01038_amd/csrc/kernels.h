@@ -56,6 +56,9 @@ void launch_gemm(hipStream_t s, const GemmArgs& a);
 bool gemm_mfma_supported(const GemmArgs& a);
 void launch_gemm_naive(hipStream_t s, const GemmArgs& a);
 void launch_gemm_mfma(hipStream_t s, const GemmArgs& a);      // requires gemm_mfma_supported(a)
+// C[m, n] = bias[n] + sum over s of partial[s][m][n] (fixed order): the second half of a split-K product whose reduction was
+// deferred (2-byte types only)
+void launch_splitk_reduce(hipStream_t s, int dt, const float* partial, int splits, int M, int N, void* C, int ldc, const void* bias);
 
 // Grouped weight gradients (half precision): one launch computes C_i[M_i, N_i] = A_i^T B_i over K_i rows for every job and,
 // where colsum is set, colsum_i[M_i] = the column sums of A_i (the bias gradient that goes with the weight gradient).
@@ -191,6 +194,12 @@ struct DecodeAttnArgs {
   // must be writable), which saves the separate append.  Honoured only where decode_attention_appends() says so.
   const void *k_new = nullptr, *v_new = nullptr;
   int ld_new = 0;
+  // Optional: the query projection left as q_splits fp32 slices [q_splits][rows][H * dh] of a split-K product, without its bias
+  // (q_bias [H * dh] or null).  The kernel adds them up while it loads the query; q must then be a writable [rows, ldq] buffer,
+  // which receives the sum only where the kernel cannot do that (see launch_decode_attention).
+  const float* q_partial = nullptr;
+  int q_splits = 0;
+  const void* q_bias = nullptr;
 };
 void launch_decode_attention(hipStream_t s, const DecodeAttnArgs& a);
 bool decode_attention_appends(const DecodeAttnArgs& a);   // would this launch append k_new / v_new to the caches itself?

@@ -1546,13 +1546,14 @@ void decode_ln(tfm_decoder* D, const void* x, const void* y, int g, int b, void*
 // qkv_new (self-attention): the step's fused [rows, 3d] projection, whose keys and values are to be appended to the caches k
 // and v at position t: by the attention kernel itself where it can, else by a copy kernel first
 void decode_attention(tfm_decoder* D, const void* q, int ldq, const void* k, const void* v, int row_stride, const int* anc, int n_max,
-                      double positions, const void* qkv_new = nullptr) {
+                      double positions, const void* qkv_new = nullptr, int q_splits = 0, const void* q_bias = nullptr) {
   tfm_ctx* c = D->c;
   const int d = c->cfg.d_model, H = c->cfg.n_heads;
   DecodeAttnArgs a{};
   a.dt = c->dt; a.q = q; a.ldq = ldq; a.k = k; a.v = v; a.row_stride = row_stride; a.o = D->att; a.ldo = d;
   a.anc = anc; a.src_off = D->src_off; a.rows = D->rows; a.H = H; a.dh = d / H; a.beam = D->beam; a.t = D->t;
   a.max_steps = D->max_steps; a.n_max = n_max;
+  if (q_splits > 0) { a.q_partial = (const float*)c->splitk_ws; a.q_splits = q_splits; a.q_bias = q_bias; }
   if (qkv_new) {
     a.k_new = (const char*)qkv_new + (size_t)d * c->esz; a.v_new = (const char*)qkv_new + (size_t)2 * d * c->esz; a.ld_new = 3 * d;
     if (!decode_attention_appends(a)) {
@@ -1580,9 +1581,11 @@ int decode_sublayer(tfm_decoder* D, const Block& b, int layer, const void* fin, 
     decode_attention(D, D->qkv, 3 * d, D->Kc[layer], D->Vc[layer], d, D->anc[D->cur], D->t + 1, (double)R * (D->t + 1), D->qkv);
     gemm(c, 0, R, d, d, D->att, d, wh(c, b.w_o), d, D->y, d, wh(c, b.b_o), 0, nullptr, nullptr, false, 0, 0.f, 1.f, &deferred);
   } else if (b.kind == CROSS) {
-    gemm(c, 0, R, d, d, fin, d, wh(c, b.w_a), d, D->q, d, wh(c, b.b_a));
+    // (the query projection has as few tiles as the output projection: its slices are summed by the attention kernel)
+    int q_splits = 0;
+    gemm(c, 0, R, d, d, fin, d, wh(c, b.w_a), d, D->q, d, wh(c, b.b_a), 0, nullptr, nullptr, false, 0, 0.f, 1.f, &q_splits);
     const char* kv = (const char*)D->xkv[layer];
-    decode_attention(D, D->q, d, kv, kv + d * c->esz, 2 * d, nullptr, D->n_src_max, src_positions);
+    decode_attention(D, D->q, d, kv, kv + d * c->esz, 2 * d, nullptr, D->n_src_max, src_positions, nullptr, q_splits, wh(c, b.b_a));
     gemm(c, 0, R, d, d, D->att, d, wh(c, b.w_o), d, D->y, d, wh(c, b.b_o), 0, nullptr, nullptr, false, 0, 0.f, 1.f, &deferred);
   } else {
     gemm(c, 0, R, F, d, fin, d, wh(c, b.w_a), d, D->inter, F, wh(c, b.b_a), 1);
