@@ -1,6 +1,6 @@
 """Benchmark of the training step on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload big|base|lm16|big_accum|tiny]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload big|base|lm16|big_accum|tiny|decode|gemm_shapes]
 
 A "step" is one update window of the named workload: k sub-batches through tfm_train_step (forward, scaled loss,
 backward, inf/nan scan) followed by tfm_apply_update (scaler + fp32 Adam).  Prints ONE JSON line:
@@ -162,12 +162,60 @@ def run_decode(args):
     print(json.dumps(out))
 
 
+def run_gemm_shapes(args):
+    """Context for the GEMM figures, not a step: every projection shape of the big Transformer at 3264 rows through
+    tfm_op_gemm, stand-alone and cache-warm, beside the vendor library (torch.matmul) on the same operands."""
+    import torch
+    import paper_1904_01038_amd as T
+    torch.cuda.set_device(0)
+    rows, d, F, V, L = 3264, 1024, 4096, 32768, 6
+    shapes = [  # form (0: X W^T, 1: dY W, 2: dY^T X), M, N, K, label
+        (0, rows, 3 * d, d, "qkv fwd"), (0, rows, d, d, "out fwd"), (0, rows, F, d, "ffn1 fwd"), (0, rows, d, F, "ffn2 fwd"),
+        (0, rows, L * 2 * d, d, "cross k/v of all layers fwd"), (0, rows, V, d, "vocabulary fwd"),
+        (1, rows, d, 3 * d, "qkv dgrad"), (1, rows, d, d, "out dgrad"), (1, rows, F, d, "ffn2 dgrad"), (1, rows, d, F, "ffn1 dgrad"),
+        (1, rows, d, L * 2 * d, "cross k/v of all layers dgrad"), (1, rows, d, V, "vocabulary dgrad"),
+        (2, 3 * d, d, rows, "qkv wgrad"), (2, d, d, rows, "out wgrad"), (2, F, d, rows, "ffn1 wgrad"), (2, d, F, rows, "ffn2 wgrad"),
+        (2, V, d, rows, "vocabulary wgrad"),
+    ]
+    dt = torch.float16
+    torch.manual_seed(0)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(f, n):
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(n):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    table = []
+    for form, M, N, K, label in shapes:
+        A = torch.randn((K, M) if form == 2 else (M, K), device="cuda", dtype=dt)
+        B = torch.randn((N, K) if form == 0 else (K, N), device="cuda", dtype=dt)
+        C = torch.empty(M, N, device="cuda", dtype=dt)
+        ours = timed(lambda: T.ops.gemm(form, A, B, C, M, N, K), args.steps)
+        lib = timed((lambda: torch.matmul(A, B.t())) if form == 0 else (lambda: torch.matmul(A, B)) if form == 1
+                    else (lambda: torch.matmul(A.t(), B)), args.steps)
+        fl = 2.0 * M * N * K
+        table.append({"shape": label, "form": form, "M": M, "N": N, "K": K, "us": ours * 1e3, "tflops": fl / ours / 1e9,
+                      "library_us": lib * 1e3, "library_tflops": fl / lib / 1e9})
+    tot = sum(r["us"] for r in table)
+    print(json.dumps({"metric": "stand-alone GEMM rate per projection shape (context, not a training step)",
+                      "value": sum(2.0 * r["M"] * r["N"] * r["K"] for r in table) / (tot * 1e-6) / 1e12, "unit": "TFLOP/s",
+                      "n_gpus": 1, "steps": args.steps, "warmup": 3, "higher_is_better": True, "dtype": "fp16", "data": "synthetic",
+                      "config": {"workload": "gemm_shapes", "rows": rows}, "shapes": table}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=12)
-    ap.add_argument("--workload", default="big", choices=list(WORKLOAD_RUN) + ["decode"])
+    ap.add_argument("--workload", default="big", choices=list(WORKLOAD_RUN) + ["decode", "gemm_shapes"])
     ap.add_argument("--decode-max-tokens", type=int, default=3584, help="padded source tokens per decoding batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1100)
@@ -187,6 +235,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.workload == "decode":
         return run_decode(args)
+    if args.workload == "gemm_shapes":
+        return run_gemm_shapes(args)
     torch.cuda.set_device(0)
     w = WORKLOADS[args.workload]
     shape = PRESETS[w["model"]]
