@@ -364,10 +364,117 @@ __global__ __launch_bounds__(NT) void row_topk_cached_kernel(const T* __restrict
   }
 }
 
+// The same result again, for rows of whole 8-element vectors: 16-byte loads, and the k rounds run inside each wavefront (lane
+// exchanges only, no block barrier); the wavefronts' k candidates each meet in LDS once and one wavefront merges them.
+template <typename T, int NV, int NT>
+__global__ __launch_bounds__(NT) void row_topk_vec_kernel(const T* __restrict__ z, int ldz, int V, float* __restrict__ top_logp,
+                                                           int* __restrict__ top_id, float* __restrict__ lse_out, int k_out) {
+  constexpr int NWV = NT / 64;
+  __shared__ float sh[16];
+  __shared__ float cand_v[NWV * 16];
+  __shared__ int cand_i[NWV * 16];
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const T* zr = z + (size_t)row * ldz;
+  float c[NV][8];
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int col = (tid + i * NT) * 8;
+    if (col < V) load_f<T, 8>(zr + col, c[i]);
+    else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) c[i][j] = -INFINITY;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) m = fmaxf(m, c[i][j]);
+  }
+  const float gm = block_max(m, sh);
+  float se = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) se += __expf(c[i][j] - gm);              // exp(-inf) = 0 for the padding
+  const float lse = gm + logf(block_sum(se, sh));
+  if (tid == 0 && lse_out) lse_out[row] = lse;
+  // this thread's best remaining (value, id): ids ascend with (i, j), so the first maximum has the smallest id
+  float bv;
+  int bi;
+  auto rescan = [&]() {
+    bv = -INFINITY; bi = 0x7fffffff;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (c[i][j] > bv) { bv = c[i][j]; bi = (tid + i * NT) * 8 + j; }
+  };
+  rescan();
+  for (int round = 0; round < k_out; ++round) {                          // this wavefront's k best, best first
+    float v = bv;
+    int id = bi;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(v, o);
+      const int oi = __shfl_xor(id, o);
+      if (better(ov, oi, v, id)) { v = ov; id = oi; }
+    }
+    if (lane == 0) { cand_v[wave * 16 + round] = v; cand_i[wave * 16 + round] = id; }
+    if (id == bi && id != 0x7fffffff) {                                  // the owner drops it and looks again
+#pragma unroll
+      for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if ((tid + i * NT) * 8 + j == id) c[i][j] = -INFINITY;
+      rescan();
+    }
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  // merge: NWV * k_out <= 256 candidates, up to four per lane; a wavefront's list is sorted, but nothing relies on that here
+  const int total = NWV * k_out;
+  float mv[4];
+  int mi[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int idx = lane + 64 * q;
+    const bool ok = idx < total;
+    const int w = ok ? idx / k_out : 0, r = ok ? idx - w * k_out : 0;
+    mv[q] = ok ? cand_v[w * 16 + r] : -INFINITY;
+    mi[q] = ok ? cand_i[w * 16 + r] : 0x7fffffff;
+  }
+  for (int round = 0; round < k_out; ++round) {
+    float v = mv[0];
+    int id = mi[0];
+#pragma unroll
+    for (int q = 1; q < 4; ++q)
+      if (better(mv[q], mi[q], v, id)) { v = mv[q]; id = mi[q]; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(v, o);
+      const int oi = __shfl_xor(id, o);
+      if (better(ov, oi, v, id)) { v = ov; id = oi; }
+    }
+    if (lane == 0) {
+      top_logp[(size_t)row * k_out + round] = v - lse;
+      top_id[(size_t)row * k_out + round] = id;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (mi[q] == id && id != 0x7fffffff) { mv[q] = -INFINITY; mi[q] = 0x7fffffff; }
+  }
+}
+
 void launch_row_topk(hipStream_t s, int dt, const void* z, int ldz, int rows, int V, int k, float* top_logp, int* top_id,
                      float* lse) {
   if (rows <= 0) return;
   dim3 grid(rows), block(256);
+  if (V % 8 == 0 && ldz % 8 == 0 && ((uintptr_t)z & 15) == 0 && V <= 1024 * 4 * 8 && k <= 16) {
+#define TKV(T, NV, NT) hipLaunchKernelGGL((row_topk_vec_kernel<T, NV, NT>), grid, dim3(NT), 0, s, (const T*)z, ldz, V, top_logp, top_id, lse, k)
+#define TKVV(T) do { if (V <= 256 * 2 * 8) TKV(T, 2, 256); else TKV(T, 4, 1024); } while (0)
+    if (dt == F32) TKVV(float); else if (dt == F16) TKVV(half_t); else TKVV(bf16_t);
+#undef TKVV
+#undef TKV
+    return;
+  }
 #define TKC(T, NCH, NT) hipLaunchKernelGGL((row_topk_cached_kernel<T, NCH, NT>), grid, dim3(NT), 0, s, (const T*)z, ldz, V, top_logp, top_id, lse, k)
 #define TK(T, K) hipLaunchKernelGGL((row_topk_kernel<T, K>), grid, block, 0, s, (const T*)z, ldz, V, top_logp, top_id, lse, k)
 #define TKK(T)                                                         \

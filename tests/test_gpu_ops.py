@@ -315,19 +315,27 @@ def test_attention_forward_backward(prec, dh, case, p_drop, packed):
 
 @pytest.mark.parametrize("gprec", ["fp32", "fp16", "bf16"])
 @pytest.mark.parametrize("wd", [0.0, 0.05])
-def test_adam_kernel_against_the_library_optimiser(gprec, wd):
+@pytest.mark.parametrize("n", [8, 4096, 13288])          # less than one lane group, exactly one block, a ragged last block
+def test_adam_kernel_against_the_library_optimiser(gprec, wd, n):
     """Three steps of the Adam kernel (gradient in fp32/fp16/bf16, unscaled by grad_mult, optional L2 weight decay) against
-    torch.optim.Adam on the CPU in float64 fed with the same (rounded) gradients; the half copy equals the rounded master."""
+    torch.optim.Adam on the CPU in float64 fed with the same (rounded) gradients; the half copy equals the rounded master;
+    nothing beyond the n elements is touched."""
     import torch
     import paper_1904_01038_amd as T
-    n, lr, b1, b2, eps, mult = 4096, 3e-3, 0.9, 0.98, 1e-8, 1.0 / 64.0
+    lr, b1, b2, eps, mult = 3e-3, 0.9, 0.98, 1e-8, 1.0 / 64.0
     rng = np.random.default_rng(5)
     w0 = rng.normal(size=n)
     gdt = _dtypes()[gprec]
-    w = torch.tensor(w0, dtype=torch.float32).cuda()
-    m = torch.zeros(n, dtype=torch.float32, device="cuda")
-    v = torch.zeros(n, dtype=torch.float32, device="cuda")
-    half = torch.zeros(n, dtype=torch.float16, device="cuda")
+    pad = 4096                                               # guard elements behind every buffer
+    wbuf = torch.full((n + pad,), 7.0, dtype=torch.float32, device="cuda")
+    mbuf = torch.full((n + pad,), 7.0, dtype=torch.float32, device="cuda")
+    vbuf = torch.full((n + pad,), 7.0, dtype=torch.float32, device="cuda")
+    hbuf = torch.full((n + pad,), 7.0, dtype=torch.float16, device="cuda")
+    w, m, v, half = wbuf[:n], mbuf[:n], vbuf[:n], hbuf[:n]
+    w.copy_(torch.tensor(w0, dtype=torch.float32))
+    m.zero_()
+    v.zero_()
+    half.zero_()
     ref = torch.tensor(w.cpu().numpy().astype(np.float64), requires_grad=True)
     opt = torch.optim.Adam([ref], lr=lr, betas=(b1, b2), eps=eps, weight_decay=wd)
     for t in range(1, 4):
@@ -338,3 +346,5 @@ def test_adam_kernel_against_the_library_optimiser(gprec, wd):
         got = w.double().cpu().numpy()
         assert np.abs(got - ref.detach().numpy()).max() <= 2e-6 * t, (t, np.abs(got - ref.detach().numpy()).max())
         assert torch.equal(half, w.half())
+    for buf in (wbuf, mbuf, vbuf, hbuf):
+        assert bool((buf[n:] == 7.0).all())
