@@ -518,9 +518,10 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   p.partial = splits > 1 ? (float*)a.splitk_ws : nullptr;
   dim3 grid(p.tiles_total, splits), block(64 * WM * WN);
   if (a.form == 0) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, false, false>), grid, block, 0, s, p);
-  else if constexpr (BM >= 128 && BN >= 128) {           // the [k][row] swizzle spans 16 vectors = 128 rows
+  else if constexpr (BN >= 128) {                        // the [k][row] swizzle spans 16 vectors = 128 rows: B of dY W ...
     if (a.form == 1) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, false, true>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, true, true>), grid, block, 0, s, p);
+    else if constexpr (BM >= 128)                        // ... and A as well for A^T B
+      hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, BK, STAGES, true, true>), grid, block, 0, s, p);
   }
   if (a.deferred_splits) *a.deferred_splits = splits > 1 ? splits : 0;
   if (splits > 1 && !a.deferred_splits) {
@@ -589,11 +590,15 @@ void launch_wgrad_grouped(hipStream_t s, int dt, const WgradJob* jobs, int n) {
 //                                                   output of ~3200 rows has 156 tiles of 256x256 but 204 of 192x256 for
 //                                                   256 CUs: 31.5 -> 28.0 us; 3000 rows: 37.6 -> 27.3 us)
 //   20   64x64       4         64     4      2      fewer than 128 tiles of 128x128 (a decoding step's few rows)
+//   22   64x128      8         64     4      1      X W^T and dY W with many rows but a narrow output and K >= 1024 (the 512-wide
+//                                                   products of the base model: 116 tiles of 128x128 become 232; 15.8 -> 13.3 us
+//                                                   at K = 2048, 14.1 -> 11.7 us at K = 1536; slower than the others at K = 512)
 // A launch costs about rounds x (fixed + slope x K-steps), rounds = tiles over the 256 compute units rounded up (the last,
 // partly filled round takes as long as a full one); fixed / slope in us per round and 64-wide K-step, measured with
 // M = 3264: 11 / 1.45 for 256x256, 9.5 / 1.16 for 192x256, 4.4 / 0.48 for 128x128.
 static int choose_tile(const GemmArgs& a) {
   const long t1 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
+  if (a.form != 2 && a.M >= 1024 && a.K >= 1024 && t1 <= 160) return 22;
   if (t1 < 128 && a.form == 0) return 20;               // few rows (a decoding step, X W^T): smaller tiles reach more CUs
   const long t3 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
   const long t4 = (long)((a.M + 191) / 192) * ((a.N + 255) / 256);
@@ -613,6 +618,7 @@ static void gemm_mfma_dispatch(hipStream_t s, const GemmArgs& a) {
     case 13: gemm_mfma_launch<T, 256, 256, 2, 4, 64, 2>(s, a); break;
     case 12: gemm_mfma_launch<T, 128, 128, 4, 4, 64, 4>(s, a); break;
     case 14: gemm_mfma_launch<T, 192, 256, 2, 4, 64, 2>(s, a); break;   // (never chosen for A^T B: its A tile would be [k][192])
+    case 22: gemm_mfma_launch<T, 64, 128, 2, 4, 64, 4>(s, a); break;    // (nor this one: [k][64])
     case 20:                                            // (the [k][row] swizzle spans 16 vectors: NT form only)
       if (a.form == 0) gemm_mfma_launch<T, 64, 64, 2, 2, 64, 4>(s, a);
       else gemm_mfma_launch<T, 128, 128, 2, 2, 32, 3>(s, a);

@@ -20,6 +20,8 @@ GEMM_SHAPES = [  # M, N, K: several tiles plus ragged tails in every dimension
     # large outputs with short contractions: the 192x256 tiling (221 tiles, ragged in both directions) and the 256x256 tiling
     # (221 tiles where 192x256 would need a second round)
     (3200, 3080, 72), (3264, 4104, 40),
+    # many rows, a narrow output, a long contraction: the 64x128 tiling (ragged in every direction)
+    (1100, 520, 1032),
 ]
 
 
