@@ -113,6 +113,7 @@ template <int ROWS, int BK, int NW, bool TR>
 struct Operand {
   static constexpr int TILE_BYTES = ROWS * BK * 2;
   static constexpr int LOADS = TILE_BYTES / 1024 / NW;   // direct-to-LDS loads per wavefront per stage
+  static_assert(LOADS >= 1 && LOADS * 1024 * NW == TILE_BYTES, "every wavefront loads a whole number of 1 KB pieces of the tile");
   static constexpr int ROW_BYTES = ROWS * 2;             // [k][row] layout only
   static constexpr int KROW_BYTES = BK * 2;              // [row][k] layout only: 64 or 128
   static constexpr int VPR = BK / 8;                     // 16-byte vectors per [row][k] row: 4 or 8
