@@ -509,7 +509,8 @@ static void gemm_mfma_launch(hipStream_t s, const GemmArgs& a) {
   if (a.form == 2 && a.splitk_ws && !a.bias && !a.relu && !a.mask && !a.residual && !p.drop_thr && p.tiles_total <= 128 && nk >= 32) {
     splits = 256 / p.tiles_total;
     if (splits > 8) splits = 8;
-  } else if (a.form == 0 && BM == 64 && a.splitk_ws && !a.mask && !a.residual && !p.drop_thr && p.tiles_total <= 128 && nk >= 8) {
+  } else if (a.form == 0 && BM == 64 && BN == 64 && a.splitk_ws && !a.mask && !a.residual && !p.drop_thr && p.tiles_total <= 128 && nk >= 8 &&
+             !(a.deferred_splits && a.relu)) {                // (a deferred reduction has no ReLU)
     // X W^T with few rows (a decoding step): the weights stream through more CUs; every slice keeps >= 4 K-steps and
     // bias / ReLU move into the reduction
     splits = std::min(std::min(256 / p.tiles_total, nk / 4), 8);
