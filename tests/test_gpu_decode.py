@@ -13,6 +13,11 @@ SHAPES = {
     "pre": ModelShape(1, 2, 32, 4, 48, 80, pre_norm=1),
     "lm": ModelShape(0, 2, 32, 2, 64, 96, pre_norm=1),
     "half": ModelShape(2, 2, 128, 2, 256, 512),         # head width 64: the MFMA GEMMs serve rows that are a multiple of 8
+    # contractions long enough for the few-row products to be split along K: the slices of a sub-layer's last product are summed
+    # by the LayerNorm kernel, those of the cross-attention query projection by the attention kernel (head width 64) or, where
+    # the general attention kernel runs (head width 32), by a reduction in front of it
+    "wide": ModelShape(1, 1, 512, 8, 1024, 96),
+    "wide_dh32": ModelShape(1, 1, 512, 16, 1024, 96),
     # adaptive inputs + adaptive softmax: clusters of 24 / 32 / 40 tokens (generic kernels) and of 126 (+2 entries) / 128 / 256
     # tokens, every table a multiple of 8 rows (matrix-core GEMMs)
     "adaptive": ModelShape(0, 2, 32, 2, 64, 96, pre_norm=1, cutoffs=(24, 56), factor=2),
@@ -65,6 +70,7 @@ def check_step(lp_gpu, top_lp, top_id, lp_ref, tol):
 
 @pytest.mark.parametrize("name,prec,tol", [("post", "fp32", 2e-4), ("pre", "fp32", 2e-4), ("lm", "fp32", 2e-4),
                                            ("half", "fp16", 3e-2), ("half", "bf16", 2e-1),
+                                           ("wide", "fp16", 3e-2), ("wide", "bf16", 2e-1), ("wide_dh32", "fp16", 3e-2),
                                            ("adaptive", "fp32", 2e-4), ("adaptive_half", "fp16", 3e-2), ("adaptive_half", "bf16", 2e-1)])
 def test_steps_with_reordered_beams_match_the_full_decoder(name, prec, tol):
     import paper_1904_01038_amd as T
