@@ -176,9 +176,9 @@ int tfm_profile_read(tfm_ctx* ctx, tfm_prof_entry out[TFM_PROF_CLASSES], int32_t
 /* ---- measurement aids: what this device sustains, to print beside the published peaks -------------------------------
  * tfm_probe_mfma: a register-only loop of 32x32x16 matrix-core instructions (dtype TFM_FP16 or TFM_BF16) on every
  * compute unit; *tflops receives the rate.  scratch: device memory, at least 2048 bytes per compute unit (256 CUs:
- * 512 KiB), written with throw-away values.  tfm_probe_copy: a plain 16-byte-per-lane copy kernel of `bytes` (a
- * multiple of 16, both pointers 16-byte aligned, no overlap), timed over 10 launches; *gbs receives (bytes read +
- * bytes written) per second.  Both block until the measurement is done. */
+ * 512 KiB), written with throw-away values.  tfm_probe_copy: a copy kernel of `bytes` (a multiple of 16, both pointers
+ * 16-byte aligned, no overlap; at most 2^31 x 4 KiB) in the fastest form found on this device - one 16-byte non-temporal load
+ * and store per thread, no loop - timed over 10 launches; *gbs receives (bytes read + bytes written) per second.  Both block until the measurement is done. */
 int tfm_probe_mfma(int32_t dtype, void* scratch, size_t scratch_bytes, double* tflops, void* stream);
 int tfm_probe_copy(void* dst, const void* src, size_t bytes, double* gbs, void* stream);
 /* tfm_probe_fetch: the rate at which compute units pull data in: one 16-wavefront block per compute unit re-reads its own
